@@ -1,0 +1,150 @@
+"""Thin ctypes binding of libtempo.so: same names as the C ABI, argument marshalling only.
+
+Tensors are torch CUDA tensors (PyTorch supplies device memory and the stream; every step
+of the layers runs in the HIP kernels).  Outputs are written into tensors the caller passes.
+There is no CPU fallback: if the shared library has not been built, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libtempo.so")
+
+TEMPO_OK = 0
+TEMPO_F32, TEMPO_BF16 = 0, 1
+TEMPO_GELU_ERF, TEMPO_GELU_TANH = 0, 1
+_DT = {torch.float32: TEMPO_F32, torch.bfloat16: TEMPO_BF16}
+_KIND = {"erf": TEMPO_GELU_ERF, "tanh": TEMPO_GELU_TANH}
+
+_vp, _i64, _u64 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_uint64
+_int, _f32, _sz = ctypes.c_int, ctypes.c_float, ctypes.c_size_t
+
+_SIGNATURES = {
+    "tempo_status_string": (ctypes.c_char_p, [_int]),
+    "tempo_version": (_int, []),
+    "tempo_set_launch_param": (_int, [_int, _int]),
+    "tempo_get_launch_param": (_int, [_int]),
+    "tempo_gelu_fwd": (_int, [_vp, _vp, _vp, _i64, _int, _int, _vp]),
+    "tempo_gelu_bwd": (_int, [_vp, _vp, _vp, _vp, _i64, _int, _int, _vp]),
+    "tempo_layernorm_fwd": (_int, [_vp, _vp, _vp, _vp, _vp, _vp, _i64, _i64, _f32, _int, _vp]),
+    "tempo_layernorm_bwd_workspace_bytes": (_sz, [_i64, _i64]),
+    "tempo_layernorm_bwd": (_int, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _i64, _i64,
+                                   _int, _vp]),
+    "tempo_attn_softmax_dropout_fwd": (_int, [_vp, _vp, _int, _vp, _vp, _vp, _i64, _i64, _i64,
+                                              _i64, _f32, _u64, _u64, _int, _vp]),
+    "tempo_attn_softmax_dropout_bwd": (_int, [_vp, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _i64,
+                                              _f32, _int, _vp]),
+}
+
+_lib = None
+
+
+class TempoError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (status {status})")
+
+
+def load() -> ctypes.CDLL:
+    """Load libtempo.so (built in-tree by build.py); raises if it is missing."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(
+                f"{LIB_PATH} not found: build it with `python -m paper_2210_10246_amd.build` "
+                "(there is no CPU fallback)")
+        lib = ctypes.CDLL(LIB_PATH)
+        for name, (res, args) in _SIGNATURES.items():
+            fn = getattr(lib, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = lib
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return load().tempo_status_string(status).decode()
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("tensors must be contiguous CUDA tensors")
+    return t.data_ptr()
+
+
+def _stream(stream):
+    s = torch.cuda.current_stream() if stream is None else stream
+    return s.cuda_stream
+
+
+def _check(status: int, where: str):
+    if status != TEMPO_OK:
+        raise TempoError(status, where)
+
+
+def mask_words(n: int) -> int:
+    return (n + 31) // 32
+
+
+def tempo_set_launch_param(key: int, value: int):
+    _check(load().tempo_set_launch_param(key, value), "tempo_set_launch_param")
+
+
+def tempo_get_launch_param(key: int) -> int:
+    return load().tempo_get_launch_param(key)
+
+
+def tempo_gelu_fwd(x, y, mask, kind="erf", stream=None):
+    """(y, mask) = GELU*(x); y may be x."""
+    _check(load().tempo_gelu_fwd(_ptr(x), _ptr(y), _ptr(mask), x.numel(), _DT[x.dtype],
+                                 _KIND[kind], _stream(stream)), "tempo_gelu_fwd")
+
+
+def tempo_gelu_bwd(dy, y, mask, dx, kind="erf", stream=None):
+    """dx = dy * GELU'(GELU*^-1(y, mask)); dx may be dy."""
+    _check(load().tempo_gelu_bwd(_ptr(dy), _ptr(y), _ptr(mask), _ptr(dx), y.numel(), _DT[y.dtype],
+                                 _KIND[kind], _stream(stream)), "tempo_gelu_bwd")
+
+
+def tempo_layernorm_fwd(x, gamma, beta, y, rstd, mean=None, eps=1e-5, stream=None):
+    M = x.shape[-1]
+    N = x.numel() // M if M else 0
+    _check(load().tempo_layernorm_fwd(_ptr(x), _ptr(gamma), _ptr(beta), _ptr(y), _ptr(rstd),
+                                      _ptr(mean), N, M, eps, _DT[x.dtype], _stream(stream)),
+           "tempo_layernorm_fwd")
+
+
+def tempo_layernorm_bwd_workspace_bytes(N: int, M: int) -> int:
+    return load().tempo_layernorm_bwd_workspace_bytes(N, M)
+
+
+def tempo_layernorm_bwd(dy, y, gamma, beta, rstd, dx, dgamma, dbeta, workspace, stream=None):
+    M = y.shape[-1]
+    N = y.numel() // M if M else 0
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(load().tempo_layernorm_bwd(_ptr(dy), _ptr(y), _ptr(gamma), _ptr(beta), _ptr(rstd),
+                                      _ptr(dx), _ptr(dgamma), _ptr(dbeta), _ptr(workspace),
+                                      ws_bytes, N, M, _DT[y.dtype], _stream(stream)),
+           "tempo_layernorm_bwd")
+
+
+def tempo_attn_softmax_dropout_fwd(scores, key_len, causal, probs, out, keep_bits, p, seed, offset,
+                                   stream=None):
+    B, A, Sq, Sk = scores.shape
+    _check(load().tempo_attn_softmax_dropout_fwd(
+        _ptr(scores), _ptr(key_len), int(bool(causal)), _ptr(probs), _ptr(out), _ptr(keep_bits),
+        B, A, Sq, Sk, p, seed, offset, _DT[scores.dtype], _stream(stream)),
+        "tempo_attn_softmax_dropout_fwd")
+
+
+def tempo_attn_softmax_dropout_bwd(dout, probs, keep_bits, dscores, out_recomputed, p, stream=None):
+    B, A, Sq, Sk = probs.shape
+    _check(load().tempo_attn_softmax_dropout_bwd(
+        _ptr(dout), _ptr(probs), _ptr(keep_bits), _ptr(dscores), _ptr(out_recomputed),
+        B, A, Sq, Sk, p, _DT[probs.dtype], _stream(stream)), "tempo_attn_softmax_dropout_bwd")

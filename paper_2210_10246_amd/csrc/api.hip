@@ -1,0 +1,159 @@
+// C ABI of libtempo: argument validation, then one launcher per entry point.
+#include <atomic>
+#include <cmath>
+
+#include "tempo_device.h"
+#include "tempo_host.h"
+
+namespace tempo {
+
+static std::atomic<int> g_tune[kTuneCount] = {
+    {16},   // gelu fwd: workgroups per CU
+    {16},   // gelu bwd
+    {8},    // layernorm fwd
+    {512},  // layernorm bwd: workgroups in total
+    {16},   // attention fwd
+    {16},   // attention bwd
+};
+
+int tune_get(TuneKey k) { return g_tune[k].load(std::memory_order_relaxed); }
+
+int compute_units() {
+  static std::atomic<int> cached{0};
+  int v = cached.load(std::memory_order_relaxed);
+  if (v > 0) return v;
+  int dev = 0;
+  hipDeviceProp_t prop;
+  if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess ||
+      prop.multiProcessorCount <= 0) {
+    (void)hipGetLastError();
+    return 256;
+  }
+  cached.store(prop.multiProcessorCount, std::memory_order_relaxed);
+  return prop.multiProcessorCount;
+}
+
+static bool dtype_ok(tempo_dtype dt) { return dt == TEMPO_F32 || dt == TEMPO_BF16; }
+static bool kind_ok(tempo_gelu_kind k) { return k == TEMPO_GELU_ERF || k == TEMPO_GELU_TANH; }
+static bool prob_ok(float p) { return p >= 0.0f && p < 1.0f; }  // false for NaN
+
+}  // namespace tempo
+
+using namespace tempo;
+
+extern "C" {
+
+const char* tempo_status_string(tempo_status s) {
+  switch (s) {
+    case TEMPO_OK: return "ok";
+    case TEMPO_ERR_INVALID_ARG: return "invalid argument";
+    case TEMPO_ERR_UNSUPPORTED: return "unsupported (pointer not 16-byte aligned)";
+    case TEMPO_ERR_WORKSPACE: return "workspace too small";
+    case TEMPO_ERR_LAUNCH: return "kernel launch failed";
+  }
+  return "unknown status";
+}
+
+int tempo_version(void) { return 100; }
+
+TEMPO_API int tempo_set_launch_param(int key, int value) {
+  if (key < 0 || key >= kTuneCount || value < 1 || value > 65536) return TEMPO_ERR_INVALID_ARG;
+  g_tune[key].store(value, std::memory_order_relaxed);
+  return TEMPO_OK;
+}
+
+TEMPO_API int tempo_get_launch_param(int key) {
+  if (key < 0 || key >= kTuneCount) return -1;
+  return tune_get(static_cast<TuneKey>(key));
+}
+
+tempo_status tempo_gelu_fwd(const void* x, void* y, uint32_t* mask, int64_t n, tempo_dtype dt,
+                            tempo_gelu_kind kind, void* hip_stream) {
+  if (n < 0 || !dtype_ok(dt) || !kind_ok(kind)) return TEMPO_ERR_INVALID_ARG;
+  if (n == 0) return TEMPO_OK;
+  if (!x || !y || !mask) return TEMPO_ERR_INVALID_ARG;
+  if (!aligned16(x) || !aligned16(y) || !aligned16(mask)) return TEMPO_ERR_UNSUPPORTED;
+  return launch_gelu_fwd(x, y, mask, n, dt, kind, static_cast<hipStream_t>(hip_stream));
+}
+
+tempo_status tempo_gelu_bwd(const void* dy, const void* y, const uint32_t* mask, void* dx,
+                            int64_t n, tempo_dtype dt, tempo_gelu_kind kind, void* hip_stream) {
+  if (n < 0 || !dtype_ok(dt) || !kind_ok(kind)) return TEMPO_ERR_INVALID_ARG;
+  if (n == 0) return TEMPO_OK;
+  if (!dy || !y || !mask || !dx) return TEMPO_ERR_INVALID_ARG;
+  if (!aligned16(dy) || !aligned16(y) || !aligned16(mask) || !aligned16(dx))
+    return TEMPO_ERR_UNSUPPORTED;
+  return launch_gelu_bwd(dy, y, mask, dx, n, dt, kind, static_cast<hipStream_t>(hip_stream));
+}
+
+tempo_status tempo_layernorm_fwd(const void* x, const float* gamma, const float* beta, void* y,
+                                 float* rstd, float* mean, int64_t N, int64_t M, float eps,
+                                 tempo_dtype dt, void* hip_stream) {
+  if (N < 0 || M < 0 || !dtype_ok(dt) || !(eps >= 0.0f) || M > INT32_MAX)
+    return TEMPO_ERR_INVALID_ARG;
+  if (N == 0 || M == 0) return TEMPO_OK;
+  if (!x || !gamma || !beta || !y || !rstd) return TEMPO_ERR_INVALID_ARG;
+  if (!aligned16(x) || !aligned16(gamma) || !aligned16(beta) || !aligned16(y) ||
+      !aligned16(rstd) || !aligned16(mean))
+    return TEMPO_ERR_UNSUPPORTED;
+  return launch_layernorm_fwd(x, gamma, beta, y, rstd, mean, N, M, eps, dt,
+                              static_cast<hipStream_t>(hip_stream));
+}
+
+size_t tempo_layernorm_bwd_workspace_bytes(int64_t N, int64_t M) {
+  if (N <= 0 || M <= 0) return 0;
+  return static_cast<size_t>(layernorm_bwd_blocks(N, M)) * 2 * static_cast<size_t>(M) *
+         sizeof(float);
+}
+
+tempo_status tempo_layernorm_bwd(const void* dy, const void* y, const float* gamma,
+                                 const float* beta, const float* rstd, void* dx, float* dgamma,
+                                 float* dbeta, void* workspace, size_t workspace_bytes, int64_t N,
+                                 int64_t M, tempo_dtype dt, void* hip_stream) {
+  if (N < 0 || M < 0 || !dtype_ok(dt) || M > INT32_MAX) return TEMPO_ERR_INVALID_ARG;
+  if (N == 0 || M == 0) return TEMPO_OK;
+  if (!dy || !y || !gamma || !beta || !rstd || !dx || !dgamma || !dbeta || !workspace)
+    return TEMPO_ERR_INVALID_ARG;
+  if (!aligned16(dy) || !aligned16(y) || !aligned16(gamma) || !aligned16(beta) ||
+      !aligned16(rstd) || !aligned16(dx) || !aligned16(dgamma) || !aligned16(dbeta) ||
+      !aligned16(workspace))
+    return TEMPO_ERR_UNSUPPORTED;
+  if (workspace_bytes < tempo_layernorm_bwd_workspace_bytes(N, M)) return TEMPO_ERR_WORKSPACE;
+  return launch_layernorm_bwd(dy, y, gamma, beta, rstd, dx, dgamma, dbeta,
+                              static_cast<float*>(workspace), N, M, dt,
+                              static_cast<hipStream_t>(hip_stream));
+}
+
+tempo_status tempo_attn_softmax_dropout_fwd(const void* scores, const int32_t* key_len, int causal,
+                                            void* probs, void* out, uint32_t* keep_bits, int64_t B,
+                                            int64_t A, int64_t Sq, int64_t Sk, float p,
+                                            uint64_t seed, uint64_t offset, tempo_dtype dt,
+                                            void* hip_stream) {
+  if (B < 0 || A < 0 || Sq < 0 || Sk < 0 || !dtype_ok(dt) || !prob_ok(p) || Sq > INT32_MAX ||
+      Sk > INT32_MAX)
+    return TEMPO_ERR_INVALID_ARG;
+  if (B == 0 || A == 0 || Sq == 0 || Sk == 0) return TEMPO_OK;
+  if (!scores || !probs || !keep_bits) return TEMPO_ERR_INVALID_ARG;
+  if (!aligned16(scores) || !aligned16(probs) || !aligned16(out) || !aligned16(keep_bits))
+    return TEMPO_ERR_UNSUPPORTED;
+  return launch_attn_fwd(scores, key_len, causal, probs, out, keep_bits, B, A, Sq, Sk, p, seed,
+                         offset, dt, static_cast<hipStream_t>(hip_stream));
+}
+
+tempo_status tempo_attn_softmax_dropout_bwd(const void* dout, const void* probs,
+                                            const uint32_t* keep_bits, void* dscores,
+                                            void* out_recomputed, int64_t B, int64_t A, int64_t Sq,
+                                            int64_t Sk, float p, tempo_dtype dt, void* hip_stream) {
+  if (B < 0 || A < 0 || Sq < 0 || Sk < 0 || !dtype_ok(dt) || !prob_ok(p) || Sq > INT32_MAX ||
+      Sk > INT32_MAX)
+    return TEMPO_ERR_INVALID_ARG;
+  if (B == 0 || A == 0 || Sq == 0 || Sk == 0) return TEMPO_OK;
+  if (!dout || !probs || !keep_bits || !dscores) return TEMPO_ERR_INVALID_ARG;
+  if (!aligned16(dout) || !aligned16(probs) || !aligned16(keep_bits) || !aligned16(dscores) ||
+      !aligned16(out_recomputed))
+    return TEMPO_ERR_UNSUPPORTED;
+  return launch_attn_bwd(dout, probs, keep_bits, dscores, out_recomputed, B, A, Sq, Sk, p, dt,
+                         static_cast<hipStream_t>(hip_stream));
+}
+
+}  // extern "C"

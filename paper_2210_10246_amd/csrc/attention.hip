@@ -1,0 +1,445 @@
+// Attention softmax -> dropout sublayer for gfx950 (Sec. 3.3, 3.4; App. E.3, E.4).
+//
+// Forward keeps only P (the softmax output) and a 1-bit keep mask; the dropout output is a
+// transient.  Backward rebuilds the dropout output from (P, mask) by one multiply and derives
+// the score gradient from P alone.  A group of LANES lanes owns one row in registers (CH
+// chunks of 8 elements per lane, chunk c of lane t = c*LANES + t so every access of a group
+// is contiguous).  The keep bits come from Philox4x32-10, one call per chunk, so the mask is a
+// pure function of (seed, offset, element index) and does not depend on the launch shape.
+#include "tempo_device.h"
+#include "tempo_host.h"
+
+namespace tempo {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr float kLog2e = 1.4426950408889634f;
+
+struct RngArgs {
+  uint32_t seed_lo, seed_hi, off_lo, off_hi;
+  uint32_t t16;  // keep iff 16-bit draw < t16; 65536 keeps everything (generator skipped)
+};
+
+// Philox4x32-10 (Salmon, Moraes, Dror, Shaw, SC'11): ten rounds of two 32x32->64 multiplies,
+// the key advanced by the two Weyl constants between rounds.
+__device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                              uint32_t k0, uint32_t k1, uint32_t (&w)[4]) {
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    const uint64_t p0 = static_cast<uint64_t>(0xD2511F53u) * c0;
+    const uint64_t p1 = static_cast<uint64_t>(0xCD9E8D57u) * c2;
+    const uint32_t n0 = static_cast<uint32_t>(p1 >> 32) ^ c1 ^ k0;
+    const uint32_t n2 = static_cast<uint32_t>(p0 >> 32) ^ c3 ^ k1;
+    c1 = static_cast<uint32_t>(p1);
+    c3 = static_cast<uint32_t>(p0);
+    c0 = n0;
+    c2 = n2;
+    k0 += 0x9E3779B9u;
+    k1 += 0xBB67AE85u;
+  }
+  w[0] = c0; w[1] = c1; w[2] = c2; w[3] = c3;
+}
+
+// Keep bits of the 8 elements of group g (bit i = element 8g + i).
+__device__ __forceinline__ uint32_t keep_byte(uint64_t g, const RngArgs& a) {
+  if (a.t16 >= 65536u) return 0xFFu;
+  uint32_t w[4];
+  philox4x32_10(static_cast<uint32_t>(g), static_cast<uint32_t>(g >> 32), a.off_lo, a.off_hi,
+                a.seed_lo, a.seed_hi, w);
+  uint32_t byte = 0;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    byte |= ((w[i] & 0xFFFFu) < a.t16 ? 1u : 0u) << (2 * i);
+    byte |= ((w[i] >> 16) < a.t16 ? 1u : 0u) << (2 * i + 1);
+  }
+  return byte;
+}
+
+__device__ __forceinline__ uint32_t merge_quad_bytes(uint32_t byte, int lane_in_quad) {
+  uint32_t w = byte << (8 * lane_in_quad);
+  w |= __shfl_xor(w, 1, kWave);
+  w |= __shfl_xor(w, 2, kWave);
+  return w;
+}
+
+// Number of leading key columns of row `row` that take part in the softmax.
+__device__ __forceinline__ int row_limit(int64_t row, const int32_t* key_len, int causal,
+                                         int64_t rows_per_batch, int Sq, int Sk) {
+  int limit = Sk;
+  if (key_len) {
+    const int kl = key_len[row / rows_per_batch];
+    limit = min(limit, max(kl, 0));
+  }
+  if (causal) {
+    const int i = static_cast<int>(row % Sq);
+    limit = min(limit, max(i + (Sk - Sq) + 1, 0));
+  }
+  return limit;
+}
+
+// WORDS: Sk % 32 == 0, mask written as whole words (4 lanes merge their bytes); otherwise
+// Sk % 8 == 0 and every lane writes its own byte of the little-endian word.
+template <typename T, int LANES, int CH, bool WORDS>
+__global__ __launch_bounds__(kThreads) void attn_fwd_kernel(
+    const T* scores, const int32_t* __restrict__ key_len, int causal, T* probs,
+    T* __restrict__ out, uint32_t* __restrict__ keep_bits, int64_t rows, int64_t rows_per_batch,
+    int Sq, int Sk, float scale, RngArgs rng) {
+  constexpr int kGroups = kThreads / LANES;
+  const int g = threadIdx.x / LANES;
+  const int t = threadIdx.x % LANES;
+  const int chunks = Sk >> 3;
+  for (int64_t row = static_cast<int64_t>(blockIdx.x) * kGroups + g; row < rows;
+       row += static_cast<int64_t>(gridDim.x) * kGroups) {
+    const int limit = row_limit(row, key_len, causal, rows_per_batch, Sq, Sk);
+    const T* sr = scores + row * Sk;
+    float v[CH][8];
+    float mx = -INFINITY;
+#pragma unroll
+    for (int c = 0; c < CH; ++c) {
+      const int col0 = (c * LANES + t) * 8;
+      if (col0 < limit) {  // also false for padding chunks (col0 >= Sk >= limit)
+        Store<T>::load8(sr + col0, v[c]);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          v[c][i] = (col0 + i < limit) ? v[c][i] : -INFINITY;
+          mx = fmaxf(mx, v[c][i]);
+        }
+      } else {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[c][i] = -INFINITY;
+      }
+    }
+    mx = group_max<LANES>(mx);
+    const float shift = (mx == -INFINITY) ? 0.0f : mx * kLog2e;
+    float sum = 0.0f;
+#pragma unroll
+    for (int c = 0; c < CH; ++c) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const float e = __builtin_amdgcn_exp2f(fmaf(v[c][i], kLog2e, -shift));
+        v[c][i] = e;
+        sum += e;
+      }
+    }
+    sum = group_sum<LANES>(sum);
+    const float rinv = (sum > 0.0f) ? 1.0f / sum : 0.0f;
+    const int64_t row_chunk0 = row * chunks;
+#pragma unroll
+    for (int c = 0; c < CH; ++c) {
+      const int ch = c * LANES + t;
+      uint32_t byte = 0;
+      if (ch < chunks) {
+        byte = keep_byte(static_cast<uint64_t>(row_chunk0 + ch), rng);
+        float p8[8], o8[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          p8[i] = Store<T>::round(v[c][i] * rinv);
+          o8[i] = ((byte >> i) & 1u) ? p8[i] * scale : 0.0f;
+        }
+        Store<T>::store8(probs + row * Sk + ch * 8, p8);
+        if (out) Store<T>::store8(out + row * Sk + ch * 8, o8);
+      }
+      if (WORDS) {
+        const uint32_t word = merge_quad_bytes(byte, t & 3);
+        if ((t & 3) == 0 && ch < chunks) keep_bits[(row_chunk0 + ch) >> 2] = word;
+      } else if (ch < chunks) {
+        uint8_t* kb = reinterpret_cast<uint8_t*>(keep_bits);
+        const int64_t gi = row_chunk0 + ch;
+        kb[gi] = static_cast<uint8_t>(byte);
+        if (gi == rows * chunks - 1) {  // zero the unused bytes of the last word
+          for (int64_t b = gi + 1; (b & 3) != 0; ++b) kb[b] = 0;
+        }
+      }
+    }
+  }
+}
+
+template <typename T, int LANES, int CH, bool WORDS>
+__global__ __launch_bounds__(kThreads) void attn_bwd_kernel(
+    const T* dout, const T* __restrict__ probs, const uint32_t* __restrict__ keep_bits,
+    T* dscores, T* __restrict__ out_re, int64_t rows, int Sk, float scale) {
+  constexpr int kGroups = kThreads / LANES;
+  const int g = threadIdx.x / LANES;
+  const int t = threadIdx.x % LANES;
+  const int chunks = Sk >> 3;
+  for (int64_t row = static_cast<int64_t>(blockIdx.x) * kGroups + g; row < rows;
+       row += static_cast<int64_t>(gridDim.x) * kGroups) {
+    const int64_t row_chunk0 = row * chunks;
+    float dp[CH][8], pr[CH][8];
+    uint32_t bytes[CH];
+    float dot = 0.0f;
+#pragma unroll
+    for (int c = 0; c < CH; ++c) {
+      const int ch = c * LANES + t;
+      if (ch < chunks) {
+        Store<T>::load8(dout + row * Sk + ch * 8, dp[c]);
+        Store<T>::load8(probs + row * Sk + ch * 8, pr[c]);
+        const int64_t gi = row_chunk0 + ch;
+        if (WORDS) bytes[c] = keep_bits[gi >> 2] >> (8 * static_cast<int>(gi & 3));
+        else bytes[c] = reinterpret_cast<const uint8_t*>(keep_bits)[gi];
+      } else {
+        bytes[c] = 0;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) dp[c][i] = pr[c][i] = 0.0f;
+      }
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        dp[c][i] = ((bytes[c] >> i) & 1u) ? dp[c][i] * scale : 0.0f;
+        dot = fmaf(dp[c][i], pr[c][i], dot);
+      }
+    }
+    dot = group_sum<LANES>(dot);
+#pragma unroll
+    for (int c = 0; c < CH; ++c) {
+      const int ch = c * LANES + t;
+      if (ch < chunks) {
+        float ds[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) ds[i] = pr[c][i] * (dp[c][i] - dot);
+        Store<T>::store8(dscores + row * Sk + ch * 8, ds);
+        if (out_re) {
+          float o8[8];
+#pragma unroll
+          for (int i = 0; i < 8; ++i) o8[i] = ((bytes[c] >> i) & 1u) ? pr[c][i] * scale : 0.0f;
+          Store<T>::store8(out_re + row * Sk + ch * 8, o8);
+        }
+      }
+    }
+  }
+}
+
+// ---- any Sk: one wave per row, scalar accesses, the row re-read from cache per pass --------
+
+__device__ __forceinline__ bool keep_bit_of(int64_t e, const RngArgs& a) {
+  return (keep_byte(static_cast<uint64_t>(e) >> 3, a) >> (e & 7)) & 1u;
+}
+
+template <typename T>
+__global__ __launch_bounds__(kThreads) void attn_fwd_generic_kernel(
+    const T* scores, const int32_t* __restrict__ key_len, int causal, T* probs,
+    T* __restrict__ out, int64_t rows, int64_t rows_per_batch, int Sq, int Sk, float scale,
+    RngArgs rng) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = threadIdx.x / kWave;
+  constexpr int kWaves = kThreads / kWave;
+  for (int64_t row = static_cast<int64_t>(blockIdx.x) * kWaves + wave; row < rows;
+       row += static_cast<int64_t>(gridDim.x) * kWaves) {
+    const int limit = row_limit(row, key_len, causal, rows_per_batch, Sq, Sk);
+    const T* sr = scores + row * Sk;
+    float mx = -INFINITY;
+    for (int j = lane; j < limit; j += kWave) mx = fmaxf(mx, Store<T>::load1(sr + j));
+    mx = group_max<kWave>(mx);
+    const float shift = (mx == -INFINITY) ? 0.0f : mx * kLog2e;
+    float sum = 0.0f;
+    for (int j = lane; j < limit; j += kWave)
+      sum += __builtin_amdgcn_exp2f(fmaf(Store<T>::load1(sr + j), kLog2e, -shift));
+    sum = group_sum<kWave>(sum);
+    const float rinv = (sum > 0.0f) ? 1.0f / sum : 0.0f;
+    for (int j = lane; j < Sk; j += kWave) {
+      float p = 0.0f;
+      if (j < limit)
+        p = Store<T>::round(__builtin_amdgcn_exp2f(fmaf(Store<T>::load1(sr + j), kLog2e, -shift)) *
+                            rinv);
+      const int64_t e = row * Sk + j;
+      Store<T>::store1(probs + e, p);
+      if (out) Store<T>::store1(out + e, keep_bit_of(e, rng) ? p * scale : 0.0f);
+    }
+  }
+}
+
+// Mask words for shapes whose rows do not end on chunk boundaries: one thread per word.
+__global__ __launch_bounds__(kThreads) void keep_words_kernel(uint32_t* __restrict__ keep_bits,
+                                                             int64_t n, RngArgs rng) {
+  const int64_t words = (n + 31) >> 5;
+  for (int64_t w = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; w < words;
+       w += static_cast<int64_t>(gridDim.x) * kThreads) {
+    uint32_t word = 0;
+#pragma unroll
+    for (int b = 0; b < 4; ++b) word |= keep_byte(static_cast<uint64_t>(w) * 4 + b, rng) << (8 * b);
+    const int64_t left = n - w * 32;
+    if (left < 32) word &= (1u << left) - 1u;
+    keep_bits[w] = word;
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(kThreads) void attn_bwd_generic_kernel(
+    const T* dout, const T* __restrict__ probs, const uint32_t* __restrict__ keep_bits,
+    T* dscores, T* __restrict__ out_re, int64_t rows, int Sk, float scale) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = threadIdx.x / kWave;
+  constexpr int kWaves = kThreads / kWave;
+  for (int64_t row = static_cast<int64_t>(blockIdx.x) * kWaves + wave; row < rows;
+       row += static_cast<int64_t>(gridDim.x) * kWaves) {
+    float dot = 0.0f;
+    for (int j = lane; j < Sk; j += kWave) {
+      const int64_t e = row * Sk + j;
+      const bool k = (keep_bits[e >> 5] >> (e & 31)) & 1u;
+      const float dp = k ? Store<T>::load1(dout + e) * scale : 0.0f;
+      dot = fmaf(dp, Store<T>::load1(probs + e), dot);
+    }
+    dot = group_sum<kWave>(dot);
+    for (int j = lane; j < Sk; j += kWave) {
+      const int64_t e = row * Sk + j;
+      const bool k = (keep_bits[e >> 5] >> (e & 31)) & 1u;
+      const float p = Store<T>::load1(probs + e);
+      const float dp = k ? Store<T>::load1(dout + e) * scale : 0.0f;
+      Store<T>::store1(dscores + e, p * (dp - dot));
+      if (out_re) Store<T>::store1(out_re + e, k ? p * scale : 0.0f);
+    }
+  }
+}
+
+struct Shape {
+  int lanes;
+  int ch;
+};
+
+// Aim at 4 chunks per lane (enough bytes in flight per lane, few butterfly steps): the
+// narrowest power-of-two group of at least 4 lanes that covers the row with <= 4 chunks per
+// lane, else 64 lanes with 6 or 8.  ch == 0: row too long for registers.
+Shape pick_shape(int chunks) {
+  int lanes = 4;
+  while (lanes < 64 && lanes * 4 < chunks) lanes <<= 1;
+  const int need = (chunks + lanes - 1) / lanes;
+  static const int allowed[] = {1, 2, 3, 4, 6, 8};
+  for (int a : allowed)
+    if (a >= need) return {lanes, (lanes == 4 || a >= 3) ? a : 3};
+  return {0, 0};
+}
+
+int row_grid(int64_t rows, int lanes, int blocks_per_cu) {
+  const int groups = kThreads / lanes;
+  const int64_t want = (rows + groups - 1) / groups;
+  const int64_t cap = static_cast<int64_t>(compute_units()) * blocks_per_cu;
+  const int64_t b = want < cap ? want : cap;
+  return static_cast<int>(b < 1 ? 1 : b);
+}
+
+}  // namespace
+
+#define TEMPO_ATTN_DISPATCH(LAUNCH)                                                        \
+  switch (sh.lanes * 100 + sh.ch) {                                                        \
+    case 401: LAUNCH(4, 1); break;                                                         \
+    case 402: LAUNCH(4, 2); break;                                                         \
+    case 403: LAUNCH(4, 3); break;                                                         \
+    case 404: LAUNCH(4, 4); break;                                                         \
+    case 803: LAUNCH(8, 3); break;                                                         \
+    case 804: LAUNCH(8, 4); break;                                                         \
+    case 1603: LAUNCH(16, 3); break;                                                       \
+    case 1604: LAUNCH(16, 4); break;                                                       \
+    case 3203: LAUNCH(32, 3); break;                                                       \
+    case 3204: LAUNCH(32, 4); break;                                                       \
+    case 6403: LAUNCH(64, 3); break;                                                       \
+    case 6404: LAUNCH(64, 4); break;                                                       \
+    case 6406: LAUNCH(64, 6); break;                                                       \
+    case 6408: LAUNCH(64, 8); break;                                                       \
+    default: return TEMPO_ERR_UNSUPPORTED;                                                 \
+  }
+
+tempo_status launch_attn_fwd(const void* scores, const int32_t* key_len, int causal, void* probs,
+                             void* out, uint32_t* keep_bits, int64_t B, int64_t A, int64_t Sq,
+                             int64_t Sk, float p, uint64_t seed, uint64_t offset, tempo_dtype dt,
+                             hipStream_t st) {
+  const int64_t rows = B * A * Sq;
+  const int64_t rows_per_batch = A * Sq;
+  const float scale = 1.0f / (1.0f - p);
+  RngArgs rng;
+  rng.seed_lo = static_cast<uint32_t>(seed);
+  rng.seed_hi = static_cast<uint32_t>(seed >> 32);
+  rng.off_lo = static_cast<uint32_t>(offset);
+  rng.off_hi = static_cast<uint32_t>(offset >> 32);
+  double t = (1.0 - static_cast<double>(p)) * 65536.0 + 0.5;
+  t = t < 0.0 ? 0.0 : (t > 65536.0 ? 65536.0 : t);
+  rng.t16 = (p == 0.0f) ? 65536u : static_cast<uint32_t>(t);  // floor for t >= 0
+  const int bpc = tune_get(kTuneAttnFwdBlocksPerCu);
+  Shape sh = pick_shape(static_cast<int>(Sk / 8));
+  if (Sk % 8 == 0 && sh.ch != 0) {
+    const int grid = row_grid(rows, sh.lanes, bpc);
+    const bool words = (Sk % 32 == 0);
+#define TEMPO_LAUNCH_T(T, L, C, W)                                                           \
+  hipLaunchKernelGGL((attn_fwd_kernel<T, L, C, W>), dim3(grid), dim3(kThreads), 0, st,       \
+                     static_cast<const T*>(scores), key_len, causal, static_cast<T*>(probs), \
+                     static_cast<T*>(out), keep_bits, rows, rows_per_batch,                  \
+                     static_cast<int>(Sq), static_cast<int>(Sk), scale, rng)
+#define TEMPO_LAUNCH(L, C)                                                                   \
+  do {                                                                                       \
+    if (dt == TEMPO_F32) {                                                                   \
+      if (words) TEMPO_LAUNCH_T(float, L, C, true);                                          \
+      else TEMPO_LAUNCH_T(float, L, C, false);                                               \
+    } else {                                                                                 \
+      if (words) TEMPO_LAUNCH_T(bf16_t, L, C, true);                                         \
+      else TEMPO_LAUNCH_T(bf16_t, L, C, false);                                              \
+    }                                                                                        \
+  } while (0)
+    TEMPO_ATTN_DISPATCH(TEMPO_LAUNCH)
+#undef TEMPO_LAUNCH
+#undef TEMPO_LAUNCH_T
+    return launch_status();
+  }
+  const int grid = row_grid(rows, kWave, bpc);
+  if (dt == TEMPO_F32)
+    hipLaunchKernelGGL((attn_fwd_generic_kernel<float>), dim3(grid), dim3(kThreads), 0, st,
+                       static_cast<const float*>(scores), key_len, causal,
+                       static_cast<float*>(probs), static_cast<float*>(out), rows, rows_per_batch,
+                       static_cast<int>(Sq), static_cast<int>(Sk), scale, rng);
+  else
+    hipLaunchKernelGGL((attn_fwd_generic_kernel<bf16_t>), dim3(grid), dim3(kThreads), 0, st,
+                       static_cast<const bf16_t*>(scores), key_len, causal,
+                       static_cast<bf16_t*>(probs), static_cast<bf16_t*>(out), rows,
+                       rows_per_batch, static_cast<int>(Sq), static_cast<int>(Sk), scale, rng);
+  if (hipGetLastError() != hipSuccess) return TEMPO_ERR_LAUNCH;
+  const int64_t n = rows * Sk;
+  const int64_t words = (n + 31) / 32;
+  const int64_t wgrid = (words + kThreads - 1) / kThreads;
+  const int64_t cap = static_cast<int64_t>(compute_units()) * 8;
+  hipLaunchKernelGGL(keep_words_kernel, dim3(static_cast<int>(wgrid < cap ? wgrid : cap)),
+                     dim3(kThreads), 0, st, keep_bits, n, rng);
+  return launch_status();
+}
+
+tempo_status launch_attn_bwd(const void* dout, const void* probs, const uint32_t* keep_bits,
+                             void* dscores, void* out_re, int64_t B, int64_t A, int64_t Sq,
+                             int64_t Sk, float p, tempo_dtype dt, hipStream_t st) {
+  const int64_t rows = B * A * Sq;
+  const float scale = 1.0f / (1.0f - p);
+  const int bpc = tune_get(kTuneAttnBwdBlocksPerCu);
+  Shape sh = pick_shape(static_cast<int>(Sk / 8));
+  if (Sk % 8 == 0 && sh.ch != 0) {
+    const int grid = row_grid(rows, sh.lanes, bpc);
+    const bool words = (Sk % 32 == 0);
+#define TEMPO_LAUNCH_T(T, L, C, W)                                                           \
+  hipLaunchKernelGGL((attn_bwd_kernel<T, L, C, W>), dim3(grid), dim3(kThreads), 0, st,       \
+                     static_cast<const T*>(dout), static_cast<const T*>(probs), keep_bits,   \
+                     static_cast<T*>(dscores), static_cast<T*>(out_re), rows,                \
+                     static_cast<int>(Sk), scale)
+#define TEMPO_LAUNCH(L, C)                                                                   \
+  do {                                                                                       \
+    if (dt == TEMPO_F32) {                                                                   \
+      if (words) TEMPO_LAUNCH_T(float, L, C, true);                                          \
+      else TEMPO_LAUNCH_T(float, L, C, false);                                               \
+    } else {                                                                                 \
+      if (words) TEMPO_LAUNCH_T(bf16_t, L, C, true);                                         \
+      else TEMPO_LAUNCH_T(bf16_t, L, C, false);                                              \
+    }                                                                                        \
+  } while (0)
+    TEMPO_ATTN_DISPATCH(TEMPO_LAUNCH)
+#undef TEMPO_LAUNCH
+#undef TEMPO_LAUNCH_T
+    return launch_status();
+  }
+  const int grid = row_grid(rows, kWave, bpc);
+  if (dt == TEMPO_F32)
+    hipLaunchKernelGGL((attn_bwd_generic_kernel<float>), dim3(grid), dim3(kThreads), 0, st,
+                       static_cast<const float*>(dout), static_cast<const float*>(probs),
+                       keep_bits, static_cast<float*>(dscores), static_cast<float*>(out_re), rows,
+                       static_cast<int>(Sk), scale);
+  else
+    hipLaunchKernelGGL((attn_bwd_generic_kernel<bf16_t>), dim3(grid), dim3(kThreads), 0, st,
+                       static_cast<const bf16_t*>(dout), static_cast<const bf16_t*>(probs),
+                       keep_bits, static_cast<bf16_t*>(dscores), static_cast<bf16_t*>(out_re),
+                       rows, static_cast<int>(Sk), scale);
+  return launch_status();
+}
+
+}  // namespace tempo

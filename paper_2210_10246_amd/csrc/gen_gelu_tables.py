@@ -1,0 +1,224 @@
+#!/usr/bin/env python3
+"""Writes gelu_tables.inc: piecewise-cubic tables for the GELU kernels.
+
+    python paper_2210_10246_amd/csrc/gen_gelu_tables.py
+
+Backward composite d(y, m) = GELU'(GELU*^-1(y, m))  (App. E.1 eq. 2).  The paper fits
+piecewise polynomials of degree up to 13 in y (App. F.1) without printing them; a
+polynomial in y cannot follow the square-root behaviour of d at the minimum, so the
+pieces here are cubics in variables in which d is smooth:
+
+  right branch (m=1)            s = sqrt(y - y*),  uniform pieces of width 1/CR in s
+  left branch, y <= -2^-4       s = sqrt(y - y*),  uniform pieces of width 1/CL in s
+  left branch, -2^-4 < y < 0    quarter-octaves of -y: piece = exponent and two mantissa
+                                bits of -y, local variable = the remaining 21 mantissa bits
+
+Every piece stores (c0, c1, c2, c3) with d = ((c3 z + c2) z + c1) z + c0; z in [0,1) for
+the s-pieces, z = the integer value of the low 21 mantissa bits for the tail pieces
+(coefficients pre-scaled).  The last tail piece is all zero: below 2^-28 |d| < 4e-8.
+
+No inversion is needed to fit: sample x densely, compute y = GELU(x) and d = GELU'(x)
+exactly in float64, derive the piece and local variable from y, least-squares fit in the
+Chebyshev basis per piece.  The script prints the worst absolute error of each region.
+
+Forward (erf kind) table: GELU(x) itself as cubics on uniform pieces of width 1/16 in
+x over [-8, 8); outside, GELU(x) = x (right) or -0 (left) to below 1e-14.
+
+This file shares nothing with the CPU checker: its GELU, derivative and minimum search
+are written here with the math/scipy primitives only.
+"""
+import math
+import os
+import struct
+
+import numpy as np
+from numpy.polynomial import chebyshev as cheb
+from numpy.polynomial import polynomial as poly
+from scipy.special import erfc
+
+CR = 32          # right-branch pieces per unit s
+NR = 82          # right-branch pieces: s in [0, 82/32 = 2.5625)  (y up to 6.39)
+CL = 64          # left-branch pieces per unit s
+NL = 21          # left-near pieces: s in [0, 21/64), covers y in [y*, -2^-4]
+TAIL_TOP_EXP = -4          # tail is -y < 2^-4
+TAIL_OCTAVES = 24          # 2^-5 .. 2^-28
+TAIL_SUB_BITS = 2          # quarter octaves
+NT = TAIL_OCTAVES * (1 << TAIL_SUB_BITS) + 1   # + the all-zero piece
+FWD_PER_UNIT = 16
+FWD_LO, FWD_HI = -8.0, 8.0
+NF = int((FWD_HI - FWD_LO) * FWD_PER_UNIT)
+
+A_TANH = 0.044715
+K_TANH = math.sqrt(2.0 / math.pi)
+
+
+def g_val(x, kind):
+    if kind == "erf":
+        return x * 0.5 * erfc(-x / math.sqrt(2.0))
+    u = K_TANH * (x + A_TANH * x**3)
+    with np.errstate(over="ignore"):
+        return x / (1.0 + np.exp(-2.0 * u))
+
+
+def g_der(x, kind):
+    if kind == "erf":
+        return 0.5 * erfc(-x / math.sqrt(2.0)) + x * np.exp(-0.5 * x * x) / math.sqrt(2.0 * math.pi)
+    u = K_TANH * (x + A_TANH * x**3)
+    with np.errstate(over="ignore"):
+        sg = 1.0 / (1.0 + np.exp(-2.0 * u))
+    return sg + x * sg * (1.0 - sg) * 2.0 * K_TANH * (1.0 + 3.0 * A_TANH * x * x)
+
+
+def minimum(kind):
+    lo, hi = -1.0, -0.5
+    for _ in range(200):
+        mid = 0.5 * (lo + hi)
+        if g_der(np.float64(mid), kind) < 0:
+            lo = mid
+        else:
+            hi = mid
+    xs = 0.5 * (lo + hi)
+    return xs, float(g_val(np.float64(xs), kind))
+
+
+def fit_piece(z, d, deg=3):
+    """Least-squares cubic in z in [0,1] (Chebyshev basis on [0,1], Chebyshev weight),
+    returned as monomial coefficients c0..c3 in z, plus the worst abs error on the samples."""
+    t = 2.0 * z - 1.0
+    w = 1.0 / np.power(np.maximum(1.0 - t * t, 1e-4), 0.25)
+    c = cheb.chebfit(t, d, deg, w=w)
+    err = float(np.abs(cheb.chebval(t, c) - d).max())
+    p_t = cheb.cheb2poly(c)                       # polynomial in t
+    # substitute t = 2z - 1
+    p_z = np.zeros(deg + 1)
+    base = np.array([1.0])
+    for k, a in enumerate(p_t):
+        p_z[: len(base)] += a * base
+        base = poly.polymul(base, np.array([-1.0, 2.0]))
+    return p_z, err
+
+
+def bwd_table(kind):
+    xs, ys = minimum(kind)
+    rows = np.zeros((NR + NL + NT, 4))
+    errs = {}
+    # ---- right branch: x from x* upward, dense in s
+    n = 4_000_001
+    x = xs + np.linspace(0.0, 1.0, n) ** 2 * (9.0 - xs)
+    y, d = g_val(x, kind), g_der(x, kind)
+    s = np.sqrt(np.maximum(y - ys, 0.0))
+    u = s * CR
+    worst = 0.0
+    for i in range(NR):
+        sel = (u >= i) & (u <= i + 1)
+        rows[i], e = fit_piece(u[sel] - i, d[sel])
+        worst = max(worst, e)
+    errs["right"] = worst
+    # ---- left branch: x from x* downward
+    x = xs - np.linspace(0.0, 1.0, n) ** 2 * 14.5
+    y, d = g_val(x, kind), g_der(x, kind)
+    s = np.sqrt(np.maximum(y - ys, 0.0))
+    u = s * CL
+    worst = 0.0
+    for i in range(NL):
+        # samples run a little past the hand-over point y = -2^-4
+        sel = (u >= i) & (u <= i + 1) & (y <= -(2.0 ** TAIL_TOP_EXP) * 0.98)
+        if sel.sum() < 8:
+            raise RuntimeError("left-near piece without samples")
+        rows[NR + i], e = fit_piece(u[sel] - i, d[sel])
+        worst = max(worst, e)
+    errs["left_near"] = worst
+    ny = -y
+    sub = 1 << TAIL_SUB_BITS
+    zmax = float(1 << (23 - TAIL_SUB_BITS))
+    worst = 0.0
+    for o in range(TAIL_OCTAVES):
+        ex = TAIL_TOP_EXP - 1 - o                       # octave [2^ex, 2^(ex+1))
+        for j in range(sub):
+            a = 2.0**ex * (1.0 + j / sub)
+            b = 2.0**ex * (1.0 + (j + 1) / sub)
+            sel = (ny >= a) & (ny <= b)
+            if sel.sum() < 8:
+                raise RuntimeError("tail piece without samples")
+            c, e = fit_piece((ny[sel] - a) / (b - a), d[sel])
+            # piece index counts DOWN in magnitude: first piece is the top quarter-octave
+            k = o * sub + (sub - 1 - j)
+            rows[NR + NL + k] = c / zmax ** np.arange(4)     # local variable = integer mantissa
+            worst = max(worst, e)
+    errs["left_tail"] = worst
+    errs["below_tail"] = float(np.abs(d[ny < 2.0 ** (TAIL_TOP_EXP - TAIL_OCTAVES)]).max())
+    return xs, ys, rows, errs
+
+
+def fwd_table():
+    rows = np.zeros((NF, 4))
+    worst = 0.0
+    for i in range(NF):
+        a = FWD_LO + i / FWD_PER_UNIT
+        z = 0.5 - 0.5 * np.cos(np.linspace(0, math.pi, 400))
+        x = a + z / FWD_PER_UNIT
+        rows[i], e = fit_piece(z, g_val(x, "erf"))
+        worst = max(worst, e)
+    return rows, worst
+
+
+def f32_hex(v):
+    return "0x%08Xu" % struct.unpack("<I", struct.pack("<f", float(np.float32(v))))[0]
+
+
+def emit_rows(name, rows):
+    out = [f"static TEMPO_TABLE_QUAL const uint32_t {name}[{rows.shape[0]}][4] = {{"]
+    for r in rows:
+        out.append("  {" + ", ".join(f32_hex(v) for v in r) + "},")
+    out.append("};")
+    return out
+
+
+def main():
+    lines = [
+        "// Generated by gen_gelu_tables.py -- do not edit.  IEEE binary32 bit patterns.",
+        "#pragma once",
+        "#include <stdint.h>",
+        "#ifndef TEMPO_TABLE_QUAL",
+        "#define TEMPO_TABLE_QUAL",
+        "#endif",
+        f"#define TEMPO_GELU_CR {CR}",
+        f"#define TEMPO_GELU_NR {NR}",
+        f"#define TEMPO_GELU_CL {CL}",
+        f"#define TEMPO_GELU_NL {NL}",
+        f"#define TEMPO_GELU_NT {NT}",
+        f"#define TEMPO_GELU_TAIL_SUB_BITS {TAIL_SUB_BITS}",
+        f"#define TEMPO_GELU_TAIL_TOP_EXP ({TAIL_TOP_EXP})",
+        f"#define TEMPO_GELU_BWD_ROWS {NR + NL + NT}",
+        f"#define TEMPO_GELU_FWD_ROWS {NF}",
+        f"#define TEMPO_GELU_FWD_PER_UNIT {FWD_PER_UNIT}",
+        f"#define TEMPO_GELU_FWD_LO ({FWD_LO}f)",
+        f"#define TEMPO_GELU_FWD_HI ({FWD_HI}f)",
+    ]
+    report = []
+    for kind in ("erf", "tanh"):
+        xs, ys, rows, errs = bwd_table(kind)
+        ys_hi = float(np.float32(ys))
+        ys_lo = float(np.float32(ys - ys_hi))
+        K = kind.upper()
+        lines += [
+            f"// {kind}: x* = {xs!r}, y* = {ys!r}",
+            f"#define TEMPO_GELU_{K}_XSTAR_F32 {f32_hex(xs)}",
+            f"#define TEMPO_GELU_{K}_YSTAR_HI {f32_hex(ys_hi)}",
+            f"#define TEMPO_GELU_{K}_YSTAR_LO {f32_hex(ys_lo)}",
+        ]
+        lines += emit_rows(f"tempo_gelu_bwd_table_{kind}", rows)
+        report.append(f"{kind}: " + ", ".join(f"{k} {v:.2e}" for k, v in errs.items()))
+    rows, worst = fwd_table()
+    lines += emit_rows("tempo_gelu_fwd_table_erf", rows)
+    report.append(f"fwd erf table: {worst:.2e}")
+    lines.insert(1, "// worst abs fit error (float64 coefficients): " + "; ".join(report))
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "gelu_tables.inc")
+    with open(path, "w") as f:
+        f.write("\n".join(lines) + "\n")
+    print("\n".join(report))
+    print("wrote", path)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,488 @@
+// In-place LayerNorm for gfx950 (Sec. 3.2; App. D.2, D.3).
+//
+// Forward: a group of LANES lanes owns one row, held entirely in registers (CH chunks of 8
+// elements per lane), so x is read once; mean and the biased variance are taken in two
+// register passes; gamma/beta stay in registers across the rows a group walks.
+// Backward: same ownership; xhat is rebuilt from the OUTPUT as (y - beta)/gamma, the two row
+// sums are butterfly-reduced, and the column sums for dgamma/dbeta are carried in registers
+// across rows, tree-reduced over the workgroup through LDS in a fixed order and written as
+// one partial per workgroup; a second small kernel adds the partials in a fixed order.
+#include "tempo_device.h"
+#include "tempo_host.h"
+
+namespace tempo {
+namespace {
+
+constexpr int kFwdThreads = 256;
+constexpr int kBwdWaves = 8;
+constexpr int kBwdThreads = kBwdWaves * kWave;
+constexpr int kMaxFastM = 4096;      // forward: 64 lanes x 8 chunks x 8 elements
+constexpr int kMaxFastBwdM = 2048;   // backward: the LDS tree needs 16 M bytes (64 KiB limit)
+
+__device__ __forceinline__ void load_param8(const float* p, float (&v)[8]) {
+  Store<float>::load8(p, v);
+}
+
+template <typename T, int LANES, int CH>
+__global__ __launch_bounds__(kFwdThreads) void ln_fwd_kernel(
+    const T* x, const float* __restrict__ gamma, const float* __restrict__ beta, T* y,
+    float* __restrict__ rstd_out, float* __restrict__ mean_out, int64_t N, int M, float eps) {
+  constexpr int kGroups = kFwdThreads / LANES;
+  const int g = threadIdx.x / LANES;
+  const int t = threadIdx.x % LANES;
+  const int chunks = M >> 3;
+  const float inv_m = 1.0f / static_cast<float>(M);
+  float ga[CH][8], be[CH][8];
+#pragma unroll
+  for (int c = 0; c < CH; ++c) {
+    const int ch = c * LANES + t;
+    if (ch < chunks) {
+      load_param8(gamma + ch * 8, ga[c]);
+      load_param8(beta + ch * 8, be[c]);
+    } else {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) ga[c][i] = be[c][i] = 0.0f;
+    }
+  }
+  for (int64_t row = static_cast<int64_t>(blockIdx.x) * kGroups + g; row < N;
+       row += static_cast<int64_t>(gridDim.x) * kGroups) {
+    const T* xr = x + row * M;
+    T* yr = y + row * M;
+    float v[CH][8];
+    float sum = 0.0f;
+#pragma unroll
+    for (int c = 0; c < CH; ++c) {
+      const int ch = c * LANES + t;
+      if (ch < chunks) {
+        Store<T>::load8(xr + ch * 8, v[c]);
+      } else {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[c][i] = 0.0f;
+      }
+#pragma unroll
+      for (int i = 0; i < 8; ++i) sum += v[c][i];
+    }
+    const float mu = group_sum<LANES>(sum) * inv_m;
+    float sq = 0.0f;
+#pragma unroll
+    for (int c = 0; c < CH; ++c) {
+      const int ch = c * LANES + t;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const float d = v[c][i] - mu;
+        v[c][i] = d;
+        sq += (ch < chunks) ? d * d : 0.0f;
+      }
+    }
+    const float var = group_sum<LANES>(sq) * inv_m;
+    const float rs = 1.0f / sqrtf(var + eps);
+#pragma unroll
+    for (int c = 0; c < CH; ++c) {
+      const int ch = c * LANES + t;
+      if (ch < chunks) {
+        float o[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) o[i] = fmaf(v[c][i] * rs, ga[c][i], be[c][i]);
+        Store<T>::store8(yr + ch * 8, o);
+      }
+    }
+    if (t == 0) {
+      rstd_out[row] = rs;
+      if (mean_out) mean_out[row] = mu;
+    }
+  }
+}
+
+// Sum over a 256-thread workgroup; every thread gets the result.
+__device__ __forceinline__ float block_sum_256(float v, float* lds) {
+  v = group_sum<kWave>(v);
+  const int w = threadIdx.x / kWave;
+  __syncthreads();
+  if ((threadIdx.x & (kWave - 1)) == 0) lds[w] = v;
+  __syncthreads();
+  return (lds[0] + lds[1]) + (lds[2] + lds[3]);
+}
+
+// Any M: one workgroup per row, scalar accesses, x re-read from cache for each pass.
+template <typename T>
+__global__ __launch_bounds__(256) void ln_fwd_generic_kernel(
+    const T* x, const float* __restrict__ gamma, const float* __restrict__ beta, T* y,
+    float* __restrict__ rstd_out, float* __restrict__ mean_out, int64_t N, int64_t M, float eps) {
+  __shared__ float lds[4];
+  const float inv_m = 1.0f / static_cast<float>(M);
+  for (int64_t row = blockIdx.x; row < N; row += gridDim.x) {
+    const T* xr = x + row * M;
+    T* yr = y + row * M;
+    float s = 0.0f;
+    for (int64_t j = threadIdx.x; j < M; j += 256) s += Store<T>::load1(xr + j);
+    const float mu = block_sum_256(s, lds) * inv_m;
+    float q = 0.0f;
+    for (int64_t j = threadIdx.x; j < M; j += 256) {
+      const float d = Store<T>::load1(xr + j) - mu;
+      q += d * d;
+    }
+    const float var = block_sum_256(q, lds) * inv_m;
+    const float rs = 1.0f / sqrtf(var + eps);
+    for (int64_t j = threadIdx.x; j < M; j += 256) {
+      const float d = Store<T>::load1(xr + j) - mu;
+      Store<T>::store1(yr + j, fmaf(d * rs, gamma[j], beta[j]));
+    }
+    if (threadIdx.x == 0) {
+      rstd_out[row] = rs;
+      if (mean_out) mean_out[row] = mu;
+    }
+  }
+}
+
+template <typename T, int LANES, int CH>
+__global__ __launch_bounds__(kBwdThreads) void ln_bwd_kernel(
+    const T* dy, const T* __restrict__ y, const float* __restrict__ gamma,
+    const float* __restrict__ beta, const float* __restrict__ rstd, T* dx,
+    float* __restrict__ partial, int64_t N, int M) {
+  extern __shared__ float lds[];  // [kBwdWaves/2][2][M]
+  constexpr int kGroups = kBwdThreads / LANES;
+  const int g = threadIdx.x / LANES;
+  const int t = threadIdx.x % LANES;
+  const int wave = threadIdx.x / kWave;
+  const int lane = threadIdx.x & (kWave - 1);
+  const int chunks = M >> 3;
+  const float inv_m = 1.0f / static_cast<float>(M);
+  float ga[CH][8], be[CH][8], acc_g[CH][8], acc_b[CH][8];
+#pragma unroll
+  for (int c = 0; c < CH; ++c) {
+    const int ch = c * LANES + t;
+    if (ch < chunks) {
+      load_param8(gamma + ch * 8, ga[c]);
+      load_param8(beta + ch * 8, be[c]);
+    } else {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        ga[c][i] = 1.0f;
+        be[c][i] = 0.0f;
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc_g[c][i] = acc_b[c][i] = 0.0f;
+  }
+  for (int64_t row = static_cast<int64_t>(blockIdx.x) * kGroups + g; row < N;
+       row += static_cast<int64_t>(gridDim.x) * kGroups) {
+    const T* dyr = dy + row * M;
+    const T* yr = y + row * M;
+    T* dxr = dx + row * M;
+    float gg[CH][8], xh[CH][8];
+    float c1 = 0.0f, c2 = 0.0f;
+#pragma unroll
+    for (int c = 0; c < CH; ++c) {
+      const int ch = c * LANES + t;
+      float d8[8], y8[8];
+      if (ch < chunks) {
+        Store<T>::load8(dyr + ch * 8, d8);
+        Store<T>::load8(yr + ch * 8, y8);
+      } else {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          d8[i] = 0.0f;
+          y8[i] = 0.0f;
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const float h = (y8[i] - be[c][i]) * __builtin_amdgcn_rcpf(ga[c][i]);
+        const float q = d8[i] * ga[c][i];
+        xh[c][i] = h;
+        gg[c][i] = q;
+        c1 = fmaf(q, h, c1);
+        c2 += q;
+        acc_g[c][i] = fmaf(d8[i], h, acc_g[c][i]);
+        acc_b[c][i] += d8[i];
+      }
+    }
+    c1 = group_sum<LANES>(c1) * inv_m;
+    c2 = group_sum<LANES>(c2) * inv_m;
+    const float rs = rstd[row];
+#pragma unroll
+    for (int c = 0; c < CH; ++c) {
+      const int ch = c * LANES + t;
+      if (ch < chunks) {
+        float o[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) o[i] = rs * (gg[c][i] - fmaf(xh[c][i], c1, c2));
+        Store<T>::store8(dxr + ch * 8, o);
+      }
+    }
+  }
+  // Column sums: first over the groups that share a wave (fixed butterfly), then a binary tree
+  // over the waves through LDS.
+#pragma unroll
+  for (int c = 0; c < CH; ++c) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+#pragma unroll
+      for (int m = LANES; m < kWave; m <<= 1) {
+        acc_g[c][i] += __shfl_xor(acc_g[c][i], m, kWave);
+        acc_b[c][i] += __shfl_xor(acc_b[c][i], m, kWave);
+      }
+    }
+  }
+  const bool owner = lane < LANES;  // one copy per wave
+#pragma unroll
+  for (int half = kBwdWaves / 2; half >= 1; half >>= 1) {
+    __syncthreads();
+    if (wave >= half && wave < 2 * half && owner) {
+      float* slot = lds + static_cast<size_t>(wave - half) * 2 * M;
+#pragma unroll
+      for (int c = 0; c < CH; ++c) {
+        const int ch = c * LANES + t;
+        if (ch < chunks) {
+          Store<float>::store8(slot + ch * 8, acc_g[c]);
+          Store<float>::store8(slot + M + ch * 8, acc_b[c]);
+        }
+      }
+    }
+    __syncthreads();
+    if (wave < half && owner) {
+      const float* slot = lds + static_cast<size_t>(wave) * 2 * M;
+#pragma unroll
+      for (int c = 0; c < CH; ++c) {
+        const int ch = c * LANES + t;
+        if (ch < chunks) {
+          float a[8], b[8];
+          Store<float>::load8(slot + ch * 8, a);
+          Store<float>::load8(slot + M + ch * 8, b);
+#pragma unroll
+          for (int i = 0; i < 8; ++i) {
+            acc_g[c][i] += a[i];
+            acc_b[c][i] += b[i];
+          }
+        }
+      }
+    }
+  }
+  if (wave == 0 && owner) {
+    float* slot = partial + static_cast<size_t>(blockIdx.x) * 2 * M;
+#pragma unroll
+    for (int c = 0; c < CH; ++c) {
+      const int ch = c * LANES + t;
+      if (ch < chunks) {
+        Store<float>::store8(slot + ch * 8, acc_g[c]);
+        Store<float>::store8(slot + M + ch * 8, acc_b[c]);
+      }
+    }
+  }
+}
+
+// Any M: one workgroup per row for dx; per-workgroup column partials are accumulated by
+// walking rows blockIdx.x, blockIdx.x + gridDim.x, ... with thread j owning columns j, j+256...
+// directly in the partial slot (private to the workgroup).
+template <typename T>
+__global__ __launch_bounds__(256) void ln_bwd_generic_kernel(
+    const T* dy, const T* __restrict__ y, const float* __restrict__ gamma,
+    const float* __restrict__ beta, const float* __restrict__ rstd, T* dx,
+    float* __restrict__ partial, int64_t N, int64_t M) {
+  __shared__ float lds[4];
+  const float inv_m = 1.0f / static_cast<float>(M);
+  float* pg = partial + static_cast<size_t>(blockIdx.x) * 2 * M;
+  float* pb = pg + M;
+  for (int64_t j = threadIdx.x; j < M; j += 256) {
+    pg[j] = 0.0f;
+    pb[j] = 0.0f;
+  }
+  for (int64_t row = blockIdx.x; row < N; row += gridDim.x) {
+    const T* dyr = dy + row * M;
+    const T* yr = y + row * M;
+    T* dxr = dx + row * M;
+    float c1 = 0.0f, c2 = 0.0f;
+    for (int64_t j = threadIdx.x; j < M; j += 256) {
+      const float d = Store<T>::load1(dyr + j);
+      const float h = (Store<T>::load1(yr + j) - beta[j]) / gamma[j];
+      const float q = d * gamma[j];
+      c1 = fmaf(q, h, c1);
+      c2 += q;
+      pg[j] = fmaf(d, h, pg[j]);
+      pb[j] += d;
+    }
+    c1 = block_sum_256(c1, lds) * inv_m;
+    c2 = block_sum_256(c2, lds) * inv_m;
+    const float rs = rstd[row];
+    for (int64_t j = threadIdx.x; j < M; j += 256) {
+      const float d = Store<T>::load1(dyr + j);
+      const float h = (Store<T>::load1(yr + j) - beta[j]) / gamma[j];
+      Store<T>::store1(dxr + j, rs * (d * gamma[j] - fmaf(h, c1, c2)));
+    }
+  }
+}
+
+// dgamma[j] = sum_p partial[p][0][j], dbeta[j] = sum_p partial[p][1][j]: 16 columns x 16
+// interleaved slices per workgroup, slices combined in a fixed order.
+__global__ __launch_bounds__(256) void ln_bwd_finalize_kernel(const float* __restrict__ partial,
+                                                              float* __restrict__ dgamma,
+                                                              float* __restrict__ dbeta,
+                                                              int parts, int64_t M) {
+  __shared__ float lds[16][17];
+  const int col = threadIdx.x & 15;
+  const int slice = threadIdx.x >> 4;
+  const int64_t j2 = static_cast<int64_t>(blockIdx.x) * 16 + col;  // index into [2][M]
+  float s = 0.0f;
+  if (j2 < 2 * M) {
+    for (int p = slice; p < parts; p += 16) s += partial[static_cast<size_t>(p) * 2 * M + j2];
+  }
+  lds[slice][col] = s;
+  __syncthreads();
+  if (slice == 0 && j2 < 2 * M) {
+    float tot = 0.0f;
+#pragma unroll
+    for (int k = 0; k < 16; ++k) tot += lds[k][col];
+    if (j2 < M) dgamma[j2] = tot;
+    else dbeta[j2 - M] = tot;
+  }
+}
+
+struct Shape {
+  int lanes;
+  int ch;
+};
+
+// Lanes per row and chunks per lane for a row of `chunks` 8-element chunks: least padding,
+// then the widest group.  ch == 0: no register-resident shape fits.
+Shape pick_shape(int chunks) {
+  static const int allowed[] = {1, 2, 3, 4, 6, 8};
+  Shape best = {0, 0};
+  int best_waste = 1 << 30;
+  for (int lanes = 64; lanes >= 16; lanes >>= 1) {
+    const int need = (chunks + lanes - 1) / lanes;
+    for (int a : allowed) {
+      if (a >= need) {
+        const int waste = lanes * a - chunks;
+        if (waste < best_waste) {
+          best_waste = waste;
+          best = {lanes, a};
+        }
+        break;
+      }
+    }
+  }
+  return best;
+}
+
+}  // namespace
+
+#define TEMPO_LN_DISPATCH(LAUNCH)                                                          \
+  switch (sh.lanes * 100 + sh.ch) {                                                        \
+    case 6401: LAUNCH(64, 1); break;                                                       \
+    case 6402: LAUNCH(64, 2); break;                                                       \
+    case 6403: LAUNCH(64, 3); break;                                                       \
+    case 6404: LAUNCH(64, 4); break;                                                       \
+    case 6406: LAUNCH(64, 6); break;                                                       \
+    case 6408: LAUNCH(64, 8); break;                                                       \
+    case 3201: LAUNCH(32, 1); break;                                                       \
+    case 3202: LAUNCH(32, 2); break;                                                       \
+    case 3203: LAUNCH(32, 3); break;                                                       \
+    case 3204: LAUNCH(32, 4); break;                                                       \
+    case 3206: LAUNCH(32, 6); break;                                                       \
+    case 3208: LAUNCH(32, 8); break;                                                       \
+    case 1601: LAUNCH(16, 1); break;                                                       \
+    case 1602: LAUNCH(16, 2); break;                                                       \
+    case 1603: LAUNCH(16, 3); break;                                                       \
+    case 1604: LAUNCH(16, 4); break;                                                       \
+    case 1606: LAUNCH(16, 6); break;                                                       \
+    case 1608: LAUNCH(16, 8); break;                                                       \
+    default: return TEMPO_ERR_UNSUPPORTED;                                                 \
+  }
+
+static bool fast_shape(int64_t M, Shape* sh, int64_t max_m = kMaxFastM) {
+  if (M % 8 != 0 || M > max_m) return false;
+  *sh = pick_shape(static_cast<int>(M / 8));
+  return sh->ch != 0;
+}
+
+tempo_status launch_layernorm_fwd(const void* x, const float* gamma, const float* beta, void* y,
+                                  float* rstd, float* mean, int64_t N, int64_t M, float eps,
+                                  tempo_dtype dt, hipStream_t st) {
+  Shape sh;
+  const int64_t cap = static_cast<int64_t>(compute_units()) * tune_get(kTuneLnFwdBlocksPerCu);
+  if (fast_shape(M, &sh)) {
+    const int groups = kFwdThreads / sh.lanes;
+    const int64_t want = (N + groups - 1) / groups;
+    const int grid = static_cast<int>(want < cap ? want : cap);
+#define TEMPO_LAUNCH_T(T, L, C)                                                              \
+  hipLaunchKernelGGL((ln_fwd_kernel<T, L, C>), dim3(grid), dim3(kFwdThreads), 0, st,         \
+                     static_cast<const T*>(x), gamma, beta, static_cast<T*>(y), rstd, mean,  \
+                     N, static_cast<int>(M), eps)
+    if (dt == TEMPO_F32) {
+#define TEMPO_LAUNCH(L, C) TEMPO_LAUNCH_T(float, L, C)
+      TEMPO_LN_DISPATCH(TEMPO_LAUNCH)
+#undef TEMPO_LAUNCH
+    } else {
+#define TEMPO_LAUNCH(L, C) TEMPO_LAUNCH_T(bf16_t, L, C)
+      TEMPO_LN_DISPATCH(TEMPO_LAUNCH)
+#undef TEMPO_LAUNCH
+    }
+#undef TEMPO_LAUNCH_T
+  } else {
+    const int grid = static_cast<int>(N < cap ? N : cap);
+    if (dt == TEMPO_F32)
+      hipLaunchKernelGGL((ln_fwd_generic_kernel<float>), dim3(grid), dim3(256), 0, st,
+                         static_cast<const float*>(x), gamma, beta, static_cast<float*>(y), rstd,
+                         mean, N, M, eps);
+    else
+      hipLaunchKernelGGL((ln_fwd_generic_kernel<bf16_t>), dim3(grid), dim3(256), 0, st,
+                         static_cast<const bf16_t*>(x), gamma, beta, static_cast<bf16_t*>(y),
+                         rstd, mean, N, M, eps);
+  }
+  return launch_status();
+}
+
+int layernorm_bwd_blocks(int64_t N, int64_t M) {
+  Shape sh;
+  int64_t want;
+  if (fast_shape(M, &sh, kMaxFastBwdM)) {
+    const int groups = kBwdThreads / sh.lanes;
+    want = (N + groups - 1) / groups;
+  } else {
+    want = N;
+  }
+  const int64_t cap = tune_get(kTuneLnBwdBlocks);
+  const int64_t b = want < cap ? want : cap;
+  return static_cast<int>(b < 1 ? 1 : b);
+}
+
+tempo_status launch_layernorm_bwd(const void* dy, const void* y, const float* gamma,
+                                  const float* beta, const float* rstd, void* dx, float* dgamma,
+                                  float* dbeta, float* workspace, int64_t N, int64_t M,
+                                  tempo_dtype dt, hipStream_t st) {
+  Shape sh;
+  const int grid = layernorm_bwd_blocks(N, M);
+  if (fast_shape(M, &sh, kMaxFastBwdM)) {
+    const size_t lds_bytes = static_cast<size_t>(kBwdWaves / 2) * 2 * M * sizeof(float);
+#define TEMPO_LAUNCH_T(T, L, C)                                                              \
+  hipLaunchKernelGGL((ln_bwd_kernel<T, L, C>), dim3(grid), dim3(kBwdThreads), lds_bytes, st, \
+                     static_cast<const T*>(dy), static_cast<const T*>(y), gamma, beta, rstd, \
+                     static_cast<T*>(dx), workspace, N, static_cast<int>(M))
+    if (dt == TEMPO_F32) {
+#define TEMPO_LAUNCH(L, C) TEMPO_LAUNCH_T(float, L, C)
+      TEMPO_LN_DISPATCH(TEMPO_LAUNCH)
+#undef TEMPO_LAUNCH
+    } else {
+#define TEMPO_LAUNCH(L, C) TEMPO_LAUNCH_T(bf16_t, L, C)
+      TEMPO_LN_DISPATCH(TEMPO_LAUNCH)
+#undef TEMPO_LAUNCH
+    }
+#undef TEMPO_LAUNCH_T
+  } else {
+    if (dt == TEMPO_F32)
+      hipLaunchKernelGGL((ln_bwd_generic_kernel<float>), dim3(grid), dim3(256), 0, st,
+                         static_cast<const float*>(dy), static_cast<const float*>(y), gamma, beta,
+                         rstd, static_cast<float*>(dx), workspace, N, M);
+    else
+      hipLaunchKernelGGL((ln_bwd_generic_kernel<bf16_t>), dim3(grid), dim3(256), 0, st,
+                         static_cast<const bf16_t*>(dy), static_cast<const bf16_t*>(y), gamma,
+                         beta, rstd, static_cast<bf16_t*>(dx), workspace, N, M);
+  }
+  if (hipGetLastError() != hipSuccess) return TEMPO_ERR_LAUNCH;
+  const int fgrid = static_cast<int>((2 * M + 15) / 16);
+  hipLaunchKernelGGL(ln_bwd_finalize_kernel, dim3(fgrid), dim3(256), 0, st, workspace, dgamma,
+                     dbeta, grid, M);
+  return launch_status();
+}
+
+}  // namespace tempo

@@ -1,0 +1,48 @@
+// Host-side declarations shared by the launchers and the C ABI.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/tempo.h"
+
+namespace tempo {
+
+// Launch-shape knobs (workgroups per launch are capped at compute_units * value).
+enum TuneKey {
+  kTuneGeluFwdBlocksPerCu = 0,
+  kTuneGeluBwdBlocksPerCu = 1,
+  kTuneLnFwdBlocksPerCu = 2,
+  kTuneLnBwdBlocks = 3,  // absolute number of workgroups (also sizes the workspace)
+  kTuneAttnFwdBlocksPerCu = 4,
+  kTuneAttnBwdBlocksPerCu = 5,
+  kTuneCount = 6
+};
+int tune_get(TuneKey k);
+int compute_units();
+
+inline tempo_status launch_status() {
+  return hipGetLastError() == hipSuccess ? TEMPO_OK : TEMPO_ERR_LAUNCH;
+}
+
+tempo_status launch_gelu_fwd(const void* x, void* y, uint32_t* mask, int64_t n, tempo_dtype dt,
+                             tempo_gelu_kind kind, hipStream_t st);
+tempo_status launch_gelu_bwd(const void* dy, const void* y, const uint32_t* mask, void* dx,
+                             int64_t n, tempo_dtype dt, tempo_gelu_kind kind, hipStream_t st);
+tempo_status launch_layernorm_fwd(const void* x, const float* gamma, const float* beta, void* y,
+                                  float* rstd, float* mean, int64_t N, int64_t M, float eps,
+                                  tempo_dtype dt, hipStream_t st);
+int layernorm_bwd_blocks(int64_t N, int64_t M);
+tempo_status launch_layernorm_bwd(const void* dy, const void* y, const float* gamma,
+                                  const float* beta, const float* rstd, void* dx, float* dgamma,
+                                  float* dbeta, float* workspace, int64_t N, int64_t M,
+                                  tempo_dtype dt, hipStream_t st);
+tempo_status launch_attn_fwd(const void* scores, const int32_t* key_len, int causal, void* probs,
+                             void* out, uint32_t* keep_bits, int64_t B, int64_t A, int64_t Sq,
+                             int64_t Sk, float p, uint64_t seed, uint64_t offset, tempo_dtype dt,
+                             hipStream_t st);
+tempo_status launch_attn_bwd(const void* dout, const void* probs, const uint32_t* keep_bits,
+                             void* dscores, void* out_re, int64_t B, int64_t A, int64_t Sq,
+                             int64_t Sk, float p, tempo_dtype dt, hipStream_t st);
+
+}  // namespace tempo

@@ -1,0 +1,319 @@
+"""Parity of the HIP path (through the C ABI) against the float64 oracle, element by element.
+
+Backward kernels are fed the oracle's stored forward results (rounded to the storage dtype),
+so that both sides consume identical bits.  Masks must match bit for bit; floating-point
+results within helpers.TOL under helpers.rel_err.
+"""
+import numpy as np
+import pytest
+import torch
+
+from helpers import TOL, rel_err
+from oracle import tempo_oracle as O
+from paper_2210_10246_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+TDT = {"f32": torch.float32, "bf16": torch.bfloat16}
+
+
+@pytest.fixture(scope="module")
+def B():
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2210_10246_amd import binding
+    binding.load()
+    return binding
+
+
+def dev(a, dt):
+    """float64 array (already representable in dt) -> CUDA tensor of dtype dt."""
+    return torch.from_numpy(np.ascontiguousarray(a)).to(TDT[dt]).cuda()
+
+
+def host(t):
+    return t.detach().cpu().to(torch.float64).numpy()
+
+
+def words(t):
+    return t.detach().cpu().numpy().view(np.uint32)
+
+
+def stored(rng, shape, dt, scale=1.0):
+    return O.round_to_dtype(rng.standard_normal(shape) * scale, dt)
+
+
+# ------------------------------------------------------------------ GELU
+GELU_SIZES = [1, 7, 8, 31, 32, 33, 1000, 4099, 2 * 128 * 3072, 1_000_003]
+
+
+@pytest.mark.parametrize("kind", ["erf", "tanh"])
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+@pytest.mark.parametrize("n", GELU_SIZES)
+def test_gelu_fwd(B, n, dt, kind):
+    rng = np.random.default_rng(n)
+    x = stored(rng, n, dt, 1.5)
+    if n >= 1000:  # a few exact branch points, far tails and signed zeros
+        xs32 = np.float32(O.GELU_XSTAR[kind])
+        edge = [xs32, np.nextafter(xs32, np.float32(-9)), np.nextafter(xs32, np.float32(9)),
+                0.0, -0.0, 7.99, 8.0, 9.5, -7.99, -8.0, -9.5, 30.0, -30.0]
+        x[: len(edge)] = O.round_to_dtype(np.array(edge, dtype=np.float64), dt)
+    y_ref, m_ref = O.gelu_fwd(x, kind, dt)
+    xd = dev(x, dt)
+    yd = torch.full_like(xd, 7.0)
+    md = torch.full((B.mask_words(n),), -1, dtype=torch.int32, device="cuda")
+    B.tempo_gelu_fwd(xd, yd, md, kind)
+    torch.cuda.synchronize()
+    assert np.array_equal(words(md), O.pack_bits(m_ref)), "mask differs"
+    assert rel_err(host(yd), y_ref) <= TOL[dt]
+    # in place: the input's storage need not survive
+    md2 = torch.zeros_like(md)
+    B.tempo_gelu_fwd(xd, xd, md2, kind)
+    torch.cuda.synchronize()
+    assert torch.equal(xd, yd) and torch.equal(md, md2)
+
+
+@pytest.mark.parametrize("kind", ["erf", "tanh"])
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+@pytest.mark.parametrize("n", [1, 9, 33, 4099, 300_000])
+def test_gelu_bwd(B, n, dt, kind):
+    rng = np.random.default_rng(100 + n)
+    x = stored(rng, n, dt, 1.7)
+    if n >= 4099:
+        x[:2000] = O.round_to_dtype(rng.uniform(-14.0, 8.0, 2000), dt)             # both tails
+        x[2000:3000] = O.round_to_dtype(O.GELU_XSTAR[kind] + rng.normal(size=1000) * 1e-2, dt)
+    y, m = O.gelu_fwd(x, kind, dt)
+    dy = stored(rng, n, dt)
+    ref = O.gelu_bwd(dy, y, m, kind, dt)
+    dyd, yd = dev(dy, dt), dev(y, dt)
+    md = torch.from_numpy(O.pack_bits(m).view(np.int32)).cuda()
+    dxd = torch.empty_like(dyd)
+    B.tempo_gelu_bwd(dyd, yd, md, dxd, kind)
+    torch.cuda.synchronize()
+    assert rel_err(host(dxd), ref) <= TOL[dt]
+    B.tempo_gelu_bwd(dyd, yd, md, dyd, kind)     # dx may alias dy
+    torch.cuda.synchronize()
+    assert torch.equal(dyd, dxd)
+
+
+@pytest.mark.parametrize("kind", ["erf", "tanh"])
+def test_gelu_bwd_edge_values(B, kind):
+    ys = O.GELU_YSTAR[kind]
+    y = np.array([ys - 1e-3, ys, 0.0, -0.0, 0.0, np.inf, np.nan, 1e-30, -1e-30, -1e-45, 20.0, 6.5,
+                  -0.0625, -0.06249, -0.1, 1e-20], dtype=np.float64)
+    y = O.round_to_dtype(y, "f32")
+    m = np.array([1, 1, 0, 0, 1, 1, 1, 0, 0, 0, 1, 1, 0, 0, 0, 1], dtype=bool)
+    dy = np.ones_like(y)
+    ref = O.gelu_bwd(dy, y, m, kind, "f32")
+    dxd = torch.empty(y.size, dtype=torch.float32, device="cuda")
+    md = torch.from_numpy(O.pack_bits(m).view(np.int32)).cuda()
+    B.tempo_gelu_bwd(dev(dy, "f32"), dev(y, "f32"), md, dxd, kind)
+    got = host(dxd)
+    assert np.isnan(got[6]) and np.isnan(ref[6])
+    ok = ~np.isnan(ref)
+    np.testing.assert_allclose(got[ok], ref[ok], rtol=0, atol=5e-7)
+
+
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+def test_gelu_round_trip_against_input_based_gradient(B, dt):
+    # fwd then bwd on the GPU vs dy * GELU'(x): the lossy part is only the storage of y
+    rng = np.random.default_rng(7)
+    n = 200_000
+    x = stored(rng, n, dt, 1.5)
+    dy = stored(rng, n, dt)
+    xd, dyd = dev(x, dt), dev(dy, dt)
+    yd = torch.empty_like(xd)
+    md = torch.empty(B.mask_words(n), dtype=torch.int32, device="cuda")
+    dxd = torch.empty_like(xd)
+    B.tempo_gelu_fwd(xd, yd, md, "erf")
+    B.tempo_gelu_bwd(dyd, yd, md, dxd, "erf")
+    ref = O.gelu_bwd_from_input(dy, x, "erf")
+    err = np.abs(host(dxd) - ref)
+    # the square-root singularity at the minimum amplifies the rounding of y: |dd| ~ sqrt(ulp)
+    assert err.max() <= (5e-3 if dt == "f32" else 0.15) * max(1.0, np.abs(dy).max())
+    assert np.sqrt(np.mean(err**2)) <= (2e-6 if dt == "f32" else 6e-3)
+
+
+# ------------------------------------------------------------------ LayerNorm
+LN_SHAPES = [(256, 768), (5, 1024), (37, 768), (3, 8), (9, 64), (7, 100), (4, 4096), (3, 2048),
+             (2, 4104), (1, 1), (6, 1536), (300, 1024), (3, 3072), (1030, 256)]
+
+
+@pytest.mark.parametrize("eps", [1e-12, 1e-5])
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+@pytest.mark.parametrize("shape", LN_SHAPES)
+def test_layernorm_fwd(B, shape, dt, eps):
+    N, M = shape
+    rng = np.random.default_rng(N * 10007 + M)
+    x = stored(rng, shape, dt) + O.round_to_dtype(rng.normal(size=(N, 1)), dt)
+    x = O.round_to_dtype(x, dt)
+    gamma = O.round_to_dtype(1 + 0.1 * rng.standard_normal(M), "f32")
+    beta = O.round_to_dtype(0.1 * rng.standard_normal(M), "f32")
+    if M == 1:
+        eps = 1e-5
+    y_ref, rstd_ref, mean_ref = O.layernorm_fwd(x, gamma, beta, eps, dt)
+    xd, gd, bd = dev(x, dt), dev(gamma, "f32"), dev(beta, "f32")
+    yd = torch.empty_like(xd)
+    rd = torch.empty(N, dtype=torch.float32, device="cuda")
+    md = torch.empty(N, dtype=torch.float32, device="cuda")
+    B.tempo_layernorm_fwd(xd, gd, bd, yd, rd, md, eps)
+    torch.cuda.synchronize()
+    assert rel_err(host(yd), y_ref) <= TOL[dt]
+    assert rel_err(host(rd), rstd_ref) <= TOL["f32"]
+    assert rel_err(host(md), mean_ref) <= TOL["f32"]
+    rd2 = torch.empty_like(rd)
+    B.tempo_layernorm_fwd(xd, gd, bd, xd, rd2, None, eps)     # in place, no mean
+    torch.cuda.synchronize()
+    assert torch.equal(xd, yd) and torch.equal(rd, rd2)
+
+
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+@pytest.mark.parametrize("shape", LN_SHAPES)
+def test_layernorm_bwd(B, shape, dt):
+    N, M = shape
+    if M == 1:
+        pytest.skip("variance of one element is zero: xhat is 0/0-free but uninformative")
+    eps = 1e-5
+    rng = np.random.default_rng(N * 7919 + M)
+    x = stored(rng, shape, dt)
+    gamma = O.round_to_dtype(1 + 0.1 * rng.standard_normal(M), "f32")
+    beta = O.round_to_dtype(0.1 * rng.standard_normal(M), "f32")
+    dy = stored(rng, shape, dt)
+    y, rstd, _ = O.layernorm_fwd(x, gamma, beta, eps, dt)
+    dx_ref, dg_ref, db_ref = O.layernorm_bwd(dy, y, gamma, beta, rstd, dt)
+    dyd, yd = dev(dy, dt), dev(y, dt)
+    gd, bd, rd = dev(gamma, "f32"), dev(beta, "f32"), dev(rstd, "f32")
+    dxd = torch.empty_like(dyd)
+    dgd = torch.empty(M, dtype=torch.float32, device="cuda")
+    dbd = torch.empty(M, dtype=torch.float32, device="cuda")
+    ws = torch.empty(max(B.tempo_layernorm_bwd_workspace_bytes(N, M), 16), dtype=torch.uint8, device="cuda")
+    B.tempo_layernorm_bwd(dyd, yd, gd, bd, rd, dxd, dgd, dbd, ws)
+    torch.cuda.synchronize()
+    assert rel_err(host(dxd), dx_ref) <= TOL[dt]
+    assert rel_err(host(dgd), dg_ref) <= 2 * TOL["f32"]
+    assert rel_err(host(dbd), db_ref) <= 2 * TOL["f32"]
+    dg2, db2 = torch.empty_like(dgd), torch.empty_like(dbd)
+    B.tempo_layernorm_bwd(dyd, yd, gd, bd, rd, dyd, dg2, db2, ws)    # dx may alias dy
+    torch.cuda.synchronize()
+    assert torch.equal(dyd, dxd)
+    assert torch.equal(dg2, dgd) and torch.equal(db2, dbd)          # fixed summation order
+    with pytest.raises(B.TempoError):
+        B.tempo_layernorm_bwd(dyd, yd, gd, bd, rd, dxd, dgd, dbd, ws[:16])
+
+
+# ------------------------------------------------------------------ attention softmax -> dropout
+ATTN_CASES = [
+    # B, A, Sq, Sk, mask, p
+    (2, 12, 128, 128, "none", 0.1),
+    (3, 2, 128, 128, "padding", 0.1),
+    (2, 2, 512, 512, "padding", 0.1),
+    (1, 2, 1024, 1024, "causal", 0.1),
+    (1, 2, 5, 40, "none", 0.1),        # rows end inside a mask word: byte stores
+    (2, 1, 7, 100, "padding", 0.25),   # rows not a multiple of 8: scalar path
+    (1, 1, 3, 8, "causal", 0.5),
+    (1, 3, 4, 64, "causal", 0.1),      # Sq != Sk
+    (2, 2, 16, 96, "zero_len", 0.1),   # one sequence fully masked
+    (1, 2, 33, 2048, "causal", 0.1),
+    (1, 1, 9, 3072, "padding", 0.1),
+    (1, 1, 5, 4104, "none", 0.1),      # longer than the register path
+    (2, 2, 64, 160, "padding", 0.0),   # p = 0: everything kept
+    (1, 1, 70, 1, "none", 0.1),
+]
+
+
+def _attn_inputs(case, dt, rng):
+    Bn, A, Sq, Sk, mask, p = case
+    s = stored(rng, (Bn, A, Sq, Sk), dt, 0.125 if Sk >= 128 else 1.0)
+    key_len, causal = None, False
+    if mask == "padding":
+        key_len = rng.integers(max(1, Sk // 2), Sk + 1, size=Bn).astype(np.int32)
+    elif mask == "zero_len":
+        key_len = np.array([0] + [Sk - 3] * (Bn - 1), dtype=np.int32)
+    elif mask == "causal":
+        causal = True
+    return s, key_len, causal, np.float32(p)
+
+
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+@pytest.mark.parametrize("case", ATTN_CASES, ids=lambda c: "x".join(map(str, c)))
+def test_attn_fwd(B, case, dt):
+    rng = np.random.default_rng(hash(case[:4]) % (1 << 31))
+    s, key_len, causal, p = _attn_inputs(case, dt, rng)
+    seed, offset = 0x5EED0000ABCD1234, (1 << 33) + 17
+    P_ref, out_ref, K_ref = O.attn_softmax_dropout_fwd(s, key_len, causal, p, seed, offset, dt)
+    sd = dev(s, dt)
+    kd = None if key_len is None else torch.from_numpy(key_len).cuda()
+    Pd = torch.full_like(sd, 3.0)
+    od = torch.full_like(sd, 3.0)
+    n = s.size
+    md = torch.full((B.mask_words(n),), -1, dtype=torch.int32, device="cuda")
+    B.tempo_attn_softmax_dropout_fwd(sd, kd, causal, Pd, od, md, float(p), seed, offset)
+    torch.cuda.synchronize()
+    assert np.array_equal(words(md), O.pack_bits(K_ref)), "keep mask differs"
+    assert rel_err(host(Pd), P_ref) <= TOL[dt]
+    assert rel_err(host(od), out_ref) <= TOL[dt]
+    valid = O.attention_valid(*s.shape, key_len, causal)
+    assert np.all(host(Pd)[~valid] == 0) and np.all(host(od)[~K_ref] == 0)
+    # out is optional; P may overwrite the scores
+    md2 = torch.zeros_like(md)
+    B.tempo_attn_softmax_dropout_fwd(sd, kd, causal, sd, None, md2, float(p), seed, offset)
+    torch.cuda.synchronize()
+    assert torch.equal(sd, Pd) and torch.equal(md, md2)
+    # backward's recomputed dropout output is bit-identical to the forward's (same stored P)
+    dod = dev(stored(rng, s.shape, dt), dt)
+    dsd, ord_ = torch.empty_like(sd), torch.empty_like(sd)
+    B.tempo_attn_softmax_dropout_bwd(dod, Pd, md, dsd, ord_, float(p))
+    torch.cuda.synchronize()
+    assert torch.equal(ord_.view(torch.int16 if dt == "bf16" else torch.int32),
+                       od.view(torch.int16 if dt == "bf16" else torch.int32))
+
+
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+@pytest.mark.parametrize("case", ATTN_CASES, ids=lambda c: "x".join(map(str, c)))
+def test_attn_bwd(B, case, dt):
+    rng = np.random.default_rng(hash(case[:4]) % (1 << 31) + 1)
+    s, key_len, causal, p = _attn_inputs(case, dt, rng)
+    seed, offset = 99, 5
+    P, _, K = O.attn_softmax_dropout_fwd(s, key_len, causal, p, seed, offset, dt)
+    dout = stored(rng, s.shape, dt)
+    dS_ref, out_re_ref = O.attn_softmax_dropout_bwd(dout, P, K, p, dt)
+    dod, Pd = dev(dout, dt), dev(P, dt)
+    md = torch.from_numpy(O.pack_bits(K).view(np.int32)).cuda()
+    dsd, ord_ = torch.empty_like(dod), torch.empty_like(dod)
+    B.tempo_attn_softmax_dropout_bwd(dod, Pd, md, dsd, ord_, float(p))
+    torch.cuda.synchronize()
+    assert rel_err(host(dsd), dS_ref) <= TOL[dt]
+    assert rel_err(host(ord_), out_re_ref) <= TOL[dt]
+    B.tempo_attn_softmax_dropout_bwd(dod, Pd, md, dod, None, float(p))   # in place, no Out
+    torch.cuda.synchronize()
+    assert torch.equal(dod, dsd)
+
+
+def test_mask_does_not_depend_on_launch_shape(B):
+    rng = np.random.default_rng(5)
+    s = stored(rng, (2, 2, 64, 256), "bf16")
+    sd = dev(s, "bf16")
+    masks = []
+    old = B.tempo_get_launch_param(4)
+    for cap in (1, 3, 16):
+        B.tempo_set_launch_param(4, cap)
+        md = torch.zeros(B.mask_words(s.size), dtype=torch.int32, device="cuda")
+        B.tempo_attn_softmax_dropout_fwd(sd, None, False, torch.empty_like(sd), None, md, 0.1, 42, 0)
+        masks.append(md.cpu())
+    B.tempo_set_launch_param(4, old)
+    assert torch.equal(masks[0], masks[1]) and torch.equal(masks[0], masks[2])
+    assert np.array_equal(words(masks[0]), O.pack_bits(O.dropout_keep(s.size, 0.1, 42, 0)))
+
+
+def test_non_default_stream(B):
+    st = torch.cuda.Stream()
+    rng = np.random.default_rng(6)
+    x = stored(rng, 5000, "f32")
+    xd = dev(x, "f32")
+    yd = torch.empty_like(xd)
+    md = torch.empty(B.mask_words(x.size), dtype=torch.int32, device="cuda")
+    torch.cuda.synchronize()
+    with torch.cuda.stream(st):
+        B.tempo_gelu_fwd(xd, yd, md, "erf")
+    st.synchronize()
+    y_ref, m_ref = O.gelu_fwd(x, "erf", "f32")
+    assert rel_err(host(yd), y_ref) <= TOL["f32"] and np.array_equal(words(md), O.pack_bits(m_ref))
