@@ -1,0 +1,292 @@
+#!/usr/bin/env python3
+"""Benchmark of the Tempo hot path on one MI355X.
+
+A step is one pass of the whole hot path of one encoder layer over one batch of synthetic
+input: GELU fwd+bwd, two LayerNorms fwd+bwd, attention softmax-dropout fwd+bwd, all through
+the C ABI.  Inputs are resident in HBM before the timed region; buffer sets are rotated so
+that nothing is served from the 256 MB Infinity Cache.  One JSON line is printed.
+
+    python bench.py [--steps K] [--warmup W] [--config 1] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, vendor peak
+ROTATE_BYTES = 640 << 20       # distinct bytes a kernel must touch before it sees a buffer again
+METRIC = "fwd+bwd HBM GB/s (% of peak) per layer; activation bytes saved/token"
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", type=int, default=1, help="BASELINE.json config index (0-4)")
+    ap.add_argument("--batch", type=int, default=None, help="batch override (config 4 sweep)")
+    ap.add_argument("--dtype", choices=["f32", "bf16"], default=None)
+    ap.add_argument("--kernel-iters", type=int, default=60, help="launches per kernel timing loop")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-timing", action="store_true")
+    ap.add_argument("--only", default=None, help="time only this kernel (for profiling)")
+    return ap.parse_args()
+
+
+def algorithmic_bytes(cfg):
+    """Bytes each kernel must move per launch (reads of inputs + writes of outputs)."""
+    e = cfg.elem_bytes
+    n_g = cfg.tokens * cfg.ffn
+    N, M = cfg.tokens, cfg.hidden
+    n_a = cfg.batch * cfg.heads * cfg.seq * cfg.seq
+    return {
+        "gelu_fwd": n_g * 2 * e + n_g / 8,
+        "gelu_bwd": n_g * 3 * e + n_g / 8,
+        "layernorm_fwd": N * M * 2 * e + 4 * N + 8 * M,
+        "layernorm_bwd": N * M * 3 * e + 4 * N + 16 * M,
+        "attn_fwd": n_a * 3 * e + n_a / 8,
+        "attn_bwd": n_a * 4 * e + n_a / 8,
+    }
+
+
+def activation_bytes_saved(cfg):
+    """Bytes per token and layer that need not be kept for backward, by tensor inventory."""
+    e, H, A, S = cfg.elem_bytes, cfg.hidden, cfg.heads, cfg.seq
+    kept_base = {"gelu": 4 * H * e, "layernorm": 2 * (H * e + 8), "attention": 3 * A * S * e + A * S}
+    kept_here = {"gelu": (4 * H) // 8, "layernorm": 2 * 4, "attention": A * S * e + (A * S) // 8}
+    return {k: kept_base[k] - kept_here[k] for k in kept_base}
+
+
+class Buffers:
+    """R rotating sets of device buffers for one kernel family."""
+
+    def __init__(self, make, footprint):
+        self.n = max(2, min(16, -(-ROTATE_BYTES // max(footprint, 1))))
+        self.sets = [make(i) for i in range(self.n)]
+        self.i = 0
+
+    def next(self):
+        s = self.sets[self.i]
+        self.i = (self.i + 1) % self.n
+        return s
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU; --gpus must be 1 (no multi-GPU path exists)",
+              file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    from paper_2210_10246_amd import binding as B
+    from paper_2210_10246_amd import workloads as W
+
+    B.load()
+    assert torch.cuda.is_available(), "bench.py needs the MI355X"
+    dev = torch.device("cuda:0")
+    cfg = W.config(args.config, batch=args.batch, dtype=args.dtype)
+    dt = cfg.dtype
+    tdt = W.torch_dtype(dt)
+    e = cfg.elem_bytes
+    N, M = cfg.tokens, cfg.hidden
+    shape_a = (cfg.batch, cfg.heads, cfg.seq, cfg.seq)
+    n_g, n_a = N * cfg.ffn, int(np.prod(shape_a))
+    algo = algorithmic_bytes(cfg)
+
+    # ---- seeded inputs, generated once on the host and copied into every rotating set
+    g_in = W.gelu_inputs(cfg)
+    l_in = W.layernorm_inputs(cfg)
+    a_in = W.attention_inputs(cfg)
+    key_len = None if a_in["key_len"] is None else a_in["key_len"].to(dev)
+    gamma, beta = l_in["gamma"].to(dev), l_in["beta"].to(dev)
+    gx0, gdy0 = g_in["x"].to(dev), g_in["dy"].to(dev)
+    lx0, ldy0 = l_in["x"].to(dev), l_in["dy"].to(dev)
+    as0, ado0 = a_in["scores"].to(dev), a_in["dout"].to(dev)
+    ws_bytes = B.tempo_layernorm_bwd_workspace_bytes(N, M)
+
+    def gelu_set(_):
+        return dict(x=gx0.clone(), dy=gdy0.clone(), y=torch.empty_like(gx0), dx=torch.empty_like(gx0),
+                    m=torch.empty(B.mask_words(n_g), dtype=torch.int32, device=dev))
+
+    def ln_set(_):
+        return dict(x=lx0.clone(), dy=ldy0.clone(), y=torch.empty_like(lx0), dx=torch.empty_like(lx0),
+                    rstd=torch.empty(N, dtype=torch.float32, device=dev),
+                    dg=torch.empty(M, dtype=torch.float32, device=dev),
+                    db=torch.empty(M, dtype=torch.float32, device=dev),
+                    ws=torch.empty(ws_bytes, dtype=torch.uint8, device=dev))
+
+    def attn_set(_):
+        return dict(s=as0.clone(), do=ado0.clone(), P=torch.empty_like(as0), out=torch.empty_like(as0),
+                    dS=torch.empty_like(as0), out_re=torch.empty_like(as0),
+                    k=torch.empty(B.mask_words(n_a), dtype=torch.int32, device=dev))
+
+    gelu_b = Buffers(gelu_set, 4 * n_g * e)
+    ln_b = Buffers(ln_set, 4 * N * M * e)
+    attn_b = Buffers(attn_set, 6 * n_a * e)
+    seed, p, kind, eps = cfg.dropout_seed, cfg.p, cfg.gelu_kind, cfg.eps
+    causal = a_in["causal"]
+
+    def k_gelu_fwd(s): B.tempo_gelu_fwd(s["x"], s["y"], s["m"], kind)
+    def k_gelu_bwd(s): B.tempo_gelu_bwd(s["dy"], s["y"], s["m"], s["dx"], kind)
+    def k_ln_fwd(s): B.tempo_layernorm_fwd(s["x"], gamma, beta, s["y"], s["rstd"], None, eps)
+    def k_ln_bwd(s): B.tempo_layernorm_bwd(s["dy"], s["y"], gamma, beta, s["rstd"], s["dx"], s["dg"], s["db"], s["ws"])
+    def k_attn_fwd(s): B.tempo_attn_softmax_dropout_fwd(s["s"], key_len, causal, s["P"], s["out"], s["k"], p, seed, 0)
+    def k_attn_bwd(s): B.tempo_attn_softmax_dropout_bwd(s["do"], s["P"], s["k"], s["dS"], s["out_re"], p)
+
+    kernels = {
+        "gelu_fwd": (k_gelu_fwd, gelu_b), "gelu_bwd": (k_gelu_bwd, gelu_b),
+        "layernorm_fwd": (k_ln_fwd, ln_b), "layernorm_bwd": (k_ln_bwd, ln_b),
+        "attn_fwd": (k_attn_fwd, attn_b), "attn_bwd": (k_attn_bwd, attn_b),
+    }
+
+    # every set gets a valid forward state once (backward kernels read y / P / masks)
+    for s in gelu_b.sets: k_gelu_fwd(s)
+    for s in ln_b.sets: k_ln_fwd(s)
+    for s in attn_b.sets: k_attn_fwd(s)
+    torch.cuda.synchronize()
+
+    def step():
+        g = gelu_b.next()
+        a = attn_b.next()
+        l1, l2 = ln_b.next(), ln_b.next()
+        # forward order of an encoder layer, then backward in reverse
+        k_attn_fwd(a); k_ln_fwd(l1); k_gelu_fwd(g); k_ln_fwd(l2)
+        k_ln_bwd(l2); k_gelu_bwd(g); k_ln_bwd(l1); k_attn_bwd(a)
+
+    step_bytes = (algo["gelu_fwd"] + algo["gelu_bwd"] + 2 * (algo["layernorm_fwd"] + algo["layernorm_bwd"])
+                  + algo["attn_fwd"] + algo["attn_bwd"])
+
+    ms_per_step = float("nan")
+    if args.only is None:
+        for _ in range(args.warmup):
+            step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+        ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    # ---- per-kernel launch durations: events on the stream the kernels are launched on
+    per_kernel = {}
+    if not args.no_kernel_timing:
+        for name, (fn, bufs) in kernels.items():
+            if args.only is not None and name != args.only:
+                continue
+            for _ in range(max(3, bufs.n)):
+                fn(bufs.next())
+            torch.cuda.synchronize()
+            ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            ev0.record()
+            for _ in range(args.kernel_iters):
+                fn(bufs.next())
+            ev1.record()
+            ev1.synchronize()
+            us = ev0.elapsed_time(ev1) * 1e3 / args.kernel_iters
+            gbs = algo[name] / us * 1e-3
+            per_kernel[name] = {"us": round(us, 2), "GB/s": round(gbs, 1),
+                                "frac_of_peak": round(gbs / HBM_PEAK_GBS, 4),
+                                "bytes": int(algo[name]), "buffer_sets": bufs.n}
+
+    # ---- what a plain 16-byte copy reaches on this GPU (read + write bytes per second)
+    copy_gbs = None
+    if not args.no_kernel_timing and args.only is None:
+        nb = 256 << 20
+        srcs = [torch.empty(nb, dtype=torch.uint8, device=dev).fill_(i) for i in range(3)]
+        dsts = [torch.empty(nb, dtype=torch.uint8, device=dev) for _ in range(3)]
+        for i in range(3):
+            B.tempo_copy(srcs[i], dsts[i])
+        torch.cuda.synchronize()
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        ev0.record()
+        for i in range(30):
+            B.tempo_copy(srcs[i % 3], dsts[i % 3])
+        ev1.record()
+        ev1.synchronize()
+        copy_gbs = round(2 * nb * 30 / (ev0.elapsed_time(ev1) * 1e-3) * 1e-9, 1)
+        del srcs, dsts
+
+    value = step_bytes / (ms_per_step * 1e-3) * 1e-9 if ms_per_step == ms_per_step else None
+    roofline = None
+    if per_kernel:
+        weight = {k: v["us"] * (2 if k.startswith("layernorm") else 1) for k, v in per_kernel.items()}
+        dom = max(weight, key=weight.get)
+        k = per_kernel[dom]
+        roofline = {"kernel": dom, "bound": "hbm", "achieved": k["GB/s"], "peak": HBM_PEAK_GBS,
+                    "unit": "GB/s", "frac": k["frac_of_peak"], "traffic": None,
+                    "us_per_launch": k["us"], "algorithmic_bytes": k["bytes"]}
+
+    cpu = None
+    if not args.no_cpu_baseline and args.only is None:
+        cpu = cpu_baseline(cfg, algo)
+
+    saved = activation_bytes_saved(cfg)
+    line = {
+        "metric": METRIC, "value": None if value is None else round(value, 1), "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": None if value is None else round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": dt,
+        "data": "synthetic",
+        "config": {"workload": f"config {cfg.index}: {cfg.name}", "batch": cfg.batch, "seq_len": cfg.seq,
+                   "hidden": cfg.hidden, "heads": cfg.heads, "ffn": cfg.ffn, "mask": cfg.mask,
+                   "dropout_p": cfg.p, "gelu": cfg.gelu_kind,
+                   "step": "attn fwd, LN fwd, GELU fwd, LN fwd, LN bwd, GELU bwd, LN bwd, attn bwd",
+                   "algorithmic_bytes_per_step": int(step_bytes)},
+        "frac_of_hbm_peak": None if value is None else round(value / HBM_PEAK_GBS, 4),
+        "copy_kernel_GB/s": copy_gbs,
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "kernels": per_kernel,
+        "activation_bytes_saved_per_token": {**saved, "total": sum(saved.values())},
+    }
+    print(json.dumps(line))
+
+
+def cpu_baseline(cfg, algo):
+    """The float64 oracle, as it stands, on the leading 1/64 of the rows of the same workload."""
+    import numpy as np
+    from oracle import tempo_oracle as O
+    from paper_2210_10246_amd import workloads as W
+
+    frac = 64
+    dt = cfg.dtype
+    rows = max(1, cfg.tokens // frac)
+    ab = max(1, cfg.batch // frac) if cfg.batch >= frac else 1
+    a_frac = cfg.batch / ab
+    g = W.gelu_inputs(cfg, rows=rows)
+    l = W.layernorm_inputs(cfg, rows=rows)
+    a = W.attention_inputs(cfg, batch=ab)
+    gx, gdy = W.as_f64(g["x"]), W.as_f64(g["dy"])
+    lx, ldy = W.as_f64(l["x"]), W.as_f64(l["dy"])
+    gam, bet = W.as_f64(l["gamma"]), W.as_f64(l["beta"])
+    sc, do = W.as_f64(a["scores"]), W.as_f64(a["dout"])
+    kl = None if a["key_len"] is None else a["key_len"].numpy()
+    t0 = time.perf_counter()
+    y, m = O.gelu_fwd(gx, cfg.gelu_kind, dt)
+    O.gelu_bwd(gdy, y, m, cfg.gelu_kind, dt)
+    for _ in range(2):
+        ly, rstd, _ = O.layernorm_fwd(lx, gam, bet, cfg.eps, dt)
+        O.layernorm_bwd(ldy, ly, gam, bet, rstd, dt)
+    P, _, K = O.attn_softmax_dropout_fwd(sc, kl, a["causal"], cfg.p, cfg.dropout_seed, 0, dt)
+    O.attn_softmax_dropout_bwd(do, P, K, cfg.p, dt)
+    sec = time.perf_counter() - t0
+    row_frac = rows / cfg.tokens
+    sample_bytes = ((algo["gelu_fwd"] + algo["gelu_bwd"]) * row_frac
+                    + 2 * (algo["layernorm_fwd"] + algo["layernorm_bwd"]) * row_frac
+                    + (algo["attn_fwd"] + algo["attn_bwd"]) / a_frac)
+    return {"value": round(sample_bytes / sec * 1e-9, 5), "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "seconds": round(sec, 2), "host_cores_available": os.cpu_count(),
+            "sample": f"first {rows} of {cfg.tokens} rows for GELU and LayerNorm, first {ab} of "
+                      f"{cfg.batch} sequences for attention; numpy float64, single thread"}
+
+
+if __name__ == "__main__":
+    main()

@@ -55,15 +55,26 @@ TEMPO_API int tempo_version(void);
 
 /*
  * Launch-shape knobs for tuning and benchmarking (process-wide, not needed for correctness):
- *   key 0 gelu_fwd, 1 gelu_bwd, 2 layernorm_fwd, 4 attn fwd, 5 attn bwd: cap on workgroups per
- *   compute unit; key 3: total workgroups of layernorm_bwd (this also sizes its workspace, so
- *   query tempo_layernorm_bwd_workspace_bytes after changing it).  Results never depend on
- *   these except the summation order of dgamma/dbeta.  value in [1, 65536].
- * tempo_set_launch_param returns TEMPO_OK or TEMPO_ERR_INVALID_ARG; the getter returns -1 for
- * an unknown key.
+ *   key 0 / 1: 8-element chunks per lane in gelu_fwd / gelu_bwd (1, 2 or 4);
+ *   key 2, 4, 5: cap on workgroups per compute unit of layernorm_fwd, attn fwd, attn bwd
+ *   (rows beyond the cap are walked in a loop);
+ *   key 3: rows each lane group of layernorm_bwd walks; this sets its grid and the size of its
+ *   workspace, so query tempo_layernorm_bwd_workspace_bytes after changing it.
+ * Results never depend on these except the summation order of dgamma/dbeta.  value in
+ * [1, 65536].  tempo_set_launch_param returns TEMPO_OK or TEMPO_ERR_INVALID_ARG; the getter
+ * returns -1 for an unknown key.
  */
 TEMPO_API int tempo_set_launch_param(int key, int value);
 TEMPO_API int tempo_get_launch_param(int key);
+
+/*
+ * Plain device-to-device copy of nbytes (a multiple of 16) with 16-byte accesses, at most
+ * blocks_per_cu workgroups per compute unit.  Not part of the method: it is the yardstick for
+ * the bandwidth a pure streaming kernel reaches on this GPU and the known-size kernel used to
+ * calibrate hardware byte counters.  src and dst must not overlap.
+ */
+TEMPO_API tempo_status tempo_copy(const void* src, void* dst, int64_t nbytes, int blocks_per_cu,
+                                  void* hip_stream);
 
 /*
  * In-place GELU forward, (y, m) = GELU*(x)            [Sec. 3.1; App. E.1 eq. (1); App. F.1]

@@ -29,6 +29,7 @@ _SIGNATURES = {
     "tempo_version": (_int, []),
     "tempo_set_launch_param": (_int, [_int, _int]),
     "tempo_get_launch_param": (_int, [_int]),
+    "tempo_copy": (_int, [_vp, _vp, _i64, _int, _vp]),
     "tempo_gelu_fwd": (_int, [_vp, _vp, _vp, _i64, _int, _int, _vp]),
     "tempo_gelu_bwd": (_int, [_vp, _vp, _vp, _vp, _i64, _int, _int, _vp]),
     "tempo_layernorm_fwd": (_int, [_vp, _vp, _vp, _vp, _vp, _vp, _i64, _i64, _f32, _int, _vp]),
@@ -98,6 +99,14 @@ def tempo_set_launch_param(key: int, value: int):
 
 def tempo_get_launch_param(key: int) -> int:
     return load().tempo_get_launch_param(key)
+
+
+def tempo_copy(src, dst, blocks_per_cu=16, stream=None):
+    """Plain streaming copy of src into dst (same byte size, multiple of 16)."""
+    nbytes = src.numel() * src.element_size()
+    assert nbytes == dst.numel() * dst.element_size()
+    _check(load().tempo_copy(_ptr(src), _ptr(dst), nbytes, blocks_per_cu, _stream(stream)),
+           "tempo_copy")
 
 
 def tempo_gelu_fwd(x, y, mask, kind="erf", stream=None):

@@ -8,12 +8,12 @@
 namespace tempo {
 
 static std::atomic<int> g_tune[kTuneCount] = {
-    {16},   // gelu fwd: workgroups per CU
-    {16},   // gelu bwd
-    {8},    // layernorm fwd
-    {512},  // layernorm bwd: workgroups in total
-    {16},   // attention fwd
-    {16},   // attention bwd
+    {4},      // gelu fwd: chunks per lane
+    {2},      // gelu bwd: chunks per lane
+    {65536},  // layernorm fwd: workgroups per CU (65536 = one row per lane group)
+    {4},      // layernorm bwd: rows per lane group
+    {65536},  // attention fwd: workgroups per CU (65536 = one row per lane group)
+    {65536},  // attention bwd: workgroups per CU
 };
 
 int tune_get(TuneKey k) { return g_tune[k].load(std::memory_order_relaxed); }
@@ -36,6 +36,16 @@ int compute_units() {
 static bool dtype_ok(tempo_dtype dt) { return dt == TEMPO_F32 || dt == TEMPO_BF16; }
 static bool kind_ok(tempo_gelu_kind k) { return k == TEMPO_GELU_ERF || k == TEMPO_GELU_TANH; }
 static bool prob_ok(float p) { return p >= 0.0f && p < 1.0f; }  // false for NaN
+
+// Plain streaming copy, 16 bytes per lane and access: the reference point for what the memory
+// system delivers to a kernel that does nothing else, and the known-size kernel against which
+// hardware byte counters are calibrated.
+__global__ __launch_bounds__(256) void copy_kernel(const u32x4* __restrict__ src,
+                                                   u32x4* __restrict__ dst, int64_t n16) {
+  const int64_t stride = static_cast<int64_t>(gridDim.x) * 256;
+  for (int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x; i < n16; i += stride)
+    dst[i] = src[i];
+}
 
 }  // namespace tempo
 
@@ -65,6 +75,21 @@ TEMPO_API int tempo_set_launch_param(int key, int value) {
 TEMPO_API int tempo_get_launch_param(int key) {
   if (key < 0 || key >= kTuneCount) return -1;
   return tune_get(static_cast<TuneKey>(key));
+}
+
+tempo_status tempo_copy(const void* src, void* dst, int64_t nbytes, int blocks_per_cu,
+                        void* hip_stream) {
+  if (nbytes < 0 || (nbytes & 15) != 0 || blocks_per_cu < 1) return TEMPO_ERR_INVALID_ARG;
+  if (nbytes == 0) return TEMPO_OK;
+  if (!src || !dst) return TEMPO_ERR_INVALID_ARG;
+  if (!aligned16(src) || !aligned16(dst)) return TEMPO_ERR_UNSUPPORTED;
+  const int64_t n16 = nbytes / 16;
+  const int64_t want = (n16 + 255) / 256;
+  const int64_t cap = static_cast<int64_t>(compute_units()) * blocks_per_cu;
+  hipLaunchKernelGGL(copy_kernel, dim3(static_cast<int>(want < cap ? want : cap)), dim3(256), 0,
+                     static_cast<hipStream_t>(hip_stream), static_cast<const u32x4*>(src),
+                     static_cast<u32x4*>(dst), n16);
+  return launch_status();
 }
 
 tempo_status tempo_gelu_fwd(const void* x, void* y, uint32_t* mask, int64_t n, tempo_dtype dt,

@@ -20,6 +20,11 @@ struct RngArgs {
   uint32_t t16;  // keep iff 16-bit draw < t16; 65536 keeps everything (generator skipped)
 };
 
+// a ^ b ^ c in one VALU op (v_bitop3_b32 with truth table 0x96).
+__device__ __forceinline__ uint32_t xor3(uint32_t a, uint32_t b, uint32_t c) {
+  return __builtin_amdgcn_bitop3_b32(a, b, c, 0x96);
+}
+
 // Philox4x32-10 (Salmon, Moraes, Dror, Shaw, SC'11): ten rounds of two 32x32->64 multiplies,
 // the key advanced by the two Weyl constants between rounds.
 __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
@@ -28,8 +33,8 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
   for (int r = 0; r < 10; ++r) {
     const uint64_t p0 = static_cast<uint64_t>(0xD2511F53u) * c0;
     const uint64_t p1 = static_cast<uint64_t>(0xCD9E8D57u) * c2;
-    const uint32_t n0 = static_cast<uint32_t>(p1 >> 32) ^ c1 ^ k0;
-    const uint32_t n2 = static_cast<uint32_t>(p0 >> 32) ^ c3 ^ k1;
+    const uint32_t n0 = xor3(static_cast<uint32_t>(p1 >> 32), c1, k0);
+    const uint32_t n2 = xor3(static_cast<uint32_t>(p0 >> 32), c3, k1);
     c1 = static_cast<uint32_t>(p1);
     c3 = static_cast<uint32_t>(p0);
     c0 = n0;
@@ -48,109 +53,143 @@ __device__ __forceinline__ uint32_t keep_byte(uint64_t g, const RngArgs& a) {
                 a.seed_lo, a.seed_hi, w);
   uint32_t byte = 0;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    byte |= ((w[i] & 0xFFFFu) < a.t16 ? 1u : 0u) << (2 * i);
-    byte |= ((w[i] >> 16) < a.t16 ? 1u : 0u) << (2 * i + 1);
+  for (int i = 3; i >= 0; --i) {  // last element first: each step shifts one bit in
+    byte = (byte << 1) | ((w[i] >> 16) < a.t16 ? 1u : 0u);
+    byte = (byte << 1) | ((w[i] & 0xFFFFu) < a.t16 ? 1u : 0u);
   }
   return byte;
 }
 
-__device__ __forceinline__ uint32_t merge_quad_bytes(uint32_t byte, int lane_in_quad) {
-  uint32_t w = byte << (8 * lane_in_quad);
-  w |= __shfl_xor(w, 1, kWave);
-  w |= __shfl_xor(w, 2, kWave);
-  return w;
-}
 
-// Number of leading key columns of row `row` that take part in the softmax.
-__device__ __forceinline__ int row_limit(int64_t row, const int32_t* key_len, int causal,
-                                         int64_t rows_per_batch, int Sq, int Sk) {
-  int limit = Sk;
-  if (key_len) {
-    const int kl = key_len[row / rows_per_batch];
-    limit = min(limit, max(kl, 0));
-  }
-  if (causal) {
-    const int i = static_cast<int>(row % Sq);
-    limit = min(limit, max(i + (Sk - Sq) + 1, 0));
-  }
+// Number of leading key columns of query row i that take part in the softmax.
+__device__ __forceinline__ int row_limit(int i, int key_limit, int causal, int Sq, int Sk) {
+  int limit = key_limit;
+  if (causal) limit = min(limit, max(i + (Sk - Sq) + 1, 0));
   return limit;
 }
 
+// Work unit = one "row set": the kThreads/LANES consecutive query rows of one [Sq, Sk] slice
+// that a workgroup handles at once (one row per lane group).  Workgroups walk the row sets
+// grid-stride and every lane group fetches its next row before it starts computing on the
+// current one, so the load latency of a row is hidden behind the arithmetic of the previous
+// one (softmax + Philox is ~35 VALU ops per element, about as long as the memory time).
 // WORDS: Sk % 32 == 0, mask written as whole words (4 lanes merge their bytes); otherwise
 // Sk % 8 == 0 and every lane writes its own byte of the little-endian word.
 template <typename T, int LANES, int CH, bool WORDS>
 __global__ __launch_bounds__(kThreads) void attn_fwd_kernel(
     const T* scores, const int32_t* __restrict__ key_len, int causal, T* probs,
-    T* __restrict__ out, uint32_t* __restrict__ keep_bits, int64_t rows, int64_t rows_per_batch,
-    int Sq, int Sk, float scale, RngArgs rng) {
+    T* __restrict__ out, uint32_t* __restrict__ keep_bits, int slices, int A, int Sq, int Sk,
+    float scale, RngArgs rng) {
   constexpr int kGroups = kThreads / LANES;
   const int g = threadIdx.x / LANES;
   const int t = threadIdx.x % LANES;
   const int chunks = Sk >> 3;
-  for (int64_t row = static_cast<int64_t>(blockIdx.x) * kGroups + g; row < rows;
-       row += static_cast<int64_t>(gridDim.x) * kGroups) {
-    const int limit = row_limit(row, key_len, causal, rows_per_batch, Sq, Sk);
-    const T* sr = scores + row * Sk;
-    float v[CH][8];
-    float mx = -INFINITY;
+  const int sets_per_slice = (Sq + kGroups - 1) / kGroups;
+  const int64_t total_sets = static_cast<int64_t>(slices) * sets_per_slice;
+
+  // limit (number of leading columns in the softmax) of this lane group's row in row set rs;
+  // -1 if the group has no row there
+  auto locate = [&](int64_t rs, int64_t& row) -> int {
+    const int slice = static_cast<int>(rs / sets_per_slice);
+    const int i = static_cast<int>(rs % sets_per_slice) * kGroups + g;
+    row = static_cast<int64_t>(slice) * Sq + i;
+    if (i >= Sq) return -1;
+    const int key_limit = key_len ? min(max(key_len[slice / A], 0), Sk) : Sk;
+    return row_limit(i, key_limit, causal, Sq, Sk);
+  };
+  auto fetch = [&](Raw<T> (&raw)[CH], int64_t row, int limit) {
 #pragma unroll
     for (int c = 0; c < CH; ++c) {
       const int col0 = (c * LANES + t) * 8;
-      if (col0 < limit) {  // also false for padding chunks (col0 >= Sk >= limit)
-        Store<T>::load8(sr + col0, v[c]);
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-          v[c][i] = (col0 + i < limit) ? v[c][i] : -INFINITY;
-          mx = fmaxf(mx, v[c][i]);
-        }
-      } else {
-#pragma unroll
-        for (int i = 0; i < 8; ++i) v[c][i] = -INFINITY;
-      }
+      if (col0 < limit) raw[c].load(scores + row * Sk + col0);
     }
-    mx = group_max<LANES>(mx);
-    const float shift = (mx == -INFINITY) ? 0.0f : mx * kLog2e;
-    float sum = 0.0f;
-#pragma unroll
-    for (int c = 0; c < CH; ++c) {
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const float e = __builtin_amdgcn_exp2f(fmaf(v[c][i], kLog2e, -shift));
-        v[c][i] = e;
-        sum += e;
-      }
+  };
+
+  int64_t rs = blockIdx.x;
+  if (rs >= total_sets) return;
+  int64_t row;
+  int limit = locate(rs, row);
+  Raw<T> cur[CH];
+  fetch(cur, row, limit);
+  for (; rs < total_sets; rs += gridDim.x) {
+    const int64_t rs_next = rs + gridDim.x;
+    int64_t row_next = 0;
+    int limit_next = -1;
+    Raw<T> nxt[CH];
+    if (rs_next < total_sets) {
+      limit_next = locate(rs_next, row_next);
+      fetch(nxt, row_next, limit_next);
     }
-    sum = group_sum<LANES>(sum);
-    const float rinv = (sum > 0.0f) ? 1.0f / sum : 0.0f;
-    const int64_t row_chunk0 = row * chunks;
+    if (limit >= 0) {
+      float v[CH][8];
+      float mx = -INFINITY;
 #pragma unroll
-    for (int c = 0; c < CH; ++c) {
-      const int ch = c * LANES + t;
-      uint32_t byte = 0;
-      if (ch < chunks) {
-        byte = keep_byte(static_cast<uint64_t>(row_chunk0 + ch), rng);
-        float p8[8], o8[8];
+      for (int c = 0; c < CH; ++c) {
+        const int col0 = (c * LANES + t) * 8;
+        if (col0 < limit) {
+          cur[c].unpack(v[c]);
+          if (col0 + 8 > limit) {  // the chunk the limit falls into
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-          p8[i] = Store<T>::round(v[c][i] * rinv);
-          o8[i] = ((byte >> i) & 1u) ? p8[i] * scale : 0.0f;
-        }
-        Store<T>::store8(probs + row * Sk + ch * 8, p8);
-        if (out) Store<T>::store8(out + row * Sk + ch * 8, o8);
-      }
-      if (WORDS) {
-        const uint32_t word = merge_quad_bytes(byte, t & 3);
-        if ((t & 3) == 0 && ch < chunks) keep_bits[(row_chunk0 + ch) >> 2] = word;
-      } else if (ch < chunks) {
-        uint8_t* kb = reinterpret_cast<uint8_t*>(keep_bits);
-        const int64_t gi = row_chunk0 + ch;
-        kb[gi] = static_cast<uint8_t>(byte);
-        if (gi == rows * chunks - 1) {  // zero the unused bytes of the last word
-          for (int64_t b = gi + 1; (b & 3) != 0; ++b) kb[b] = 0;
+            for (int k = 0; k < 8; ++k) v[c][k] = (col0 + k < limit) ? v[c][k] : -INFINITY;
+          }
+#pragma unroll
+          for (int k = 0; k < 8; ++k) mx = fmaxf(mx, v[c][k]);
         }
       }
+      mx = group_max<LANES>(mx);
+      const float shift = (mx == -INFINITY) ? 0.0f : mx * kLog2e;
+      float sum = 0.0f;
+#pragma unroll
+      for (int c = 0; c < CH; ++c) {
+        const int col0 = (c * LANES + t) * 8;
+        if (col0 < limit) {
+#pragma unroll
+          for (int k = 0; k < 8; ++k) {
+            const float e = __builtin_amdgcn_exp2f(fmaf(v[c][k], kLog2e, -shift));
+            v[c][k] = e;
+            sum += e;
+          }
+        } else {  // masked, or padding beyond the row
+#pragma unroll
+          for (int k = 0; k < 8; ++k) v[c][k] = 0.0f;
+        }
+      }
+      sum = group_sum<LANES>(sum);
+      const float rinv = (sum > 0.0f) ? __builtin_amdgcn_rcpf(sum) : 0.0f;
+      const int64_t row_chunk0 = row * chunks;
+#pragma unroll
+      for (int c = 0; c < CH; ++c) {
+        const int ch = c * LANES + t;
+        uint32_t byte = 0;
+        if (ch < chunks) {
+          byte = keep_byte(static_cast<uint64_t>(row_chunk0 + ch), rng);
+          float p8[8], o8[8];
+#pragma unroll
+          for (int k = 0; k < 8; ++k) {
+            p8[k] = Store<T>::round(v[c][k] * rinv);
+            o8[k] = ((byte >> k) & 1u) ? p8[k] * scale : 0.0f;
+          }
+          store8_stream<T>(probs + row * Sk + ch * 8, p8);
+          if (out) store8_stream<T>(out + row * Sk + ch * 8, o8);
+        }
+        if (WORDS) {
+          // the 4 lanes of a quad share a group, so they are all here together
+          const uint32_t word = merge_quad_bytes(byte, t & 3);
+          if ((t & 3) == 0 && ch < chunks) keep_bits[(row_chunk0 + ch) >> 2] = word;
+        } else if (ch < chunks) {
+          uint8_t* kb = reinterpret_cast<uint8_t*>(keep_bits);
+          const int64_t gi = row_chunk0 + ch;
+          kb[gi] = static_cast<uint8_t>(byte);
+          if (gi == static_cast<int64_t>(slices) * Sq * chunks - 1) {
+            for (int64_t b = gi + 1; (b & 3) != 0; ++b) kb[b] = 0;  // rest of the last word
+          }
+        }
+      }
     }
+#pragma unroll
+    for (int c = 0; c < CH; ++c) cur[c] = nxt[c];
+    row = row_next;
+    limit = limit_next;
   }
 }
 
@@ -172,8 +211,8 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_kernel(
     for (int c = 0; c < CH; ++c) {
       const int ch = c * LANES + t;
       if (ch < chunks) {
-        Store<T>::load8(dout + row * Sk + ch * 8, dp[c]);
-        Store<T>::load8(probs + row * Sk + ch * 8, pr[c]);
+        load8_stream<T>(dout + row * Sk + ch * 8, dp[c]);
+        load8_stream<T>(probs + row * Sk + ch * 8, pr[c]);
         const int64_t gi = row_chunk0 + ch;
         if (WORDS) bytes[c] = keep_bits[gi >> 2] >> (8 * static_cast<int>(gi & 3));
         else bytes[c] = reinterpret_cast<const uint8_t*>(keep_bits)[gi];
@@ -196,12 +235,12 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_kernel(
         float ds[8];
 #pragma unroll
         for (int i = 0; i < 8; ++i) ds[i] = pr[c][i] * (dp[c][i] - dot);
-        Store<T>::store8(dscores + row * Sk + ch * 8, ds);
+        store8_stream<T>(dscores + row * Sk + ch * 8, ds);
         if (out_re) {
           float o8[8];
 #pragma unroll
           for (int i = 0; i < 8; ++i) o8[i] = ((bytes[c] >> i) & 1u) ? pr[c][i] * scale : 0.0f;
-          Store<T>::store8(out_re + row * Sk + ch * 8, o8);
+          store8_stream<T>(out_re + row * Sk + ch * 8, o8);
         }
       }
     }
@@ -224,7 +263,8 @@ __global__ __launch_bounds__(kThreads) void attn_fwd_generic_kernel(
   constexpr int kWaves = kThreads / kWave;
   for (int64_t row = static_cast<int64_t>(blockIdx.x) * kWaves + wave; row < rows;
        row += static_cast<int64_t>(gridDim.x) * kWaves) {
-    const int limit = row_limit(row, key_len, causal, rows_per_batch, Sq, Sk);
+    const int key_limit = key_len ? min(max(key_len[row / rows_per_batch], 0), Sk) : Sk;
+    const int limit = row_limit(static_cast<int>(row % Sq), key_limit, causal, Sq, Sk);
     const T* sr = scores + row * Sk;
     float mx = -INFINITY;
     for (int j = lane; j < limit; j += kWave) mx = fmaxf(mx, Store<T>::load1(sr + j));
@@ -295,16 +335,16 @@ struct Shape {
   int ch;
 };
 
-// Aim at 4 chunks per lane (enough bytes in flight per lane, few butterfly steps): the
-// narrowest power-of-two group of at least 4 lanes that covers the row with <= 4 chunks per
-// lane, else 64 lanes with 6 or 8.  ch == 0: row too long for registers.
+// One chunk per lane while the row fits in a wave (every access of a wave is then one
+// contiguous run of 16-byte pieces), more chunks per lane for longer rows.
+// ch == 0: row too long for registers.
 Shape pick_shape(int chunks) {
   int lanes = 4;
-  while (lanes < 64 && lanes * 4 < chunks) lanes <<= 1;
+  while (lanes < 64 && lanes < chunks) lanes <<= 1;
   const int need = (chunks + lanes - 1) / lanes;
   static const int allowed[] = {1, 2, 3, 4, 6, 8};
   for (int a : allowed)
-    if (a >= need) return {lanes, (lanes == 4 || a >= 3) ? a : 3};
+    if (a >= need) return {lanes, a};
   return {0, 0};
 }
 
@@ -321,15 +361,11 @@ int row_grid(int64_t rows, int lanes, int blocks_per_cu) {
 #define TEMPO_ATTN_DISPATCH(LAUNCH)                                                        \
   switch (sh.lanes * 100 + sh.ch) {                                                        \
     case 401: LAUNCH(4, 1); break;                                                         \
-    case 402: LAUNCH(4, 2); break;                                                         \
-    case 403: LAUNCH(4, 3); break;                                                         \
-    case 404: LAUNCH(4, 4); break;                                                         \
-    case 803: LAUNCH(8, 3); break;                                                         \
-    case 804: LAUNCH(8, 4); break;                                                         \
-    case 1603: LAUNCH(16, 3); break;                                                       \
-    case 1604: LAUNCH(16, 4); break;                                                       \
-    case 3203: LAUNCH(32, 3); break;                                                       \
-    case 3204: LAUNCH(32, 4); break;                                                       \
+    case 801: LAUNCH(8, 1); break;                                                         \
+    case 1601: LAUNCH(16, 1); break;                                                       \
+    case 3201: LAUNCH(32, 1); break;                                                       \
+    case 6401: LAUNCH(64, 1); break;                                                       \
+    case 6402: LAUNCH(64, 2); break;                                                       \
     case 6403: LAUNCH(64, 3); break;                                                       \
     case 6404: LAUNCH(64, 4); break;                                                       \
     case 6406: LAUNCH(64, 6); break;                                                       \
@@ -354,13 +390,17 @@ tempo_status launch_attn_fwd(const void* scores, const int32_t* key_len, int cau
   rng.t16 = (p == 0.0f) ? 65536u : static_cast<uint32_t>(t);  // floor for t >= 0
   const int bpc = tune_get(kTuneAttnFwdBlocksPerCu);
   Shape sh = pick_shape(static_cast<int>(Sk / 8));
-  if (Sk % 8 == 0 && sh.ch != 0) {
-    const int grid = row_grid(rows, sh.lanes, bpc);
+  if (Sk % 8 == 0 && sh.ch != 0 && B * A <= INT32_MAX) {
+    const int slices = static_cast<int>(B * A);
+    const int groups = kThreads / sh.lanes;
+    const int64_t total_sets = static_cast<int64_t>(slices) * ((Sq + groups - 1) / groups);
+    const int64_t cap = static_cast<int64_t>(compute_units()) * bpc;
+    const dim3 grid(static_cast<unsigned>(total_sets < cap ? total_sets : cap));
     const bool words = (Sk % 32 == 0);
 #define TEMPO_LAUNCH_T(T, L, C, W)                                                           \
-  hipLaunchKernelGGL((attn_fwd_kernel<T, L, C, W>), dim3(grid), dim3(kThreads), 0, st,       \
+  hipLaunchKernelGGL((attn_fwd_kernel<T, L, C, W>), grid, dim3(kThreads), 0, st,             \
                      static_cast<const T*>(scores), key_len, causal, static_cast<T*>(probs), \
-                     static_cast<T*>(out), keep_bits, rows, rows_per_batch,                  \
+                     static_cast<T*>(out), keep_bits, slices, static_cast<int>(A),           \
                      static_cast<int>(Sq), static_cast<int>(Sk), scale, rng)
 #define TEMPO_LAUNCH(L, C)                                                                   \
   do {                                                                                       \

@@ -15,7 +15,6 @@ namespace tempo {
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kUnroll = 2;  // chunks in flight per lane and loop trip
 
 template <int KIND>
 struct GeluConst;
@@ -103,140 +102,396 @@ __device__ __forceinline__ void load_table(f32x4* lds, const uint32_t (*src)[4])
   __syncthreads();
 }
 
-// Merge the 8-bit chunk masks of 4 adjacent lanes into the 32-bit word they share.
-__device__ __forceinline__ uint32_t merge_quad_bytes(uint32_t byte, int lane_in_quad) {
-  uint32_t w = byte << (8 * lane_in_quad);
-  w |= __shfl_xor(w, 1, kWave);
-  w |= __shfl_xor(w, 2, kWave);
-  return w;
-}
 
-template <typename T, int KIND>
+// Work decomposition (both kernels): workgroup b owns the contiguous tile of kThreads*K chunks
+// starting at chunk b*kThreads*K; chunk k of lane t is tile_base + k*kThreads + t, so each
+// access of a wave is one contiguous 1 KiB (bf16) run, workgroups are short-lived, and the
+// whole grid sweeps memory front to back.  All of a lane's loads are issued before the table
+// is staged into LDS, so the two latencies overlap.
+template <typename T, int KIND, int K>
 __global__ __launch_bounds__(kThreads) void gelu_fwd_kernel(const T* x, T* y,  // may alias
                                                             uint32_t* __restrict__ mask,
                                                             int64_t n) {
   __shared__ f32x4 tab[KIND == TEMPO_GELU_ERF ? TEMPO_GELU_FWD_ROWS : 1];
-  if (KIND == TEMPO_GELU_ERF) load_table<TEMPO_GELU_FWD_ROWS>(tab, tempo_gelu_fwd_table_erf);
   const float xstar = as_f32(GeluConst<KIND>::xstar);
-  const int64_t n_chunks = (n + 7) >> 3;
-  const int64_t threads = static_cast<int64_t>(gridDim.x) * kThreads;
   const int lane = threadIdx.x & (kWave - 1);
-  const int64_t gtid = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
-  // trip count is uniform over a wave: lanes past the end run with everything guarded off
-  for (int64_t q0 = gtid; q0 - lane < n_chunks; q0 += threads * kUnroll) {
-    float v[kUnroll][8];
+  const int64_t q_base = static_cast<int64_t>(blockIdx.x) * (kThreads * K) + threadIdx.x;
+  float v[K][8];
 #pragma unroll
-    for (int u = 0; u < kUnroll; ++u) {
-      const int64_t q = q0 + u * threads;
-      const int64_t left = n - q * 8;
-      if (left > 0) {
-        load8_guarded<T>(x + q * 8, left, v[u], -1.0e30f);
-      } else {
+  for (int k = 0; k < K; ++k) {
+    const int64_t q = q_base + k * kThreads;
+    const int64_t left = n - q * 8;
+    if (left > 0) {
+      load8_guarded<T>(x + q * 8, left, v[k], -1.0e30f);
+    } else {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) v[u][i] = -1.0e30f;
-      }
+      for (int i = 0; i < 8; ++i) v[k][i] = -1.0e30f;
     }
+  }
+  if (KIND == TEMPO_GELU_ERF) load_table<TEMPO_GELU_FWD_ROWS>(tab, tempo_gelu_fwd_table_erf);
 #pragma unroll
-    for (int u = 0; u < kUnroll; ++u) {
-      const int64_t q = q0 + u * threads;
-      const int64_t left = n - q * 8;
-      uint32_t byte = 0;
-      float r[8];
+  for (int k = 0; k < K; ++k) {
+    const int64_t q = q_base + k * kThreads;
+    const int64_t left = n - q * 8;
+    uint32_t byte = 0;
+    float r[8];
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const float xv = v[u][i];
-        byte |= (xv >= xstar ? 1u : 0u) << i;
-        r[i] = (KIND == TEMPO_GELU_ERF) ? gelu_erf_value(xv, tab) : gelu_tanh_value(xv);
-      }
-      const uint32_t word = merge_quad_bytes(byte, lane & 3);
-      if (left > 0) store8_guarded<T>(y + q * 8, left, r);
-      if ((lane & 3) == 0 && left > 0) mask[q >> 2] = word;
+    for (int i = 0; i < 8; ++i) {
+      const float xv = v[k][i];
+      byte |= (xv >= xstar ? 1u : 0u) << i;
+      r[i] = (KIND == TEMPO_GELU_ERF) ? gelu_erf_value(xv, tab) : gelu_tanh_value(xv);
     }
+    // every lane of the wave takes part in the merge; absent chunks contribute zero bits
+    const uint32_t word = merge_quad_bytes(byte, lane & 3);
+    if (left > 0) store8_guarded<T>(y + q * 8, left, r);
+    if ((lane & 3) == 0 && left > 0) mask[q >> 2] = word;
   }
 }
 
-template <typename T, int KIND>
+template <typename T, int KIND, int K>
 __global__ __launch_bounds__(kThreads) void gelu_bwd_kernel(const T* dy,  // may alias dx
                                                             const T* __restrict__ y,
                                                             const uint32_t* __restrict__ mask,
                                                             T* dx, int64_t n) {
   __shared__ f32x4 tab[TEMPO_GELU_BWD_ROWS];
-  load_table<TEMPO_GELU_BWD_ROWS>(tab, GeluConst<KIND>::bwd_table());
-  const int64_t n_chunks = (n + 7) >> 3;
-  const int64_t threads = static_cast<int64_t>(gridDim.x) * kThreads;
-  const int64_t gtid = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
-  for (int64_t q0 = gtid; q0 < n_chunks; q0 += threads * kUnroll) {
-    float g[kUnroll][8], o[kUnroll][8];
-    uint32_t w[kUnroll];
+  const int64_t q_base = static_cast<int64_t>(blockIdx.x) * (kThreads * K) + threadIdx.x;
+  float g[K][8], o[K][8];
+  uint32_t w[K];
 #pragma unroll
-    for (int u = 0; u < kUnroll; ++u) {
-      const int64_t q = q0 + u * threads;
-      const int64_t left = n - q * 8;
-      w[u] = 0;
-      if (left > 0) {
-        load8_guarded<T>(dy + q * 8, left, g[u], 0.0f);
-        load8_guarded<T>(y + q * 8, left, o[u], 0.0f);
-        w[u] = mask[q >> 2];
-      }
+  for (int k = 0; k < K; ++k) {
+    const int64_t q = q_base + k * kThreads;
+    const int64_t left = n - q * 8;
+    w[k] = 0;
+    if (left > 0) {
+      load8_guarded<T>(dy + q * 8, left, g[k], 0.0f);
+      load8_guarded<T>(y + q * 8, left, o[k], 0.0f);
+      w[k] = __builtin_nontemporal_load(mask + (q >> 2));
     }
+  }
+  load_table<TEMPO_GELU_BWD_ROWS>(tab, GeluConst<KIND>::bwd_table());
 #pragma unroll
-    for (int u = 0; u < kUnroll; ++u) {
-      const int64_t q = q0 + u * threads;
+  for (int k = 0; k < K; ++k) {
+    const int64_t q = q_base + k * kThreads;
+    const int64_t left = n - q * 8;
+    if (left <= 0) continue;
+    const uint32_t byte = w[k] >> (8 * static_cast<int>(q & 3));
+    float r[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const bool right = (byte >> i) & 1u;
+      r[i] = g[k][i] * gelu_composite<KIND>(o[k][i], right, tab);
+    }
+    store8_guarded<T>(dx + q * 8, left, r);
+  }
+}
+
+// ---- bfloat16 storage: per-pattern lookup ------------------------------------------------
+// A bf16 value has 2^16 bit patterns, so GELU ("Phi" factor) and the backward composite are
+// tabulated per pattern (tables generated offline, float32 entries) and staged into LDS:
+// 16 KiB forward, 32 KiB backward.  Per element this leaves a handful of integer ops, one
+// ds_read_b32 and one multiply, which keeps the vector ALU far below the memory time (the
+// cubic path above costs ~40 VALU ops per element, more than a bf16 element's share of HBM
+// time).  Workgroups of 1024 lanes own contiguous tiles of 1024*K chunks.
+constexpr int kLutThreads = 1024;
+
+template <int KIND>
+struct GeluLut;
+template <>
+struct GeluLut<TEMPO_GELU_ERF> {
+  __device__ static const uint32_t* fwd() { return tempo_gelu_lut_fwd_erf; }
+  __device__ static const uint32_t* bwd() { return tempo_gelu_lut_bwd_erf; }
+};
+template <>
+struct GeluLut<TEMPO_GELU_TANH> {
+  __device__ static const uint32_t* fwd() { return tempo_gelu_lut_fwd_tanh; }
+  __device__ static const uint32_t* bwd() { return tempo_gelu_lut_bwd_tanh; }
+};
+
+template <int WORDS>
+__device__ __forceinline__ void stage_lut(uint32_t* lds, const uint32_t* src) {
+  static_assert(WORDS % (4 * kLutThreads) == 0, "whole 16-byte pieces per lane");
+#pragma unroll
+  for (int i = 0; i < WORDS / (4 * kLutThreads); ++i) {
+    const int j = (i * kLutThreads + threadIdx.x) * 4;
+    *reinterpret_cast<u32x4*>(lds + j) = *reinterpret_cast<const u32x4*>(src + j);
+  }
+  __syncthreads();
+}
+
+typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
+typedef short i16x2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ uint32_t lds_word(const uint32_t* lut, uint32_t byte_offset) {
+  return *reinterpret_cast<const uint32_t*>(reinterpret_cast<const char*>(lut) + byte_offset);
+}
+
+// LDS byte offsets of the forward entries of the two bf16 values packed in w (packed 16-bit
+// integer ops: one instruction serves both halves).  Entry index = key | sign << 11 with
+// key = clamp(pattern(|x|) - LUT_LO, 0, LUT_N - 1).
+__device__ __forceinline__ uint32_t lut_fwd_offsets(uint32_t w) {
+  const u16x2 lo = {TEMPO_GELU_LUT_LO, TEMPO_GELU_LUT_LO};
+  const u16x2 top = {TEMPO_GELU_LUT_N - 1, TEMPO_GELU_LUT_N - 1};
+  u16x2 k = __builtin_bit_cast(u16x2, w & 0x7FFF7FFFu);
+  k = __builtin_elementwise_min(__builtin_elementwise_sub_sat(k, lo), top);
+  const uint32_t idx = ((w >> 4) & 0x08000800u) | __builtin_bit_cast(uint32_t, k);
+  const u16x2 two = {2, 2};
+  return __builtin_bit_cast(uint32_t, static_cast<u16x2>(__builtin_bit_cast(u16x2, idx) << two));
+}
+
+// Same for the backward entries; mm holds the two mask bits at bit 0 and bit 16.  The left
+// branch (mask bit 0) looks LUT_LEFT_SHIFT patterns lower.  Index = m << 12 | sign << 11 | key.
+__device__ __forceinline__ uint32_t lut_bwd_offsets(uint32_t w, uint32_t mm) {
+  constexpr short lo_r = TEMPO_GELU_LUT_LO;  // window of the right branch
+  const i16x2 shift = {TEMPO_GELU_LUT_LEFT_SHIFT, TEMPO_GELU_LUT_LEFT_SHIFT};
+  const i16x2 lo = {lo_r, lo_r};
+  const i16x2 hi = {lo_r + TEMPO_GELU_LUT_N - 1, lo_r + TEMPO_GELU_LUT_N - 1};
+  const i16x2 one = {1, 1};
+  // a + (1 - m) * shift, then the right branch's window
+  i16x2 a = __builtin_bit_cast(i16x2, w & 0x7FFF7FFFu);
+  a = a + (one - __builtin_bit_cast(i16x2, mm)) * shift;
+  a = __builtin_elementwise_min(__builtin_elementwise_max(a, lo), hi) - lo;
+  const uint32_t idx = ((w >> 4) & 0x08000800u) | (mm << 12) | __builtin_bit_cast(uint32_t, a);
+  const u16x2 two = {2, 2};
+  return __builtin_bit_cast(uint32_t, static_cast<u16x2>(__builtin_bit_cast(u16x2, idx) << two));
+}
+
+// One chunk (8 bf16 in 4 words) of the forward: y words and the 8 mask bits.
+__device__ __forceinline__ void gelu_fwd_lut_chunk(const u32x4 w, const uint32_t* lut, u32x4& yw,
+                                                   uint32_t& byte) {
+  const uint32_t in[4] = {w.x, w.y, w.z, w.w};
+  uint32_t out[4];
+  uint32_t acc = 0;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const uint32_t off = lut_fwd_offsets(in[j]);
+    const uint32_t e0 = lds_word(lut, off & 0xFFFFu);
+    const uint32_t e1 = lds_word(lut, off >> 16);
+    // shift the mask bit (entry LSB) of each element into the top of acc
+    acc = __builtin_amdgcn_alignbit(e0, acc, 1);
+    acc = __builtin_amdgcn_alignbit(e1, acc, 1);
+    out[j] = pack_bf16(bf16_lo(in[j]) * as_f32(e0), bf16_hi(in[j]) * as_f32(e1));
+  }
+  yw = u32x4{out[0], out[1], out[2], out[3]};
+  byte = acc >> 24;
+}
+
+__device__ __forceinline__ u32x4 gelu_bwd_lut_chunk(const u32x4 wy, const u32x4 wd, uint32_t byte,
+                                                    const uint32_t* lut) {
+  const uint32_t iy[4] = {wy.x, wy.y, wy.z, wy.w};
+  const uint32_t id[4] = {wd.x, wd.y, wd.z, wd.w};
+  uint32_t out[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const uint32_t mm = (((byte >> (2 * j)) & 3u) * 0x8001u) & 0x00010001u;
+    const uint32_t off = lut_bwd_offsets(iy[j], mm);
+    const float y0 = bf16_lo(iy[j]), y1 = bf16_hi(iy[j]);
+    float d0 = as_f32(lds_word(lut, off & 0xFFFFu));
+    float d1 = as_f32(lds_word(lut, off >> 16));
+    d0 = (y0 != y0) ? y0 : d0;  // NaN in y propagates
+    d1 = (y1 != y1) ? y1 : d1;
+    out[j] = pack_bf16(bf16_lo(id[j]) * d0, bf16_hi(id[j]) * d1);
+  }
+  return u32x4{out[0], out[1], out[2], out[3]};
+}
+
+// Partial chunk at the very end of the tensor: gather / scatter element by element.
+__device__ __forceinline__ u32x4 load_tail_bf16(const bf16_t* p, int64_t left, uint32_t fill) {
+  uint32_t t[4] = {fill, fill, fill, fill};
+  for (int i = 0; i < left; ++i) {
+    const uint32_t b = p[i].bits;
+    t[i >> 1] = (i & 1) ? ((t[i >> 1] & 0x0000FFFFu) | (b << 16)) : ((t[i >> 1] & 0xFFFF0000u) | b);
+  }
+  return u32x4{t[0], t[1], t[2], t[3]};
+}
+__device__ __forceinline__ void store_tail_bf16(bf16_t* p, int64_t left, const u32x4 v) {
+  const uint32_t t[4] = {v.x, v.y, v.z, v.w};
+  for (int i = 0; i < left; ++i)
+    p[i].bits = static_cast<uint16_t>((i & 1) ? (t[i >> 1] >> 16) : (t[i >> 1] & 0xFFFFu));
+}
+
+constexpr uint32_t kAbsentX = 0xF149F149u;  // two bf16 of about -2.5e30: mask bit 0
+
+template <int KIND, int K>
+__global__ __launch_bounds__(kLutThreads) void gelu_fwd_lut_kernel(const bf16_t* x, bf16_t* y,
+                                                                   uint32_t* __restrict__ mask,
+                                                                   int64_t n) {
+  __shared__ uint32_t lut[2 * TEMPO_GELU_LUT_N];
+  const int lane = threadIdx.x & (kWave - 1);
+  const int64_t q_base = static_cast<int64_t>(blockIdx.x) * (kLutThreads * K) + threadIdx.x;
+  const bool full = (static_cast<int64_t>(blockIdx.x) + 1) * (kLutThreads * K) * 8 <= n;
+  u32x4 w[K];
+  if (full) {  // whole tile inside the tensor: straight-line loads
+#pragma unroll
+    for (int k = 0; k < K; ++k) w[k] = ldg_stream(x + (q_base + k * kLutThreads) * 8);
+  } else {
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+      const int64_t q = q_base + k * kLutThreads;
       const int64_t left = n - q * 8;
-      if (left <= 0) continue;
-      const uint32_t byte = w[u] >> (8 * static_cast<int>(q & 3));
-      float r[8];
+      w[k] = u32x4{kAbsentX, kAbsentX, kAbsentX, kAbsentX};
+      if (left >= 8) w[k] = ldg_stream(x + q * 8);
+      else if (left > 0) w[k] = load_tail_bf16(x + q * 8, left, kAbsentX);
+    }
+  }
+  stage_lut<2 * TEMPO_GELU_LUT_N>(lut, GeluLut<KIND>::fwd());
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const bool right = (byte >> i) & 1u;
-        r[i] = g[u][i] * gelu_composite<KIND>(o[u][i], right, tab);
-      }
-      store8_guarded<T>(dx + q * 8, left, r);
+  for (int k = 0; k < K; ++k) {
+    const int64_t q = q_base + k * kLutThreads;
+    u32x4 yw;
+    uint32_t byte;
+    gelu_fwd_lut_chunk(w[k], lut, yw, byte);
+    // every lane of the wave takes part in the merge; absent chunks contribute zero bits
+    const uint32_t word = merge_quad_bytes(byte, lane & 3);
+    if (full) {
+      stg_stream(y + q * 8, yw);
+      if ((lane & 3) == 0) mask[q >> 2] = word;
+    } else {
+      const int64_t left = n - q * 8;
+      if (left >= 8) stg_stream(y + q * 8, yw);
+      else if (left > 0) store_tail_bf16(y + q * 8, left, yw);
+      if ((lane & 3) == 0 && left > 0) mask[q >> 2] = word;
     }
   }
 }
 
-int stream_grid(int64_t n, int blocks_per_cu) {
-  const int64_t n_chunks = (n + 7) / 8;
-  const int64_t want = (n_chunks + kThreads * kUnroll - 1) / (kThreads * kUnroll);
-  const int64_t cap = static_cast<int64_t>(compute_units()) * blocks_per_cu;
-  return static_cast<int>(want < cap ? want : cap);
+template <int KIND, int K>
+__global__ __launch_bounds__(kLutThreads) void gelu_bwd_lut_kernel(const bf16_t* dy,
+                                                                   const bf16_t* __restrict__ y,
+                                                                   const uint32_t* __restrict__ mask,
+                                                                   bf16_t* dx, int64_t n) {
+  __shared__ uint32_t lut[4 * TEMPO_GELU_LUT_N];
+  const int64_t q_base = static_cast<int64_t>(blockIdx.x) * (kLutThreads * K) + threadIdx.x;
+  const bool full = (static_cast<int64_t>(blockIdx.x) + 1) * (kLutThreads * K) * 8 <= n;
+  u32x4 wy[K], wd[K];
+  uint32_t mw[K];
+  if (full) {
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+      const int64_t q = q_base + k * kLutThreads;
+      wd[k] = ldg_stream(dy + q * 8);
+      wy[k] = ldg_stream(y + q * 8);
+      mw[k] = __builtin_nontemporal_load(mask + (q >> 2));
+    }
+  } else {
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+      const int64_t q = q_base + k * kLutThreads;
+      const int64_t left = n - q * 8;
+      wy[k] = wd[k] = u32x4{0u, 0u, 0u, 0u};
+      mw[k] = 0;
+      if (left >= 8) {
+        wd[k] = ldg_stream(dy + q * 8);
+        wy[k] = ldg_stream(y + q * 8);
+      } else if (left > 0) {
+        wd[k] = load_tail_bf16(dy + q * 8, left, 0u);
+        wy[k] = load_tail_bf16(y + q * 8, left, 0u);
+      }
+      if (left > 0) mw[k] = mask[q >> 2];
+    }
+  }
+  stage_lut<4 * TEMPO_GELU_LUT_N>(lut, GeluLut<KIND>::bwd());
+#pragma unroll
+  for (int k = 0; k < K; ++k) {
+    const int64_t q = q_base + k * kLutThreads;
+    const uint32_t byte = mw[k] >> (8 * static_cast<int>(q & 3));
+    const u32x4 r = gelu_bwd_lut_chunk(wy[k], wd[k], byte, lut);
+    if (full) {
+      stg_stream(dx + q * 8, r);
+    } else {
+      const int64_t left = n - q * 8;
+      if (left >= 8) stg_stream(dx + q * 8, r);
+      else if (left > 0) store_tail_bf16(dx + q * 8, left, r);
+    }
+  }
 }
+
+int lut_grid(int64_t n, int k) {
+  const int64_t n_chunks = (n + 7) / 8;
+  const int64_t per_block = static_cast<int64_t>(kLutThreads) * k;
+  return static_cast<int>((n_chunks + per_block - 1) / per_block);
+}
+
+
+int tile_grid(int64_t n, int k) {
+  const int64_t n_chunks = (n + 7) / 8;
+  const int64_t per_block = static_cast<int64_t>(kThreads) * k;
+  return static_cast<int>((n_chunks + per_block - 1) / per_block);
+}
+
+int pick_k(int tuned) { return tuned >= 4 ? 4 : (tuned >= 2 ? 2 : 1); }
 
 }  // namespace
 
+#define TEMPO_GELU_DISPATCH(KERNEL, ...)                                                     \
+  do {                                                                                       \
+    const int grid = tile_grid(n, k);                                                        \
+    if (dt == TEMPO_F32) {                                                                   \
+      if (kind == TEMPO_GELU_ERF) {                                                          \
+        if (k == 1) TEMPO_GO(KERNEL, float, TEMPO_GELU_ERF, 1, __VA_ARGS__);                 \
+        else if (k == 2) TEMPO_GO(KERNEL, float, TEMPO_GELU_ERF, 2, __VA_ARGS__);            \
+        else TEMPO_GO(KERNEL, float, TEMPO_GELU_ERF, 4, __VA_ARGS__);                        \
+      } else {                                                                               \
+        if (k == 1) TEMPO_GO(KERNEL, float, TEMPO_GELU_TANH, 1, __VA_ARGS__);                \
+        else if (k == 2) TEMPO_GO(KERNEL, float, TEMPO_GELU_TANH, 2, __VA_ARGS__);           \
+        else TEMPO_GO(KERNEL, float, TEMPO_GELU_TANH, 4, __VA_ARGS__);                       \
+      }                                                                                      \
+    } else {                                                                                 \
+      if (kind == TEMPO_GELU_ERF) {                                                          \
+        if (k == 1) TEMPO_GO(KERNEL, bf16_t, TEMPO_GELU_ERF, 1, __VA_ARGS__);                \
+        else if (k == 2) TEMPO_GO(KERNEL, bf16_t, TEMPO_GELU_ERF, 2, __VA_ARGS__);           \
+        else TEMPO_GO(KERNEL, bf16_t, TEMPO_GELU_ERF, 4, __VA_ARGS__);                       \
+      } else {                                                                               \
+        if (k == 1) TEMPO_GO(KERNEL, bf16_t, TEMPO_GELU_TANH, 1, __VA_ARGS__);               \
+        else if (k == 2) TEMPO_GO(KERNEL, bf16_t, TEMPO_GELU_TANH, 2, __VA_ARGS__);          \
+        else TEMPO_GO(KERNEL, bf16_t, TEMPO_GELU_TANH, 4, __VA_ARGS__);                      \
+      }                                                                                      \
+    }                                                                                        \
+  } while (0)
+
+#define TEMPO_LUT_DISPATCH(KERNEL, ...)                                                       \
+  do {                                                                                       \
+    const int grid = lut_grid(n, k);                                                         \
+    if (kind == TEMPO_GELU_ERF) {                                                            \
+      if (k == 1) hipLaunchKernelGGL((KERNEL<TEMPO_GELU_ERF, 1>), dim3(grid), dim3(kLutThreads), 0, st, __VA_ARGS__);       \
+      else if (k == 2) hipLaunchKernelGGL((KERNEL<TEMPO_GELU_ERF, 2>), dim3(grid), dim3(kLutThreads), 0, st, __VA_ARGS__);  \
+      else hipLaunchKernelGGL((KERNEL<TEMPO_GELU_ERF, 4>), dim3(grid), dim3(kLutThreads), 0, st, __VA_ARGS__);              \
+    } else {                                                                                 \
+      if (k == 1) hipLaunchKernelGGL((KERNEL<TEMPO_GELU_TANH, 1>), dim3(grid), dim3(kLutThreads), 0, st, __VA_ARGS__);      \
+      else if (k == 2) hipLaunchKernelGGL((KERNEL<TEMPO_GELU_TANH, 2>), dim3(grid), dim3(kLutThreads), 0, st, __VA_ARGS__); \
+      else hipLaunchKernelGGL((KERNEL<TEMPO_GELU_TANH, 4>), dim3(grid), dim3(kLutThreads), 0, st, __VA_ARGS__);             \
+    }                                                                                        \
+  } while (0)
+
 tempo_status launch_gelu_fwd(const void* x, void* y, uint32_t* mask, int64_t n, tempo_dtype dt,
                              tempo_gelu_kind kind, hipStream_t st) {
-  const int grid = stream_grid(n, tune_get(kTuneGeluFwdBlocksPerCu));
-#define TEMPO_LAUNCH(T, K)                                                                   \
-  hipLaunchKernelGGL((gelu_fwd_kernel<T, K>), dim3(grid), dim3(kThreads), 0, st,             \
-                     static_cast<const T*>(x), static_cast<T*>(y), mask, n)
-  if (dt == TEMPO_F32) {
-    if (kind == TEMPO_GELU_ERF) TEMPO_LAUNCH(float, TEMPO_GELU_ERF);
-    else TEMPO_LAUNCH(float, TEMPO_GELU_TANH);
-  } else {
-    if (kind == TEMPO_GELU_ERF) TEMPO_LAUNCH(bf16_t, TEMPO_GELU_ERF);
-    else TEMPO_LAUNCH(bf16_t, TEMPO_GELU_TANH);
+  const int k = pick_k(tune_get(kTuneGeluFwdChunks));
+  if (dt == TEMPO_BF16) {
+    TEMPO_LUT_DISPATCH(gelu_fwd_lut_kernel, static_cast<const bf16_t*>(x), static_cast<bf16_t*>(y),
+                       mask, n);
+    return launch_status();
   }
-#undef TEMPO_LAUNCH
+#define TEMPO_GO(KERNEL, T, KIND, K, ...)                                                    \
+  hipLaunchKernelGGL((KERNEL<T, KIND, K>), dim3(grid), dim3(kThreads), 0, st,                \
+                     static_cast<const T*>(x), static_cast<T*>(y), mask, n)
+  TEMPO_GELU_DISPATCH(gelu_fwd_kernel, 0);
+#undef TEMPO_GO
   return launch_status();
 }
 
 tempo_status launch_gelu_bwd(const void* dy, const void* y, const uint32_t* mask, void* dx,
                              int64_t n, tempo_dtype dt, tempo_gelu_kind kind, hipStream_t st) {
-  const int grid = stream_grid(n, tune_get(kTuneGeluBwdBlocksPerCu));
-#define TEMPO_LAUNCH(T, K)                                                                   \
-  hipLaunchKernelGGL((gelu_bwd_kernel<T, K>), dim3(grid), dim3(kThreads), 0, st,             \
+  const int k = pick_k(tune_get(kTuneGeluBwdChunks));
+  if (dt == TEMPO_BF16) {
+    TEMPO_LUT_DISPATCH(gelu_bwd_lut_kernel, static_cast<const bf16_t*>(dy),
+                       static_cast<const bf16_t*>(y), mask, static_cast<bf16_t*>(dx), n);
+    return launch_status();
+  }
+#define TEMPO_GO(KERNEL, T, KIND, K, ...)                                                    \
+  hipLaunchKernelGGL((KERNEL<T, KIND, K>), dim3(grid), dim3(kThreads), 0, st,                \
                      static_cast<const T*>(dy), static_cast<const T*>(y), mask,              \
                      static_cast<T*>(dx), n)
-  if (dt == TEMPO_F32) {
-    if (kind == TEMPO_GELU_ERF) TEMPO_LAUNCH(float, TEMPO_GELU_ERF);
-    else TEMPO_LAUNCH(float, TEMPO_GELU_TANH);
-  } else {
-    if (kind == TEMPO_GELU_ERF) TEMPO_LAUNCH(bf16_t, TEMPO_GELU_ERF);
-    else TEMPO_LAUNCH(bf16_t, TEMPO_GELU_TANH);
-  }
-#undef TEMPO_LAUNCH
+  TEMPO_GELU_DISPATCH(gelu_bwd_kernel, 0);
+#undef TEMPO_GO
   return launch_status();
 }
 

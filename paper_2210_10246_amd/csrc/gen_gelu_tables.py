@@ -24,6 +24,17 @@ Chebyshev basis per piece.  The script prints the worst absolute error of each r
 Forward (erf kind) table: GELU(x) itself as cubics on uniform pieces of width 1/16 in
 x over [-8, 8); outside, GELU(x) = x (right) or -0 (left) to below 1e-14.
 
+bfloat16 lookup tables.  A bfloat16 input has only 2^16 bit patterns, so for bf16 storage
+both GELU and the backward composite are tabulated per pattern instead of being evaluated:
+  forward   F[sign][k] = "Phi"(x) as float32 (y = x * F), k = pattern(|x|) - LUT_LO clamped to
+            [0, 2047] with LUT_LO = pattern(2^-12): 16 octaves [2^-12, 16); below, Phi is 1/2 to
+            2e-4, above it is 0 or 1.  The lowest mantissa bit of every entry is replaced by
+            the mask bit [x >= x*] of that pattern (a 1e-7 relative change of the value).
+  backward  D[m][sign][k] = d(y, m) as float32, same key; the left branch (m=0) shifts the key
+            window down by 6 octaves to [2^-18, 2^-2) where d still matters (|d| < 5e-5 below).
+            m=0 with y >= 0 is all zero (cannot come from a forward).
+The table entries need d at given y: here (and only here) x is found by bisection.
+
 This file shares nothing with the CPU checker: its GELU, derivative and minimum search
 are written here with the math/scipy primitives only.
 """
@@ -162,6 +173,69 @@ def fwd_table():
     return rows, worst
 
 
+LUT_LO = 0x3980            # bf16 pattern of 2^-12
+LUT_N = 2048               # patterns per (sign) sub-table: 16 octaves x 128
+LUT_LEFT_SHIFT = 0x300     # the left branch looks 6 octaves lower
+
+
+def bf16_value(pattern):
+    return np.array(pattern, dtype=np.uint32).astype(np.uint32).__lshift__(16).view(np.float32).astype(np.float64)
+
+
+def invert(y, right, kind, xs):
+    """x with G(x) = y on one branch, bisection in float64."""
+    y = np.asarray(y, dtype=np.float64)
+    lo = np.full(y.shape, xs if right else -64.0)
+    hi = np.maximum(y, 0.0) + 1.0 if right else np.full(y.shape, xs)
+    for _ in range(200):
+        mid = 0.5 * (lo + hi)
+        g = g_val(mid, kind)
+        up = (g < y) if right else (g > y)
+        lo = np.where(up, mid, lo)
+        hi = np.where(up, hi, mid)
+    return 0.5 * (lo + hi)
+
+
+def lut_tables(kind):
+    xs, ys = minimum(kind)
+    xs32 = float(np.float32(xs))
+    k = np.arange(LUT_N, dtype=np.uint32)
+    mag = bf16_value(LUT_LO + k)
+    fwd = np.zeros((2, LUT_N), dtype=np.uint32)
+    for sgn in (0, 1):
+        x = mag if sgn == 0 else -mag
+        with np.errstate(over="ignore", invalid="ignore"):
+            phi = np.where(x != 0, g_val(x, kind) / x, 0.5)
+        bits = phi.astype(np.float32).view(np.uint32)
+        m = (x >= xs32).astype(np.uint32)
+        fwd[sgn] = (bits & np.uint32(0xFFFFFFFE)) | m
+    bwd = np.zeros((2, 2, LUT_N), dtype=np.float32)      # [m][sign][k]
+    # right branch, y >= 0 and y < 0
+    y = mag
+    bwd[1, 0] = g_der(invert(y, True, kind, xs), kind)
+    y = -mag
+    ok = y > ys
+    d = np.zeros(LUT_N)
+    d[ok] = g_der(invert(y[ok], True, kind, xs), kind)
+    bwd[1, 1] = d                                        # y <= y*: 0
+    # left branch, y < 0, key window 6 octaves lower
+    magl = bf16_value(LUT_LO - LUT_LEFT_SHIFT + k)
+    y = -magl
+    ok = y > ys
+    d = np.zeros(LUT_N)
+    d[ok] = g_der(invert(y[ok], False, kind, xs), kind)
+    bwd[0, 1] = d
+    return fwd.reshape(-1), bwd.reshape(-1).view(np.uint32)
+
+
+def emit_flat(name, vals):
+    out = [f"static TEMPO_TABLE_QUAL const uint32_t {name}[{len(vals)}] = {{"]
+    for i in range(0, len(vals), 8):
+        out.append("  " + ", ".join("0x%08Xu" % int(v) for v in vals[i:i + 8]) + ",")
+    out.append("};")
+    return out
+
+
 def f32_hex(v):
     return "0x%08Xu" % struct.unpack("<I", struct.pack("<f", float(np.float32(v))))[0]
 
@@ -209,6 +283,15 @@ def main():
         ]
         lines += emit_rows(f"tempo_gelu_bwd_table_{kind}", rows)
         report.append(f"{kind}: " + ", ".join(f"{k} {v:.2e}" for k, v in errs.items()))
+    lines += [
+        f"#define TEMPO_GELU_LUT_LO {LUT_LO}",
+        f"#define TEMPO_GELU_LUT_N {LUT_N}",
+        f"#define TEMPO_GELU_LUT_LEFT_SHIFT {LUT_LEFT_SHIFT}",
+    ]
+    for kind in ("erf", "tanh"):
+        fwd, bwd = lut_tables(kind)
+        lines += emit_flat(f"tempo_gelu_lut_fwd_{kind}", fwd)
+        lines += emit_flat(f"tempo_gelu_lut_bwd_{kind}", bwd)
     rows, worst = fwd_table()
     lines += emit_rows("tempo_gelu_fwd_table_erf", rows)
     report.append(f"fwd erf table: {worst:.2e}")

@@ -54,7 +54,7 @@ __global__ __launch_bounds__(kFwdThreads) void ln_fwd_kernel(
     for (int c = 0; c < CH; ++c) {
       const int ch = c * LANES + t;
       if (ch < chunks) {
-        Store<T>::load8(xr + ch * 8, v[c]);
+        load8_stream<T>(xr + ch * 8, v[c]);
       } else {
 #pragma unroll
         for (int i = 0; i < 8; ++i) v[c][i] = 0.0f;
@@ -83,7 +83,7 @@ __global__ __launch_bounds__(kFwdThreads) void ln_fwd_kernel(
         float o[8];
 #pragma unroll
         for (int i = 0; i < 8; ++i) o[i] = fmaf(v[c][i] * rs, ga[c][i], be[c][i]);
-        Store<T>::store8(yr + ch * 8, o);
+        store8_stream<T>(yr + ch * 8, o);
       }
     }
     if (t == 0) {
@@ -134,7 +134,10 @@ __global__ __launch_bounds__(256) void ln_fwd_generic_kernel(
   }
 }
 
-template <typename T, int LANES, int CH>
+// Workgroup b owns the kGroups*R consecutive rows starting at b*kGroups*R (then strides by
+// the grid); lane group g takes rows base + r*kGroups + g, r < R.  All R rows of a group are
+// fetched (kept packed) before any arithmetic, so a group waits for memory once per R rows.
+template <typename T, int LANES, int CH, int R>
 __global__ __launch_bounds__(kBwdThreads) void ln_bwd_kernel(
     const T* dy, const T* __restrict__ y, const float* __restrict__ gamma,
     const float* __restrict__ beta, const float* __restrict__ rstd, T* dx,
@@ -150,64 +153,98 @@ __global__ __launch_bounds__(kBwdThreads) void ln_bwd_kernel(
   float ga[CH][8], be[CH][8], acc_g[CH][8], acc_b[CH][8];
 #pragma unroll
   for (int c = 0; c < CH; ++c) {
-    const int ch = c * LANES + t;
-    if (ch < chunks) {
-      load_param8(gamma + ch * 8, ga[c]);
-      load_param8(beta + ch * 8, be[c]);
-    } else {
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        ga[c][i] = 1.0f;
-        be[c][i] = 0.0f;
-      }
-    }
 #pragma unroll
     for (int i = 0; i < 8; ++i) acc_g[c][i] = acc_b[c][i] = 0.0f;
   }
-  for (int64_t row = static_cast<int64_t>(blockIdx.x) * kGroups + g; row < N;
-       row += static_cast<int64_t>(gridDim.x) * kGroups) {
-    const T* dyr = dy + row * M;
-    const T* yr = y + row * M;
-    T* dxr = dx + row * M;
-    float gg[CH][8], xh[CH][8];
-    float c1 = 0.0f, c2 = 0.0f;
+  bool have_params = false;
+  for (int64_t base = static_cast<int64_t>(blockIdx.x) * (kGroups * R); base < N;
+       base += static_cast<int64_t>(gridDim.x) * (kGroups * R)) {
+    Raw<T> rd[R][CH], ry[R][CH];
+    float rs[R];
 #pragma unroll
-    for (int c = 0; c < CH; ++c) {
-      const int ch = c * LANES + t;
-      float d8[8], y8[8];
-      if (ch < chunks) {
-        Store<T>::load8(dyr + ch * 8, d8);
-        Store<T>::load8(yr + ch * 8, y8);
-      } else {
+    for (int r = 0; r < R; ++r) {
+      const int64_t row = base + r * kGroups + g;
+      rs[r] = 0.0f;
+      if (row < N) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-          d8[i] = 0.0f;
-          y8[i] = 0.0f;
+        for (int c = 0; c < CH; ++c) {
+          const int ch = c * LANES + t;
+          if (ch < chunks) {
+            rd[r][c].load(dy + row * M + ch * 8);
+            ry[r][c].load(y + row * M + ch * 8);
+          }
         }
-      }
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const float h = (y8[i] - be[c][i]) * __builtin_amdgcn_rcpf(ga[c][i]);
-        const float q = d8[i] * ga[c][i];
-        xh[c][i] = h;
-        gg[c][i] = q;
-        c1 = fmaf(q, h, c1);
-        c2 += q;
-        acc_g[c][i] = fmaf(d8[i], h, acc_g[c][i]);
-        acc_b[c][i] += d8[i];
+        rs[r] = rstd[row];
       }
     }
-    c1 = group_sum<LANES>(c1) * inv_m;
-    c2 = group_sum<LANES>(c2) * inv_m;
-    const float rs = rstd[row];
+    if (!have_params) {  // after the first rows are on their way
+      have_params = true;
 #pragma unroll
-    for (int c = 0; c < CH; ++c) {
-      const int ch = c * LANES + t;
-      if (ch < chunks) {
-        float o[8];
+      for (int c = 0; c < CH; ++c) {
+        const int ch = c * LANES + t;
+        if (ch < chunks) {
+          load_param8(gamma + ch * 8, ga[c]);
+          load_param8(beta + ch * 8, be[c]);
+        } else {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) o[i] = rs * (gg[c][i] - fmaf(xh[c][i], c1, c2));
-        Store<T>::store8(dxr + ch * 8, o);
+          for (int i = 0; i < 8; ++i) {
+            ga[c][i] = 1.0f;
+            be[c][i] = 0.0f;
+          }
+        }
+      }
+    }
+    // pass 1: the two row sums of every row (and the column accumulators); the R butterfly
+    // chains are independent, so their latencies overlap
+    float c1[R], c2[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      const int64_t row = base + r * kGroups + g;
+      c1[r] = c2[r] = 0.0f;
+      if (row >= N) continue;  // uniform over the lane group
+#pragma unroll
+      for (int c = 0; c < CH; ++c) {
+        const int ch = c * LANES + t;
+        if (ch < chunks) {
+          float d8[8], y8[8];
+          rd[r][c].unpack(d8);
+          ry[r][c].unpack(y8);
+#pragma unroll
+          for (int i = 0; i < 8; ++i) {
+            const float h = (y8[i] - be[c][i]) * __builtin_amdgcn_rcpf(ga[c][i]);
+            const float q = d8[i] * ga[c][i];
+            c1[r] = fmaf(q, h, c1[r]);
+            c2[r] += q;
+            acc_g[c][i] = fmaf(d8[i], h, acc_g[c][i]);
+            acc_b[c][i] += d8[i];
+          }
+        }
+      }
+    }
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      c1[r] = group_sum<LANES>(c1[r]) * inv_m;
+      c2[r] = group_sum<LANES>(c2[r]) * inv_m;
+    }
+    // pass 2: dx, recomputing xhat and dy*gamma from the packed registers
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      const int64_t row = base + r * kGroups + g;
+      if (row >= N) continue;
+#pragma unroll
+      for (int c = 0; c < CH; ++c) {
+        const int ch = c * LANES + t;
+        if (ch < chunks) {
+          float d8[8], y8[8], o[8];
+          rd[r][c].unpack(d8);
+          ry[r][c].unpack(y8);
+#pragma unroll
+          for (int i = 0; i < 8; ++i) {
+            const float h = (y8[i] - be[c][i]) * __builtin_amdgcn_rcpf(ga[c][i]);
+            o[i] = rs[r] * (d8[i] * ga[c][i] - fmaf(h, c1[r], c2[r]));
+          }
+          store8_stream<T>(dx + row * M + ch * 8, o);
+        }
       }
     }
   }
@@ -312,26 +349,38 @@ __global__ __launch_bounds__(256) void ln_bwd_generic_kernel(
   }
 }
 
-// dgamma[j] = sum_p partial[p][0][j], dbeta[j] = sum_p partial[p][1][j]: 16 columns x 16
-// interleaved slices per workgroup, slices combined in a fixed order.
-__global__ __launch_bounds__(256) void ln_bwd_finalize_kernel(const float* __restrict__ partial,
-                                                              float* __restrict__ dgamma,
-                                                              float* __restrict__ dbeta,
-                                                              int parts, int64_t M) {
-  __shared__ float lds[16][17];
-  const int col = threadIdx.x & 15;
-  const int slice = threadIdx.x >> 4;
-  const int64_t j2 = static_cast<int64_t>(blockIdx.x) * 16 + col;  // index into [2][M]
+// dgamma[j] = sum_p partial[p][0][j], dbeta[j] = sum_p partial[p][1][j].  A workgroup of 1024
+// lanes owns 16 adjacent columns of the [2][M] row; its 64 slices each add every 64th
+// partial (all loads of a lane are independent and issued together), then the slices are
+// combined through LDS in a fixed order.
+constexpr int kFinCols = 16;
+constexpr int kFinSlices = 64;
+__global__ __launch_bounds__(kFinCols* kFinSlices) void ln_bwd_finalize_kernel(
+    const float* __restrict__ partial, float* __restrict__ dgamma, float* __restrict__ dbeta,
+    int parts, int64_t M) {
+  __shared__ float lds[kFinSlices][kFinCols + 1];
+  const int col = threadIdx.x % kFinCols;
+  const int slice = threadIdx.x / kFinCols;
+  const int64_t j2 = static_cast<int64_t>(blockIdx.x) * kFinCols + col;  // index into [2][M]
   float s = 0.0f;
   if (j2 < 2 * M) {
-    for (int p = slice; p < parts; p += 16) s += partial[static_cast<size_t>(p) * 2 * M + j2];
+    const float* p0 = partial + j2;
+    int p = slice;
+    for (; p + 7 * kFinSlices < parts; p += 8 * kFinSlices) {
+      float v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = p0[static_cast<size_t>(p + u * kFinSlices) * 2 * M];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) s += v[u];
+    }
+    for (; p < parts; p += kFinSlices) s += p0[static_cast<size_t>(p) * 2 * M];
   }
   lds[slice][col] = s;
   __syncthreads();
   if (slice == 0 && j2 < 2 * M) {
     float tot = 0.0f;
 #pragma unroll
-    for (int k = 0; k < 16; ++k) tot += lds[k][col];
+    for (int k = 0; k < kFinSlices; ++k) tot += lds[k][col];
     if (j2 < M) dgamma[j2] = tot;
     else dbeta[j2 - M] = tot;
   }
@@ -432,6 +481,9 @@ tempo_status launch_layernorm_fwd(const void* x, const float* gamma, const float
   return launch_status();
 }
 
+// Rows a lane group fetches at once in the register-resident backward kernel.
+static int bwd_rows(int tuned) { return tuned >= 4 ? 4 : (tuned >= 2 ? 2 : 1); }
+
 int layernorm_bwd_blocks(int64_t N, int64_t M) {
   Shape sh;
   int64_t want;
@@ -441,8 +493,9 @@ int layernorm_bwd_blocks(int64_t N, int64_t M) {
   } else {
     want = N;
   }
-  const int64_t cap = tune_get(kTuneLnBwdBlocks);
-  const int64_t b = want < cap ? want : cap;
+  const int64_t rows_per_group = bwd_rows(tune_get(kTuneLnBwdRowsPerGroup));
+  int64_t b = (want + rows_per_group - 1) / rows_per_group;
+  if (b > 4096) b = 4096;  // bounds the workspace (4096 partials of 2*M floats)
   return static_cast<int>(b < 1 ? 1 : b);
 }
 
@@ -454,10 +507,17 @@ tempo_status launch_layernorm_bwd(const void* dy, const void* y, const float* ga
   const int grid = layernorm_bwd_blocks(N, M);
   if (fast_shape(M, &sh, kMaxFastBwdM)) {
     const size_t lds_bytes = static_cast<size_t>(kBwdWaves / 2) * 2 * M * sizeof(float);
+    const int rows = bwd_rows(tune_get(kTuneLnBwdRowsPerGroup));
+#define TEMPO_LAUNCH_R(T, L, C, RR)                                                          \
+  hipLaunchKernelGGL((ln_bwd_kernel<T, L, C, RR>), dim3(grid), dim3(kBwdThreads), lds_bytes, \
+                     st, static_cast<const T*>(dy), static_cast<const T*>(y), gamma, beta,   \
+                     rstd, static_cast<T*>(dx), workspace, N, static_cast<int>(M))
 #define TEMPO_LAUNCH_T(T, L, C)                                                              \
-  hipLaunchKernelGGL((ln_bwd_kernel<T, L, C>), dim3(grid), dim3(kBwdThreads), lds_bytes, st, \
-                     static_cast<const T*>(dy), static_cast<const T*>(y), gamma, beta, rstd, \
-                     static_cast<T*>(dx), workspace, N, static_cast<int>(M))
+  do {                                                                                       \
+    if (rows == 4 && C <= 4) TEMPO_LAUNCH_R(T, L, C, 4);                                     \
+    else if (rows >= 2 && C <= 4) TEMPO_LAUNCH_R(T, L, C, 2);                                \
+    else TEMPO_LAUNCH_R(T, L, C, 1);                                                         \
+  } while (0)
     if (dt == TEMPO_F32) {
 #define TEMPO_LAUNCH(L, C) TEMPO_LAUNCH_T(float, L, C)
       TEMPO_LN_DISPATCH(TEMPO_LAUNCH)
@@ -468,6 +528,7 @@ tempo_status launch_layernorm_bwd(const void* dy, const void* y, const float* ga
 #undef TEMPO_LAUNCH
     }
 #undef TEMPO_LAUNCH_T
+#undef TEMPO_LAUNCH_R
   } else {
     if (dt == TEMPO_F32)
       hipLaunchKernelGGL((ln_bwd_generic_kernel<float>), dim3(grid), dim3(256), 0, st,
@@ -479,9 +540,9 @@ tempo_status launch_layernorm_bwd(const void* dy, const void* y, const float* ga
                          beta, rstd, static_cast<bf16_t*>(dx), workspace, N, M);
   }
   if (hipGetLastError() != hipSuccess) return TEMPO_ERR_LAUNCH;
-  const int fgrid = static_cast<int>((2 * M + 15) / 16);
-  hipLaunchKernelGGL(ln_bwd_finalize_kernel, dim3(fgrid), dim3(256), 0, st, workspace, dgamma,
-                     dbeta, grid, M);
+  const int fgrid = static_cast<int>((2 * M + kFinCols - 1) / kFinCols);
+  hipLaunchKernelGGL(ln_bwd_finalize_kernel, dim3(fgrid), dim3(kFinCols * kFinSlices), 0, st,
+                     workspace, dgamma, dbeta, grid, M);
   return launch_status();
 }
 

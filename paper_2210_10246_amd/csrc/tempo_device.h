@@ -86,11 +86,74 @@ struct Store<bf16_t> {
   __device__ static __forceinline__ float round(float v) { return round_bf16(v); }
 };
 
+// Streaming variants: non-temporal 16-byte accesses for data that is touched exactly once.
+__device__ __forceinline__ u32x4 ldg_stream(const void* p) {
+  return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+}
+__device__ __forceinline__ void stg_stream(void* p, u32x4 v) {
+  __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(p));
+}
+__device__ __forceinline__ void unpack8(const u32x4 w, float (&v)[8]) {  // 8 bf16 -> float
+  v[0] = bf16_lo(w.x); v[1] = bf16_hi(w.x);
+  v[2] = bf16_lo(w.y); v[3] = bf16_hi(w.y);
+  v[4] = bf16_lo(w.z); v[5] = bf16_hi(w.z);
+  v[6] = bf16_lo(w.w); v[7] = bf16_hi(w.w);
+}
+template <typename T>
+__device__ __forceinline__ void load8_stream(const T* p, float (&v)[8]);
+template <>
+__device__ __forceinline__ void load8_stream<float>(const float* p, float (&v)[8]) {
+  const u32x4 a = ldg_stream(p), b = ldg_stream(p + 4);
+  v[0] = as_f32(a.x); v[1] = as_f32(a.y); v[2] = as_f32(a.z); v[3] = as_f32(a.w);
+  v[4] = as_f32(b.x); v[5] = as_f32(b.y); v[6] = as_f32(b.z); v[7] = as_f32(b.w);
+}
+template <>
+__device__ __forceinline__ void load8_stream<bf16_t>(const bf16_t* p, float (&v)[8]) {
+  unpack8(ldg_stream(p), v);
+}
+template <typename T>
+__device__ __forceinline__ void store8_stream(T* p, const float (&v)[8]);
+template <>
+__device__ __forceinline__ void store8_stream<float>(float* p, const float (&v)[8]) {
+  u32x4 a = {as_u32(v[0]), as_u32(v[1]), as_u32(v[2]), as_u32(v[3])};
+  u32x4 b = {as_u32(v[4]), as_u32(v[5]), as_u32(v[6]), as_u32(v[7])};
+  stg_stream(p, a);
+  stg_stream(p + 4, b);
+}
+template <>
+__device__ __forceinline__ void store8_stream<bf16_t>(bf16_t* p, const float (&v)[8]) {
+  u32x4 w = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3]), pack_bf16(v[4], v[5]),
+             pack_bf16(v[6], v[7])};
+  stg_stream(p, w);
+}
+
+// Raw (still packed) storage of one 8-element chunk, so a prefetched row costs few registers.
+template <typename T>
+struct Raw;
+template <>
+struct Raw<bf16_t> {
+  u32x4 a;
+  __device__ __forceinline__ void load(const bf16_t* p) { a = ldg_stream(p); }
+  __device__ __forceinline__ void unpack(float (&v)[8]) const { unpack8(a, v); }
+};
+template <>
+struct Raw<float> {
+  u32x4 a, b;
+  __device__ __forceinline__ void load(const float* p) {
+    a = ldg_stream(p);
+    b = ldg_stream(p + 4);
+  }
+  __device__ __forceinline__ void unpack(float (&v)[8]) const {
+    v[0] = as_f32(a.x); v[1] = as_f32(a.y); v[2] = as_f32(a.z); v[3] = as_f32(a.w);
+    v[4] = as_f32(b.x); v[5] = as_f32(b.y); v[6] = as_f32(b.z); v[7] = as_f32(b.w);
+  }
+};
+
 // Guarded chunk access: elements at or beyond `n_left` (counted from p) are absent.
 template <typename T>
 __device__ __forceinline__ void load8_guarded(const T* p, int64_t n_left, float (&v)[8], float fill) {
   if (n_left >= 8) {
-    Store<T>::load8(p, v);
+    load8_stream<T>(p, v);
   } else {
 #pragma unroll
     for (int i = 0; i < 8; ++i) v[i] = (i < n_left) ? Store<T>::load1(p + i) : fill;
@@ -99,7 +162,7 @@ __device__ __forceinline__ void load8_guarded(const T* p, int64_t n_left, float 
 template <typename T>
 __device__ __forceinline__ void store8_guarded(T* p, int64_t n_left, const float (&v)[8]) {
   if (n_left >= 8) {
-    Store<T>::store8(p, v);
+    store8_stream<T>(p, v);
   } else {
 #pragma unroll
     for (int i = 0; i < 8; ++i)
@@ -107,19 +170,56 @@ __device__ __forceinline__ void store8_guarded(T* p, int64_t n_left, const float
   }
 }
 
+// Cross-lane moves inside a row of 16 lanes through DPP (data-parallel primitives: the source
+// lane is selected by the instruction itself, no LDS round trip).  The four controls below
+// pair every lane with lane^1, lane^2 (quad permutes), then mirror 8 and 16 lanes, which for
+// values already equal inside a quad / half row acts like lane^4 and lane^8.
+constexpr int kDppXor1 = 0xB1;         // quad_perm [1,0,3,2]
+constexpr int kDppXor2 = 0x4E;         // quad_perm [2,3,0,1]
+constexpr int kDppHalfMirror = 0x141;  // row_half_mirror
+constexpr int kDppMirror = 0x140;      // row_mirror
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_u32(uint32_t v) {
+  return static_cast<uint32_t>(
+      __builtin_amdgcn_update_dpp(0, static_cast<int>(v), CTRL, 0xF, 0xF, true));
+}
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float v) {
+  return as_f32(dpp_u32<CTRL>(as_u32(v)));
+}
+
 // Butterfly reductions over groups of LANES consecutive lanes of a wave (LANES a power of
-// two <= 64); every lane of the group ends with the result.
+// two, 4 <= LANES <= 64, groups aligned to LANES); every lane of the group ends with the
+// result.  Steps inside a 16-lane row use DPP, the steps across rows go through ds_bpermute.
 template <int LANES>
 __device__ __forceinline__ float group_sum(float v) {
-#pragma unroll
-  for (int m = LANES / 2; m >= 1; m >>= 1) v += __shfl_xor(v, m, kWave);
+  static_assert(LANES >= 4 && LANES <= 64, "group size");
+  v += dpp_f32<kDppXor1>(v);
+  v += dpp_f32<kDppXor2>(v);
+  if (LANES >= 8) v += dpp_f32<kDppHalfMirror>(v);
+  if (LANES >= 16) v += dpp_f32<kDppMirror>(v);
+  if (LANES >= 32) v += __shfl_xor(v, 16, kWave);
+  if (LANES >= 64) v += __shfl_xor(v, 32, kWave);
   return v;
 }
 template <int LANES>
 __device__ __forceinline__ float group_max(float v) {
-#pragma unroll
-  for (int m = LANES / 2; m >= 1; m >>= 1) v = fmaxf(v, __shfl_xor(v, m, kWave));
+  static_assert(LANES >= 4 && LANES <= 64, "group size");
+  v = fmaxf(v, dpp_f32<kDppXor1>(v));
+  v = fmaxf(v, dpp_f32<kDppXor2>(v));
+  if (LANES >= 8) v = fmaxf(v, dpp_f32<kDppHalfMirror>(v));
+  if (LANES >= 16) v = fmaxf(v, dpp_f32<kDppMirror>(v));
+  if (LANES >= 32) v = fmaxf(v, __shfl_xor(v, 16, kWave));
+  if (LANES >= 64) v = fmaxf(v, __shfl_xor(v, 32, kWave));
   return v;
+}
+
+// Merge the 8-bit chunk masks of the 4 lanes of a quad into the 32-bit word they share.
+__device__ __forceinline__ uint32_t merge_quad_bytes(uint32_t byte, int lane_in_quad) {
+  uint32_t w = byte << (8 * lane_in_quad);
+  w |= dpp_u32<kDppXor1>(w);
+  w |= dpp_u32<kDppXor2>(w);
+  return w;
 }
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }

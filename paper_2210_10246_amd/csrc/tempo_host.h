@@ -8,13 +8,13 @@
 
 namespace tempo {
 
-// Launch-shape knobs (workgroups per launch are capped at compute_units * value).
+// Launch-shape knobs.
 enum TuneKey {
-  kTuneGeluFwdBlocksPerCu = 0,
-  kTuneGeluBwdBlocksPerCu = 1,
-  kTuneLnFwdBlocksPerCu = 2,
-  kTuneLnBwdBlocks = 3,  // absolute number of workgroups (also sizes the workspace)
-  kTuneAttnFwdBlocksPerCu = 4,
+  kTuneGeluFwdChunks = 0,       // 8-element chunks per lane (1, 2 or 4)
+  kTuneGeluBwdChunks = 1,
+  kTuneLnFwdBlocksPerCu = 2,    // cap on workgroups per compute unit
+  kTuneLnBwdRowsPerGroup = 3,   // rows each lane group walks (sets the grid and the workspace)
+  kTuneAttnFwdBlocksPerCu = 4,  // cap on workgroups per compute unit
   kTuneAttnBwdBlocksPerCu = 5,
   kTuneCount = 6
 };
