@@ -36,6 +36,8 @@ def parse():
     ap.add_argument("--kernel-iters", type=int, default=60, help="launches per kernel timing loop")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true")
+    ap.add_argument("--no-graph", action="store_true",
+                    help="launch every kernel from Python instead of replaying HIP graphs")
     ap.add_argument("--only", default=None, help="time only this kernel (for profiling)")
     return ap.parse_args()
 
@@ -68,7 +70,7 @@ class Buffers:
     """R rotating sets of device buffers for one kernel family."""
 
     def __init__(self, make, footprint):
-        self.n = max(2, min(16, -(-ROTATE_BYTES // max(footprint, 1))))
+        self.n = max(4, min(16, -(-ROTATE_BYTES // max(footprint, 1))))
         self.sets = [make(i) for i in range(self.n)]
         self.i = 0
 
@@ -153,29 +155,49 @@ def main():
     for s in attn_b.sets: k_attn_fwd(s)
     torch.cuda.synchronize()
 
-    def step():
-        g = gelu_b.next()
-        a = attn_b.next()
-        l1, l2 = ln_b.next(), ln_b.next()
+    PHASES = 4   # a step of phase ph touches buffer sets that no other phase touches
+
+    def step(ph):
+        g, a = gelu_b.sets[ph], attn_b.sets[ph]
+        l1, l2 = ln_b.sets[2 * ph], ln_b.sets[2 * ph + 1]
         # forward order of an encoder layer, then backward in reverse
         k_attn_fwd(a); k_ln_fwd(l1); k_gelu_fwd(g); k_ln_fwd(l2)
         k_ln_bwd(l2); k_gelu_bwd(g); k_ln_bwd(l1); k_attn_bwd(a)
 
+    assert ln_b.n >= 2 * PHASES and gelu_b.n >= PHASES and attn_b.n >= PHASES
     step_bytes = (algo["gelu_fwd"] + algo["gelu_bwd"] + 2 * (algo["layernorm_fwd"] + algo["layernorm_bwd"])
                   + algo["attn_fwd"] + algo["attn_bwd"])
 
+    def capture(fn):
+        """Record fn's launches into a HIP graph (the kernels are launch-bound from Python:
+        a LayerNorm launch lasts ~10 us, a ctypes call about as long)."""
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            fn()
+        return g
+
+    use_graph = not args.no_graph
     ms_per_step = float("nan")
     if args.only is None:
-        for _ in range(args.warmup):
-            step()
+        for i in range(max(args.warmup, PHASES)):
+            step(i % PHASES)
+        torch.cuda.synchronize()
+        if use_graph:
+            graphs = [capture(lambda ph=ph: step(ph)) for ph in range(PHASES)]
+            for gph in graphs:
+                gph.replay()
+            run = lambda i: graphs[i % PHASES].replay()
+        else:
+            run = lambda i: step(i % PHASES)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        for _ in range(args.steps):
-            step()
+        for i in range(args.steps):
+            run(i)
         torch.cuda.synchronize()
         ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
 
-    # ---- per-kernel launch durations: events on the stream the kernels are launched on
+    # ---- per-kernel launch durations: events on the stream the kernels are launched on,
+    # around a replayed graph of kernel_iters back-to-back launches over rotating buffers
     per_kernel = {}
     if not args.no_kernel_timing:
         for name, (fn, bufs) in kernels.items():
@@ -184,10 +206,16 @@ def main():
             for _ in range(max(3, bufs.n)):
                 fn(bufs.next())
             torch.cuda.synchronize()
+
+            def burst(fn=fn, bufs=bufs):
+                for _ in range(args.kernel_iters):
+                    fn(bufs.next())
+            body = capture(burst).replay if use_graph else burst
+            body()
+            torch.cuda.synchronize()
             ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             ev0.record()
-            for _ in range(args.kernel_iters):
-                fn(bufs.next())
+            body()
             ev1.record()
             ev1.synchronize()
             us = ev0.elapsed_time(ev1) * 1e3 / args.kernel_iters
@@ -198,7 +226,7 @@ def main():
 
     # ---- what a plain 16-byte copy reaches on this GPU (read + write bytes per second)
     copy_gbs = None
-    if not args.no_kernel_timing and args.only is None:
+    if not args.no_kernel_timing and args.only in (None, "copy"):
         nb = 256 << 20
         srcs = [torch.empty(nb, dtype=torch.uint8, device=dev).fill_(i) for i in range(3)]
         dsts = [torch.empty(nb, dtype=torch.uint8, device=dev) for _ in range(3)]
@@ -239,6 +267,7 @@ def main():
                    "hidden": cfg.hidden, "heads": cfg.heads, "ffn": cfg.ffn, "mask": cfg.mask,
                    "dropout_p": cfg.p, "gelu": cfg.gelu_kind,
                    "step": "attn fwd, LN fwd, GELU fwd, LN fwd, LN bwd, GELU bwd, LN bwd, attn bwd",
+                   "launch": "eager" if args.no_graph else "HIP graph replay (one graph per buffer phase)",
                    "algorithmic_bytes_per_step": int(step_bytes)},
         "frac_of_hbm_peak": None if value is None else round(value / HBM_PEAK_GBS, 4),
         "copy_kernel_GB/s": copy_gbs,

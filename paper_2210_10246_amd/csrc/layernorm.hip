@@ -350,11 +350,11 @@ __global__ __launch_bounds__(256) void ln_bwd_generic_kernel(
 }
 
 // dgamma[j] = sum_p partial[p][0][j], dbeta[j] = sum_p partial[p][1][j].  A workgroup of 1024
-// lanes owns 16 adjacent columns of the [2][M] row; its 64 slices each add every 64th
+// lanes owns 32 adjacent columns of the [2][M] row; its 32 slices each add every 32nd
 // partial (all loads of a lane are independent and issued together), then the slices are
 // combined through LDS in a fixed order.
-constexpr int kFinCols = 16;
-constexpr int kFinSlices = 64;
+constexpr int kFinCols = 32;   // 128 contiguous bytes per partial row
+constexpr int kFinSlices = 32;
 __global__ __launch_bounds__(kFinCols* kFinSlices) void ln_bwd_finalize_kernel(
     const float* __restrict__ partial, float* __restrict__ dgamma, float* __restrict__ dbeta,
     int parts, int64_t M) {

@@ -317,3 +317,54 @@ def test_non_default_stream(B):
     st.synchronize()
     y_ref, m_ref = O.gelu_fwd(x, "erf", "f32")
     assert rel_err(host(yd), y_ref) <= TOL["f32"] and np.array_equal(words(md), O.pack_bits(m_ref))
+
+
+def test_hip_graph_replays_match_eager(B):
+    """The benchmark replays captured HIP graphs: every replay must reproduce the eagerly
+    launched results, with the program's own eager work and synchronisations in between."""
+    rng = np.random.default_rng(11)
+    dt = "bf16"
+    N, M, n = 64, 1024, 64 * 4096
+    x = dev(stored(rng, n, dt), dt)
+    dy = dev(stored(rng, n, dt), dt)
+    lx = dev(stored(rng, (N, M), dt), dt)
+    ldy = dev(stored(rng, (N, M), dt), dt)
+    gamma = dev(O.round_to_dtype(1 + 0.1 * rng.standard_normal(M), "f32"), "f32")
+    beta = dev(O.round_to_dtype(0.1 * rng.standard_normal(M), "f32"), "f32")
+    s = dev(stored(rng, (2, 2, 128, 128), dt, 0.125), dt)
+    do = dev(stored(rng, (2, 2, 128, 128), dt), dt)
+    kl = torch.tensor([100, 128], dtype=torch.int32, device="cuda")
+    ws = torch.empty(B.tempo_layernorm_bwd_workspace_bytes(N, M), dtype=torch.uint8, device="cuda")
+
+    def fresh():
+        return dict(y=torch.empty_like(x), m=torch.empty(B.mask_words(n), dtype=torch.int32, device="cuda"),
+                    dx=torch.empty_like(x), ly=torch.empty_like(lx), rstd=torch.empty(N, device="cuda"),
+                    ldx=torch.empty_like(lx), dg=torch.empty(M, device="cuda"), db=torch.empty(M, device="cuda"),
+                    P=torch.empty_like(s), out=torch.empty_like(s), k=torch.empty(B.mask_words(s.numel()), dtype=torch.int32, device="cuda"),
+                    dS=torch.empty_like(s), ore=torch.empty_like(s))
+
+    def run(o):
+        B.tempo_gelu_fwd(x, o["y"], o["m"], "erf")
+        B.tempo_gelu_bwd(dy, o["y"], o["m"], o["dx"], "erf")
+        B.tempo_layernorm_fwd(lx, gamma, beta, o["ly"], o["rstd"], None, 1e-12)
+        B.tempo_layernorm_bwd(ldy, o["ly"], gamma, beta, o["rstd"], o["ldx"], o["dg"], o["db"], ws)
+        B.tempo_attn_softmax_dropout_fwd(s, kl, False, o["P"], o["out"], o["k"], 0.1, 77, 3)
+        B.tempo_attn_softmax_dropout_bwd(do, o["P"], o["k"], o["dS"], o["ore"], 0.1)
+
+    eager = fresh()
+    run(eager)
+    torch.cuda.synchronize()
+    captured = fresh()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        run(captured)
+    for rep in range(4):
+        for t in captured.values():
+            t.zero_() if t.dtype != torch.int32 else t.fill_(-1)
+        torch.cuda.synchronize()
+        g.replay()
+        scratch = fresh()
+        run(scratch)                      # eager work between replays
+        torch.cuda.synchronize()
+        for name in eager:
+            assert torch.equal(captured[name].view(torch.uint8), eager[name].view(torch.uint8)), (rep, name)
