@@ -127,8 +127,9 @@ tempo_status tempo_layernorm_fwd(const void* x, const float* gamma, const float*
 
 size_t tempo_layernorm_bwd_workspace_bytes(int64_t N, int64_t M) {
   if (N <= 0 || M <= 0) return 0;
-  return static_cast<size_t>(layernorm_bwd_blocks(N, M)) * 2 * static_cast<size_t>(M) *
-         sizeof(float);
+  // the larger of the two dtypes' grids, so one query serves both
+  const int a = layernorm_bwd_blocks(N, M, TEMPO_F32), b = layernorm_bwd_blocks(N, M, TEMPO_BF16);
+  return static_cast<size_t>(a > b ? a : b) * 2 * static_cast<size_t>(M) * sizeof(float);
 }
 
 tempo_status tempo_layernorm_bwd(const void* dy, const void* y, const float* gamma,

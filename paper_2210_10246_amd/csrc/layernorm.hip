@@ -481,20 +481,29 @@ tempo_status launch_layernorm_fwd(const void* x, const float* gamma, const float
   return launch_status();
 }
 
-// Rows a lane group fetches at once in the register-resident backward kernel.
-static int bwd_rows(int tuned) { return tuned >= 4 ? 4 : (tuned >= 2 ? 2 : 1); }
+// Rows a lane group fetches at once in the register-resident backward kernel: as many as the
+// knob allows while the packed rows stay within ~64 registers and the grid still has at
+// least one workgroup per compute unit.
+static int bwd_rows(int tuned, int64_t N, const Shape& sh, tempo_dtype dt) {
+  const int regs_per_row = sh.ch * (dt == TEMPO_F32 ? 16 : 8);  // dy and y, packed
+  const int groups = kBwdThreads / sh.lanes;
+  int r = tuned >= 4 ? 4 : (tuned >= 2 ? 2 : 1);
+  while (r > 1 && (r * regs_per_row > 64 ||
+                   (N + static_cast<int64_t>(groups) * r - 1) / (groups * r) < compute_units()))
+    r >>= 1;
+  return r;
+}
 
-int layernorm_bwd_blocks(int64_t N, int64_t M) {
+int layernorm_bwd_blocks(int64_t N, int64_t M, tempo_dtype dt) {
   Shape sh;
-  int64_t want;
+  int64_t b;
   if (fast_shape(M, &sh, kMaxFastBwdM)) {
-    const int groups = kBwdThreads / sh.lanes;
-    want = (N + groups - 1) / groups;
+    const int64_t rows_per_block =
+        static_cast<int64_t>(kBwdThreads / sh.lanes) * bwd_rows(tune_get(kTuneLnBwdRowsPerGroup), N, sh, dt);
+    b = (N + rows_per_block - 1) / rows_per_block;
   } else {
-    want = N;
+    b = N;
   }
-  const int64_t rows_per_group = bwd_rows(tune_get(kTuneLnBwdRowsPerGroup));
-  int64_t b = (want + rows_per_group - 1) / rows_per_group;
   if (b > 4096) b = 4096;  // bounds the workspace (4096 partials of 2*M floats)
   return static_cast<int>(b < 1 ? 1 : b);
 }
@@ -504,17 +513,17 @@ tempo_status launch_layernorm_bwd(const void* dy, const void* y, const float* ga
                                   float* dbeta, float* workspace, int64_t N, int64_t M,
                                   tempo_dtype dt, hipStream_t st) {
   Shape sh;
-  const int grid = layernorm_bwd_blocks(N, M);
+  const int grid = layernorm_bwd_blocks(N, M, dt);
   if (fast_shape(M, &sh, kMaxFastBwdM)) {
     const size_t lds_bytes = static_cast<size_t>(kBwdWaves / 2) * 2 * M * sizeof(float);
-    const int rows = bwd_rows(tune_get(kTuneLnBwdRowsPerGroup));
+    const int rows = bwd_rows(tune_get(kTuneLnBwdRowsPerGroup), N, sh, dt);
 #define TEMPO_LAUNCH_R(T, L, C, RR)                                                          \
   hipLaunchKernelGGL((ln_bwd_kernel<T, L, C, RR>), dim3(grid), dim3(kBwdThreads), lds_bytes, \
                      st, static_cast<const T*>(dy), static_cast<const T*>(y), gamma, beta,   \
                      rstd, static_cast<T*>(dx), workspace, N, static_cast<int>(M))
 #define TEMPO_LAUNCH_T(T, L, C)                                                              \
   do {                                                                                       \
-    if (rows == 4 && C <= 4) TEMPO_LAUNCH_R(T, L, C, 4);                                     \
+    if (rows == 4 && C <= 2) TEMPO_LAUNCH_R(T, L, C, 4);                                     \
     else if (rows >= 2 && C <= 4) TEMPO_LAUNCH_R(T, L, C, 2);                                \
     else TEMPO_LAUNCH_R(T, L, C, 1);                                                         \
   } while (0)

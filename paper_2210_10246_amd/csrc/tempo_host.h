@@ -32,7 +32,7 @@ tempo_status launch_gelu_bwd(const void* dy, const void* y, const uint32_t* mask
 tempo_status launch_layernorm_fwd(const void* x, const float* gamma, const float* beta, void* y,
                                   float* rstd, float* mean, int64_t N, int64_t M, float eps,
                                   tempo_dtype dt, hipStream_t st);
-int layernorm_bwd_blocks(int64_t N, int64_t M);
+int layernorm_bwd_blocks(int64_t N, int64_t M, tempo_dtype dt);
 tempo_status launch_layernorm_bwd(const void* dy, const void* y, const float* gamma,
                                   const float* beta, const float* rstd, void* dx, float* dgamma,
                                   float* dbeta, float* workspace, int64_t N, int64_t M,

@@ -1,0 +1,147 @@
+"""Parity at the full sizes of the benchmark configurations, in the launch configuration
+bench.py times (library defaults), on the seeded synthetic workloads.
+
+Where the float64 oracle is cheap (GELU forward, LayerNorm, attention of config 1) the whole
+tensor is compared; elsewhere (GELU backward: 200 bisection steps per element; the
+[B,A,S,S] maps of configs 2-4) a sample of elements / of whole [S,S] slices is compared
+element by element, and the full keep mask is checked against its expected keep rate.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from helpers import TOL, rel_err
+from oracle import tempo_oracle as O
+from paper_2210_10246_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+CASES = [
+    pytest.param(dict(index=1), id="config1"),
+    pytest.param(dict(index=2), id="config2"),
+    pytest.param(dict(index=3), id="config3"),
+    pytest.param(dict(index=4, batch=8, dtype="bf16"), id="config4-b8-bf16"),
+    pytest.param(dict(index=4, batch=8, dtype="f32"), id="config4-b8-f32"),
+]
+
+
+@pytest.fixture(scope="module")
+def B():
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2210_10246_amd import binding
+    binding.load()
+    return binding
+
+
+def _cfg(case):
+    return W.config(case["index"], batch=case.get("batch"), dtype=case.get("dtype"))
+
+
+def _words(t):
+    return t.detach().cpu().numpy().view(np.uint32)
+
+
+@pytest.mark.parametrize("case", CASES)
+def test_gelu_full_size(B, case):
+    cfg = _cfg(case)
+    dt = cfg.dtype
+    g = W.gelu_inputs(cfg)
+    x64 = W.as_f64(g["x"]).reshape(-1)
+    n = x64.size
+    xd, dyd = g["x"].cuda(), g["dy"].cuda()
+    yd = torch.empty_like(xd)
+    md = torch.empty(B.mask_words(n), dtype=torch.int32, device="cuda")
+    B.tempo_gelu_fwd(xd, yd, md, cfg.gelu_kind)
+    y_ref, m_ref = O.gelu_fwd(x64, cfg.gelu_kind, dt)
+    assert np.array_equal(_words(md), O.pack_bits(m_ref)), "mask differs"
+    y_gpu = W.as_f64(yd).reshape(-1)
+    assert rel_err(y_gpu, y_ref) <= TOL[dt]
+    # backward on the GPU's own stored y: a sample of elements, plus both ends of the tensor
+    dxd = torch.empty_like(xd)
+    B.tempo_gelu_bwd(dyd, yd, md, dxd, cfg.gelu_kind)
+    rng = np.random.default_rng(cfg.index)
+    idx = np.unique(np.concatenate([rng.integers(0, n, 200_000), np.arange(4096), np.arange(n - 4096, n)]))
+    dy64 = W.as_f64(g["dy"]).reshape(-1)
+    ref = O.gelu_bwd(dy64[idx], y_gpu[idx], m_ref[idx], cfg.gelu_kind, dt)
+    got = W.as_f64(dxd).reshape(-1)[idx]
+    assert rel_err(got, ref) <= TOL[dt]
+
+
+@pytest.mark.parametrize("case", CASES)
+def test_layernorm_full_size(B, case):
+    cfg = _cfg(case)
+    dt = cfg.dtype
+    l = W.layernorm_inputs(cfg)
+    N, M = l["x"].shape
+    gamma64, beta64 = W.as_f64(l["gamma"]), W.as_f64(l["beta"])
+    xd, dyd = l["x"].cuda(), l["dy"].cuda()
+    gd, bd = l["gamma"].cuda(), l["beta"].cuda()
+    yd = torch.empty_like(xd)
+    rd = torch.empty(N, dtype=torch.float32, device="cuda")
+    B.tempo_layernorm_fwd(xd, gd, bd, yd, rd, None, cfg.eps)
+    y_ref, rstd_ref, _ = O.layernorm_fwd(W.as_f64(l["x"]), gamma64, beta64, cfg.eps, dt)
+    assert rel_err(W.as_f64(yd), y_ref) <= TOL[dt]
+    assert rel_err(W.as_f64(rd), rstd_ref) <= TOL["f32"]
+    # backward from the GPU's own stored y and rstd
+    dxd = torch.empty_like(xd)
+    dgd = torch.empty(M, dtype=torch.float32, device="cuda")
+    dbd = torch.empty(M, dtype=torch.float32, device="cuda")
+    ws = torch.empty(B.tempo_layernorm_bwd_workspace_bytes(N, M), dtype=torch.uint8, device="cuda")
+    B.tempo_layernorm_bwd(dyd, yd, gd, bd, rd, dxd, dgd, dbd, ws)
+    dx_ref, dg_ref, db_ref = O.layernorm_bwd(W.as_f64(l["dy"]), W.as_f64(yd), gamma64, beta64,
+                                             W.as_f64(rd), dt)
+    assert rel_err(W.as_f64(dxd), dx_ref) <= TOL[dt]
+    # column sums over N rows in float32: error grows like sqrt(N) ulp of the running sum
+    assert rel_err(W.as_f64(dgd), dg_ref) <= 4 * TOL["f32"]
+    assert rel_err(W.as_f64(dbd), db_ref) <= 4 * TOL["f32"]
+
+
+@pytest.mark.parametrize("case", CASES)
+def test_attention_full_size(B, case):
+    cfg = _cfg(case)
+    dt = cfg.dtype
+    a = W.attention_inputs(cfg)
+    Bn, A, S, _ = a["scores"].shape
+    n = a["scores"].numel()
+    sd, dod = a["scores"].cuda(), a["dout"].cuda()
+    kd = None if a["key_len"] is None else a["key_len"].cuda()
+    Pd, od = torch.empty_like(sd), torch.empty_like(sd)
+    md = torch.empty(B.mask_words(n), dtype=torch.int32, device="cuda")
+    seed = cfg.dropout_seed
+    B.tempo_attn_softmax_dropout_fwd(sd, kd, a["causal"], Pd, od, md, cfg.p, seed, 0)
+    dsd, ord_ = torch.empty_like(sd), torch.empty_like(sd)
+    B.tempo_attn_softmax_dropout_bwd(dod, Pd, md, dsd, ord_, cfg.p)
+    torch.cuda.synchronize()
+    # recomputed dropout output is bit-identical to the forward's, over the whole tensor
+    view = torch.int16 if dt == "bf16" else torch.int32
+    assert torch.equal(od.view(view), ord_.view(view))
+    # keep rate of the whole mask
+    words = _words(md)
+    kept = int(np.unpackbits(words.view(np.uint8)).sum())
+    q = O.keep_threshold16(cfg.p) / 65536.0
+    assert abs(kept / n - q) < 5 * math.sqrt(q * (1 - q) / n)
+    # element-by-element on whole [S,S] slices: everything if it is small, else a sample
+    rng = np.random.default_rng(100 + cfg.index)
+    slices = [(b, h) for b in range(Bn) for h in range(A)]
+    if n > 20_000_000:
+        pick = rng.choice(len(slices), size=6, replace=False)
+        slices = [slices[0], slices[-1]] + [slices[i] for i in pick]
+    per = S * S
+    for (b, h) in slices:
+        s64 = W.as_f64(a["scores"][b, h])[None, None]
+        kl = None if a["key_len"] is None else a["key_len"][b:b + 1].numpy()
+        start = (b * A + h) * per
+        # the oracle on one slice, its keep bits taken at the slice's offset in the flat tensor
+        P_ref, _, _ = O.attn_softmax_dropout_fwd(s64, kl, a["causal"], 0.0, seed, 0, dt)
+        K_ref = O.dropout_keep(per, cfg.p, seed, 0, start=start).reshape(1, 1, S, S)
+        scale = float(np.float32(1.0) / (np.float32(1.0) - np.float32(cfg.p)))
+        out_ref = O.round_to_dtype(P_ref * K_ref * scale, dt)
+        assert per % 32 == 0
+        assert np.array_equal(words[start // 32:(start + per) // 32], O.pack_bits(K_ref)), (b, h)
+        P_gpu = W.as_f64(Pd[b, h])[None, None]
+        assert rel_err(P_gpu, P_ref) <= TOL[dt], (b, h)
+        assert rel_err(W.as_f64(od[b, h])[None, None], out_ref) <= TOL[dt], (b, h)
+        dS_ref, _ = O.attn_softmax_dropout_bwd(W.as_f64(a["dout"][b, h])[None, None], P_gpu, K_ref, cfg.p, dt)
+        assert rel_err(W.as_f64(dsd[b, h])[None, None], dS_ref) <= TOL[dt], (b, h)
