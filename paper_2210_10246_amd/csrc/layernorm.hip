@@ -134,15 +134,18 @@ __global__ __launch_bounds__(256) void ln_fwd_generic_kernel(
   }
 }
 
-// Workgroup b owns the kGroups*R consecutive rows starting at b*kGroups*R (then strides by
-// the grid); lane group g takes rows base + r*kGroups + g, r < R.  All R rows of a group are
-// fetched (kept packed) before any arithmetic, so a group waits for memory once per R rows.
-template <typename T, int LANES, int CH, int R>
+// A "batch" is kGroups*R consecutive rows: lane group g takes rows base + r*kGroups + g, r < R.
+// All R rows of a group are fetched (kept packed) before any arithmetic, so a group waits
+// for memory once per batch.  LOOP = false: one batch per workgroup (grid = batches).
+// LOOP = true: workgroups walk the batches grid-stride and fetch the next batch before they
+// compute on the current one; the column sums stay in registers across batches, so the LDS
+// tree and the partial store are paid once per workgroup however many rows it walks.
+template <typename T, int LANES, int CH, int R, bool LOOP>
 __global__ __launch_bounds__(kBwdThreads) void ln_bwd_kernel(
     const T* dy, const T* __restrict__ y, const float* __restrict__ gamma,
     const float* __restrict__ beta, const float* __restrict__ rstd, T* dx,
     float* __restrict__ partial, int64_t N, int M) {
-  extern __shared__ float lds[];  // [kBwdWaves/2][2][M]
+  extern __shared__ float lds[];  // [kBwdWaves/2][2][M] floats (>= 3*M)
   constexpr int kGroups = kBwdThreads / LANES;
   const int g = threadIdx.x / LANES;
   const int t = threadIdx.x % LANES;
@@ -150,49 +153,57 @@ __global__ __launch_bounds__(kBwdThreads) void ln_bwd_kernel(
   const int lane = threadIdx.x & (kWave - 1);
   const int chunks = M >> 3;
   const float inv_m = 1.0f / static_cast<float>(M);
-  float ga[CH][8], be[CH][8], acc_g[CH][8], acc_b[CH][8];
+  const int64_t batch_rows = kGroups * R;
+  // gamma, 1/gamma and beta/gamma live in LDS (the first 3*M floats; the same memory is
+  // reused by the reduction tree at the end), the column sums in registers
+  float* p_ga = lds;
+  float* p_rg = lds + M;
+  float* p_bg = lds + 2 * M;
+  float acc_g[CH][8], acc_b[CH][8];
 #pragma unroll
   for (int c = 0; c < CH; ++c) {
 #pragma unroll
     for (int i = 0; i < 8; ++i) acc_g[c][i] = acc_b[c][i] = 0.0f;
   }
-  bool have_params = false;
-  for (int64_t base = static_cast<int64_t>(blockIdx.x) * (kGroups * R); base < N;
-       base += static_cast<int64_t>(gridDim.x) * (kGroups * R)) {
-    Raw<T> rd[R][CH], ry[R][CH];
-    float rs[R];
+
+  auto fetch = [&](int64_t base, Raw<T> (&fd)[R][CH], Raw<T> (&fy)[R][CH], float (&fs)[R]) {
 #pragma unroll
     for (int r = 0; r < R; ++r) {
       const int64_t row = base + r * kGroups + g;
-      rs[r] = 0.0f;
+      fs[r] = 0.0f;
       if (row < N) {
 #pragma unroll
         for (int c = 0; c < CH; ++c) {
           const int ch = c * LANES + t;
           if (ch < chunks) {
-            rd[r][c].load(dy + row * M + ch * 8);
-            ry[r][c].load(y + row * M + ch * 8);
+            fd[r][c].load(dy + row * M + ch * 8);
+            fy[r][c].load(y + row * M + ch * 8);
           }
         }
-        rs[r] = rstd[row];
+        fs[r] = rstd[row];
       }
     }
-    if (!have_params) {  // after the first rows are on their way
-      have_params = true;
-#pragma unroll
-      for (int c = 0; c < CH; ++c) {
-        const int ch = c * LANES + t;
-        if (ch < chunks) {
-          load_param8(gamma + ch * 8, ga[c]);
-          load_param8(beta + ch * 8, be[c]);
-        } else {
-#pragma unroll
-          for (int i = 0; i < 8; ++i) {
-            ga[c][i] = 1.0f;
-            be[c][i] = 0.0f;
-          }
-        }
-      }
+  };
+
+  int64_t base = static_cast<int64_t>(blockIdx.x) * batch_rows;
+  Raw<T> rd[R][CH], ry[R][CH];
+  float rs[R];
+  fetch(base, rd, ry, rs);
+  // parameters after the first rows are on their way
+  for (int j = threadIdx.x; j < M; j += kBwdThreads) {
+    const float gj = gamma[j];
+    const float rj = 1.0f / gj;
+    p_ga[j] = gj;
+    p_rg[j] = rj;
+    p_bg[j] = beta[j] * rj;
+  }
+  __syncthreads();
+  while (base < N) {
+    const int64_t next = base + static_cast<int64_t>(gridDim.x) * batch_rows;
+    Raw<T> nd[R][CH], ny[R][CH];  // unused (and eliminated) without LOOP
+    float ns[R];
+    if constexpr (LOOP) {
+      if (next < N) fetch(next, nd, ny, ns);
     }
     // pass 1: the two row sums of every row (and the column accumulators); the R butterfly
     // chains are independent, so their latencies overlap
@@ -206,13 +217,16 @@ __global__ __launch_bounds__(kBwdThreads) void ln_bwd_kernel(
       for (int c = 0; c < CH; ++c) {
         const int ch = c * LANES + t;
         if (ch < chunks) {
-          float d8[8], y8[8];
+          float d8[8], y8[8], ga[8], rg[8], bg[8];
           rd[r][c].unpack(d8);
           ry[r][c].unpack(y8);
+          load_param8(p_ga + ch * 8, ga);
+          load_param8(p_rg + ch * 8, rg);
+          load_param8(p_bg + ch * 8, bg);
 #pragma unroll
           for (int i = 0; i < 8; ++i) {
-            const float h = (y8[i] - be[c][i]) * __builtin_amdgcn_rcpf(ga[c][i]);
-            const float q = d8[i] * ga[c][i];
+            const float h = fmaf(y8[i], rg[i], -bg[i]);  // xhat = (y - beta) / gamma
+            const float q = d8[i] * ga[i];
             c1[r] = fmaf(q, h, c1[r]);
             c2[r] += q;
             acc_g[c][i] = fmaf(d8[i], h, acc_g[c][i]);
@@ -235,17 +249,34 @@ __global__ __launch_bounds__(kBwdThreads) void ln_bwd_kernel(
       for (int c = 0; c < CH; ++c) {
         const int ch = c * LANES + t;
         if (ch < chunks) {
-          float d8[8], y8[8], o[8];
+          float d8[8], y8[8], o[8], ga[8], rg[8], bg[8];
           rd[r][c].unpack(d8);
           ry[r][c].unpack(y8);
+          load_param8(p_ga + ch * 8, ga);
+          load_param8(p_rg + ch * 8, rg);
+          load_param8(p_bg + ch * 8, bg);
 #pragma unroll
           for (int i = 0; i < 8; ++i) {
-            const float h = (y8[i] - be[c][i]) * __builtin_amdgcn_rcpf(ga[c][i]);
-            o[i] = rs[r] * (d8[i] * ga[c][i] - fmaf(h, c1[r], c2[r]));
+            const float h = fmaf(y8[i], rg[i], -bg[i]);
+            o[i] = rs[r] * (d8[i] * ga[i] - fmaf(h, c1[r], c2[r]));
           }
           store8_stream<T>(dx + row * M + ch * 8, o);
         }
       }
+    }
+    if constexpr (!LOOP) {
+      break;
+    } else {
+#pragma unroll
+      for (int r = 0; r < R; ++r) {
+#pragma unroll
+        for (int c = 0; c < CH; ++c) {
+          rd[r][c] = nd[r][c];
+          ry[r][c] = ny[r][c];
+        }
+        rs[r] = ns[r];
+      }
+      base = next;
     }
   }
   // Column sums: first over the groups that share a wave (fixed butterfly), then a binary tree
@@ -481,31 +512,38 @@ tempo_status launch_layernorm_fwd(const void* x, const float* gamma, const float
   return launch_status();
 }
 
-// Rows a lane group fetches at once in the register-resident backward kernel: as many as the
-// knob allows while the packed rows stay within ~64 registers and the grid still has at
-// least one workgroup per compute unit.
-static int bwd_rows(int tuned, int64_t N, const Shape& sh, tempo_dtype dt) {
+// Launch plan of the register-resident backward kernel.  Rows per lane group and batch (r):
+// as many as the knob allows while the packed rows stay within ~64 registers and the grid
+// keeps one workgroup per compute unit.  If that leaves more than two batches per compute
+// unit, workgroups loop with prefetch instead (half the rows per batch, since two batches are
+// then held in registers) on a grid of two workgroups per compute unit.
+struct BwdPlan {
+  int r;
+  bool loop;
+  int grid;
+};
+static BwdPlan bwd_plan(int64_t N, const Shape& sh, tempo_dtype dt) {
+  const int tuned = tune_get(kTuneLnBwdRowsPerGroup);
   const int regs_per_row = sh.ch * (dt == TEMPO_F32 ? 16 : 8);  // dy and y, packed
-  const int groups = kBwdThreads / sh.lanes;
+  const int64_t groups = kBwdThreads / sh.lanes;
+  const int cus = compute_units();
+  auto batches = [&](int r) { return (N + groups * r - 1) / (groups * r); };
   int r = tuned >= 4 ? 4 : (tuned >= 2 ? 2 : 1);
-  while (r > 1 && (r * regs_per_row > 64 ||
-                   (N + static_cast<int64_t>(groups) * r - 1) / (groups * r) < compute_units()))
-    r >>= 1;
-  return r;
+  while (r > 1 && (r * regs_per_row > 64 || batches(r) < cus)) r >>= 1;
+  BwdPlan p = {r, false, static_cast<int>(batches(r) > 4096 ? 4096 : batches(r))};
+  if (batches(r) > 2 * cus) {
+    p.loop = true;
+    p.r = r > 1 ? r / 2 : 1;
+    p.grid = 2 * cus;
+  }
+  if (p.grid < 1) p.grid = 1;
+  return p;
 }
 
 int layernorm_bwd_blocks(int64_t N, int64_t M, tempo_dtype dt) {
   Shape sh;
-  int64_t b;
-  if (fast_shape(M, &sh, kMaxFastBwdM)) {
-    const int64_t rows_per_block =
-        static_cast<int64_t>(kBwdThreads / sh.lanes) * bwd_rows(tune_get(kTuneLnBwdRowsPerGroup), N, sh, dt);
-    b = (N + rows_per_block - 1) / rows_per_block;
-  } else {
-    b = N;
-  }
-  if (b > 4096) b = 4096;  // bounds the workspace (4096 partials of 2*M floats)
-  return static_cast<int>(b < 1 ? 1 : b);
+  if (fast_shape(M, &sh, kMaxFastBwdM)) return bwd_plan(N, sh, dt).grid;
+  return static_cast<int>(N > 4096 ? 4096 : (N < 1 ? 1 : N));  // one row per workgroup, strided
 }
 
 tempo_status launch_layernorm_bwd(const void* dy, const void* y, const float* gamma,
@@ -516,16 +554,22 @@ tempo_status launch_layernorm_bwd(const void* dy, const void* y, const float* ga
   const int grid = layernorm_bwd_blocks(N, M, dt);
   if (fast_shape(M, &sh, kMaxFastBwdM)) {
     const size_t lds_bytes = static_cast<size_t>(kBwdWaves / 2) * 2 * M * sizeof(float);
-    const int rows = bwd_rows(tune_get(kTuneLnBwdRowsPerGroup), N, sh, dt);
-#define TEMPO_LAUNCH_R(T, L, C, RR)                                                          \
-  hipLaunchKernelGGL((ln_bwd_kernel<T, L, C, RR>), dim3(grid), dim3(kBwdThreads), lds_bytes, \
-                     st, static_cast<const T*>(dy), static_cast<const T*>(y), gamma, beta,   \
-                     rstd, static_cast<T*>(dx), workspace, N, static_cast<int>(M))
+    const BwdPlan plan = bwd_plan(N, sh, dt);
+#define TEMPO_LAUNCH_R(T, L, C, RR, LP)                                                      \
+  hipLaunchKernelGGL((ln_bwd_kernel<T, L, C, RR, LP>), dim3(grid), dim3(kBwdThreads),        \
+                     lds_bytes, st, static_cast<const T*>(dy), static_cast<const T*>(y),     \
+                     gamma, beta, rstd, static_cast<T*>(dx), workspace, N,                   \
+                     static_cast<int>(M))
 #define TEMPO_LAUNCH_T(T, L, C)                                                              \
   do {                                                                                       \
-    if (rows == 4 && C <= 2) TEMPO_LAUNCH_R(T, L, C, 4);                                     \
-    else if (rows >= 2 && C <= 4) TEMPO_LAUNCH_R(T, L, C, 2);                                \
-    else TEMPO_LAUNCH_R(T, L, C, 1);                                                         \
+    if (plan.loop) {                                                                         \
+      if (plan.r >= 2 && C <= 2) TEMPO_LAUNCH_R(T, L, C, 2, true);                           \
+      else TEMPO_LAUNCH_R(T, L, C, 1, true);                                                 \
+    } else {                                                                                 \
+      if (plan.r == 4 && C <= 2) TEMPO_LAUNCH_R(T, L, C, 4, false);                          \
+      else if (plan.r >= 2 && C <= 4) TEMPO_LAUNCH_R(T, L, C, 2, false);                     \
+      else TEMPO_LAUNCH_R(T, L, C, 1, false);                                                \
+    }                                                                                        \
   } while (0)
     if (dt == TEMPO_F32) {
 #define TEMPO_LAUNCH(L, C) TEMPO_LAUNCH_T(float, L, C)
