@@ -30,7 +30,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--config", type=int, default=1, help="BASELINE.json config index (0-4)")
+    ap.add_argument("--config", type=int, default=1, help="workload configuration index (0-4)")
     ap.add_argument("--batch", type=int, default=None, help="batch override (config 4 sweep)")
     ap.add_argument("--dtype", choices=["f32", "bf16"], default=None)
     ap.add_argument("--kernel-iters", type=int, default=60, help="launches per kernel timing loop")
@@ -249,7 +249,7 @@ def main():
         dom = max(weight, key=weight.get)
         k = per_kernel[dom]
         roofline = {"kernel": dom, "bound": "hbm", "achieved": k["GB/s"], "peak": HBM_PEAK_GBS,
-                    "unit": "GB/s", "frac": k["frac_of_peak"], "traffic": None,
+                    "unit": "GB/s", "frac": k["frac_of_peak"], "traffic": measured_traffic(cfg, dom),
                     "us_per_launch": k["us"], "algorithmic_bytes": k["bytes"]}
 
     cpu = None
@@ -277,6 +277,21 @@ def main():
         "activation_bytes_saved_per_token": {**saved, "total": sum(saved.values())},
     }
     print(json.dumps(line))
+
+
+def measured_traffic(cfg, kernel):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 FETCH_SIZE / WRITE_SIZE
+    summary of this configuration (counter values scaled by the copy-kernel calibration), or
+    None if no such summary has been recorded for it."""
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_config{cfg.index}.json")
+    if cfg != __import__("paper_2210_10246_amd.workloads", fromlist=["x"]).config(cfg.index):
+        return None          # a batch / dtype override: the recorded counters do not apply
+    try:
+        with open(path) as f:
+            rec = json.load(f)["kernels"][kernel]
+    except (OSError, KeyError, ValueError):
+        return None
+    return int(rec["fetch_bytes"] + rec["write_bytes"])
 
 
 def cpu_baseline(cfg, algo):
