@@ -68,24 +68,98 @@ __device__ __forceinline__ int row_limit(int i, int key_limit, int causal, int S
   return limit;
 }
 
+// Keep bits of the CH pieces a lane owns in one row.  Piece c of the lane is flat piece
+// piece0 + c*LANES + t.  bfloat16 pieces (8 elements) are whole Philox groups.  float32 pieces
+// (4 elements) are half groups: lanes 2k and 2k+1 hold the two halves of the same group for
+// every c, so the pair splits the generator calls (the even lane draws the groups of even c,
+// the odd lane those of odd c) and swaps the bytes with one DPP move.
+template <typename T, int LANES, int CH>
+__device__ __forceinline__ void lane_keep_bits(int64_t piece0, int t, const RngArgs& rng,
+                                               uint32_t (&bits)[CH]) {
+  if constexpr (Store<T>::kVec == 8) {
+#pragma unroll
+    for (int c = 0; c < CH; ++c)
+      bits[c] = keep_byte(static_cast<uint64_t>(piece0 + c * LANES + t), rng);
+  } else {
+    const int odd = t & 1;
+#pragma unroll
+    for (int c = 0; c < CH; c += 2) {
+      const int mine = (c + 1 < CH) ? c + odd : c;  // a trailing single piece: both lanes draw
+      const uint32_t own = keep_byte(static_cast<uint64_t>(piece0 + mine * LANES + t) >> 1, rng);
+      const uint32_t other = dpp_u32<kDppXor1>(own);
+      const uint32_t even_c = (c + 1 < CH) ? (odd ? other : own) : own;
+      bits[c] = (even_c >> (4 * odd)) & 0xFu;
+      if (c + 1 < CH) bits[c + 1] = ((odd ? own : other) >> (4 * odd)) & 0xFu;
+    }
+  }
+}
+
+// Store the mask bits of one piece.  WORDS (Sk % 32 == 0): the lanes sharing a word merge their
+// bits and one of them writes the word; otherwise (Sk % 8 == 0) bytes are written: by every
+// lane (bf16) or by the even lane of each pair (f32).  All lanes of the sharing group must
+// call this together; `valid` says whether the lane's piece exists.
+template <typename T, bool WORDS>
+__device__ __forceinline__ void store_keep_bits(uint32_t* keep_bits, int64_t piece, int t,
+                                                uint32_t bits, bool valid, int64_t total_pieces) {
+  constexpr int V = Store<T>::kVec;
+  if constexpr (WORDS) {
+    const uint32_t word = merge_mask_word<V>(bits, t);
+    constexpr int kShare = 32 / V;
+    if ((t & (kShare - 1)) == 0 && valid) keep_bits[piece / kShare] = word;
+  } else {
+    uint8_t* kb = reinterpret_cast<uint8_t*>(keep_bits);
+    uint32_t byte = bits;
+    int64_t bi = piece;  // byte index
+    bool writer = valid;
+    if constexpr (V == 4) {
+      byte = bits << (4 * (t & 1));
+      byte |= dpp_u32<kDppXor1>(byte);
+      bi = piece >> 1;
+      writer = valid && (t & 1) == 0;
+    }
+    if (writer) {
+      kb[bi] = static_cast<uint8_t>(byte);
+      const int64_t last = (V == 4 ? total_pieces >> 1 : total_pieces) - 1;
+      if (bi == last) {
+        for (int64_t b = bi + 1; (b & 3) != 0; ++b) kb[b] = 0;  // rest of the last word
+      }
+    }
+  }
+}
+
+// Mask bits of one piece as read by backward.
+template <typename T, bool WORDS>
+__device__ __forceinline__ uint32_t load_keep_bits(const uint32_t* keep_bits, int64_t piece) {
+  constexpr int V = Store<T>::kVec;
+  if constexpr (WORDS) {
+    constexpr int kShare = 32 / V;
+    return (keep_bits[piece / kShare] >> (V * static_cast<int>(piece & (kShare - 1)))) &
+           ((1u << V) - 1u);
+  } else {
+    const uint8_t* kb = reinterpret_cast<const uint8_t*>(keep_bits);
+    if constexpr (V == 8) return kb[piece];
+    return (kb[piece >> 1] >> (4 * static_cast<int>(piece & 1))) & 0xFu;
+  }
+}
+
 // Work unit = one "row set": the kThreads/LANES consecutive query rows of one [Sq, Sk] slice
-// that a workgroup handles at once (one row per lane group).  Workgroups walk the row sets
-// grid-stride and every lane group fetches its next row before it starts computing on the
-// current one, so the load latency of a row is hidden behind the arithmetic of the previous
-// one (softmax + Philox is ~35 VALU ops per element, about as long as the memory time).
-// WORDS: Sk % 32 == 0, mask written as whole words (4 lanes merge their bytes); otherwise
-// Sk % 8 == 0 and every lane writes its own byte of the little-endian word.
+// that a workgroup handles at once (one row per lane group, CH 16-byte pieces per lane, piece
+// c of lane t = c*LANES + t).  With the default launch cap every row set has its own
+// workgroup, so the grid sweeps memory front to back; under a smaller cap workgroups walk the
+// row sets grid-stride and fetch the next row before computing on the current one.
 template <typename T, int LANES, int CH, bool WORDS>
 __global__ __launch_bounds__(kThreads) void attn_fwd_kernel(
     const T* scores, const int32_t* __restrict__ key_len, int causal, T* probs,
     T* __restrict__ out, uint32_t* __restrict__ keep_bits, int slices, int A, int Sq, int Sk,
     float scale, RngArgs rng) {
   constexpr int kGroups = kThreads / LANES;
+  constexpr int V = Store<T>::kVec;
   const int g = threadIdx.x / LANES;
   const int t = threadIdx.x % LANES;
-  const int chunks = Sk >> 3;
+  const int pieces = Sk / V;
   const int sets_per_slice = (Sq + kGroups - 1) / kGroups;
   const int64_t total_sets = static_cast<int64_t>(slices) * sets_per_slice;
+  const int64_t total_pieces = static_cast<int64_t>(slices) * Sq * pieces;
 
   // limit (number of leading columns in the softmax) of this lane group's row in row set rs;
   // -1 if the group has no row there
@@ -100,7 +174,7 @@ __global__ __launch_bounds__(kThreads) void attn_fwd_kernel(
   auto fetch = [&](Raw<T> (&raw)[CH], int64_t row, int limit) {
 #pragma unroll
     for (int c = 0; c < CH; ++c) {
-      const int col0 = (c * LANES + t) * 8;
+      const int col0 = (c * LANES + t) * V;
       if (col0 < limit) raw[c].load(scores + row * Sk + col0);
     }
   };
@@ -120,20 +194,20 @@ __global__ __launch_bounds__(kThreads) void attn_fwd_kernel(
       limit_next = locate(rs_next, row_next);
       fetch(nxt, row_next, limit_next);
     }
-    if (limit >= 0) {
-      float v[CH][8];
+    if (limit >= 0) {  // uniform over the lane group
+      float v[CH][V];
       float mx = -INFINITY;
 #pragma unroll
       for (int c = 0; c < CH; ++c) {
-        const int col0 = (c * LANES + t) * 8;
+        const int col0 = (c * LANES + t) * V;
         if (col0 < limit) {
           cur[c].unpack(v[c]);
-          if (col0 + 8 > limit) {  // the chunk the limit falls into
+          if (col0 + V > limit) {  // the piece the limit falls into
 #pragma unroll
-            for (int k = 0; k < 8; ++k) v[c][k] = (col0 + k < limit) ? v[c][k] : -INFINITY;
+            for (int k = 0; k < V; ++k) v[c][k] = (col0 + k < limit) ? v[c][k] : -INFINITY;
           }
 #pragma unroll
-          for (int k = 0; k < 8; ++k) mx = fmaxf(mx, v[c][k]);
+          for (int k = 0; k < V; ++k) mx = fmaxf(mx, v[c][k]);
         }
       }
       mx = group_max<LANES>(mx);
@@ -141,49 +215,40 @@ __global__ __launch_bounds__(kThreads) void attn_fwd_kernel(
       float sum = 0.0f;
 #pragma unroll
       for (int c = 0; c < CH; ++c) {
-        const int col0 = (c * LANES + t) * 8;
+        const int col0 = (c * LANES + t) * V;
         if (col0 < limit) {
 #pragma unroll
-          for (int k = 0; k < 8; ++k) {
+          for (int k = 0; k < V; ++k) {
             const float e = __builtin_amdgcn_exp2f(fmaf(v[c][k], kLog2e, -shift));
             v[c][k] = e;
             sum += e;
           }
         } else {  // masked, or padding beyond the row
 #pragma unroll
-          for (int k = 0; k < 8; ++k) v[c][k] = 0.0f;
+          for (int k = 0; k < V; ++k) v[c][k] = 0.0f;
         }
       }
       sum = group_sum<LANES>(sum);
       const float rinv = (sum > 0.0f) ? __builtin_amdgcn_rcpf(sum) : 0.0f;
-      const int64_t row_chunk0 = row * chunks;
+      const int64_t piece0 = row * pieces;
+      uint32_t bits[CH];
+      lane_keep_bits<T, LANES, CH>(piece0, t, rng, bits);
 #pragma unroll
       for (int c = 0; c < CH; ++c) {
-        const int ch = c * LANES + t;
-        uint32_t byte = 0;
-        if (ch < chunks) {
-          byte = keep_byte(static_cast<uint64_t>(row_chunk0 + ch), rng);
-          float p8[8], o8[8];
+        const int pc = c * LANES + t;
+        const bool valid = pc < pieces;
+        if (valid) {
+          float p8[V], o8[V];
 #pragma unroll
-          for (int k = 0; k < 8; ++k) {
+          for (int k = 0; k < V; ++k) {
             p8[k] = Store<T>::round(v[c][k] * rinv);
-            o8[k] = ((byte >> k) & 1u) ? p8[k] * scale : 0.0f;
+            o8[k] = ((bits[c] >> k) & 1u) ? p8[k] * scale : 0.0f;
           }
-          store8_stream<T>(probs + row * Sk + ch * 8, p8);
-          if (out) store8_stream<T>(out + row * Sk + ch * 8, o8);
+          store_piece<T>(probs + row * Sk + pc * V, p8);
+          if (out) store_piece<T>(out + row * Sk + pc * V, o8);
         }
-        if (WORDS) {
-          // the 4 lanes of a quad share a group, so they are all here together
-          const uint32_t word = merge_quad_bytes(byte, t & 3);
-          if ((t & 3) == 0 && ch < chunks) keep_bits[(row_chunk0 + ch) >> 2] = word;
-        } else if (ch < chunks) {
-          uint8_t* kb = reinterpret_cast<uint8_t*>(keep_bits);
-          const int64_t gi = row_chunk0 + ch;
-          kb[gi] = static_cast<uint8_t>(byte);
-          if (gi == static_cast<int64_t>(slices) * Sq * chunks - 1) {
-            for (int64_t b = gi + 1; (b & 3) != 0; ++b) kb[b] = 0;  // rest of the last word
-          }
-        }
+        store_keep_bits<T, WORDS>(keep_bits, piece0 + pc, t, valid ? bits[c] : 0u, valid,
+                                  total_pieces);
       }
     }
 #pragma unroll
@@ -198,49 +263,48 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_kernel(
     const T* dout, const T* __restrict__ probs, const uint32_t* __restrict__ keep_bits,
     T* dscores, T* __restrict__ out_re, int64_t rows, int Sk, float scale) {
   constexpr int kGroups = kThreads / LANES;
+  constexpr int V = Store<T>::kVec;
   const int g = threadIdx.x / LANES;
   const int t = threadIdx.x % LANES;
-  const int chunks = Sk >> 3;
+  const int pieces = Sk / V;
   for (int64_t row = static_cast<int64_t>(blockIdx.x) * kGroups + g; row < rows;
        row += static_cast<int64_t>(gridDim.x) * kGroups) {
-    const int64_t row_chunk0 = row * chunks;
-    float dp[CH][8], pr[CH][8];
-    uint32_t bytes[CH];
+    const int64_t piece0 = row * pieces;
+    float dp[CH][V], pr[CH][V];
+    uint32_t bits[CH];
     float dot = 0.0f;
 #pragma unroll
     for (int c = 0; c < CH; ++c) {
-      const int ch = c * LANES + t;
-      if (ch < chunks) {
-        load8_stream<T>(dout + row * Sk + ch * 8, dp[c]);
-        load8_stream<T>(probs + row * Sk + ch * 8, pr[c]);
-        const int64_t gi = row_chunk0 + ch;
-        if (WORDS) bytes[c] = keep_bits[gi >> 2] >> (8 * static_cast<int>(gi & 3));
-        else bytes[c] = reinterpret_cast<const uint8_t*>(keep_bits)[gi];
+      const int pc = c * LANES + t;
+      if (pc < pieces) {
+        load_piece<T>(dout + row * Sk + pc * V, dp[c]);
+        load_piece<T>(probs + row * Sk + pc * V, pr[c]);
+        bits[c] = load_keep_bits<T, WORDS>(keep_bits, piece0 + pc);
       } else {
-        bytes[c] = 0;
+        bits[c] = 0;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) dp[c][i] = pr[c][i] = 0.0f;
+        for (int k = 0; k < V; ++k) dp[c][k] = pr[c][k] = 0.0f;
       }
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        dp[c][i] = ((bytes[c] >> i) & 1u) ? dp[c][i] * scale : 0.0f;
-        dot = fmaf(dp[c][i], pr[c][i], dot);
+      for (int k = 0; k < V; ++k) {
+        dp[c][k] = ((bits[c] >> k) & 1u) ? dp[c][k] * scale : 0.0f;
+        dot = fmaf(dp[c][k], pr[c][k], dot);
       }
     }
     dot = group_sum<LANES>(dot);
 #pragma unroll
     for (int c = 0; c < CH; ++c) {
-      const int ch = c * LANES + t;
-      if (ch < chunks) {
-        float ds[8];
+      const int pc = c * LANES + t;
+      if (pc < pieces) {
+        float ds[V];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) ds[i] = pr[c][i] * (dp[c][i] - dot);
-        store8_stream<T>(dscores + row * Sk + ch * 8, ds);
+        for (int k = 0; k < V; ++k) ds[k] = pr[c][k] * (dp[c][k] - dot);
+        store_piece<T>(dscores + row * Sk + pc * V, ds);
         if (out_re) {
-          float o8[8];
+          float o8[V];
 #pragma unroll
-          for (int i = 0; i < 8; ++i) o8[i] = ((bytes[c] >> i) & 1u) ? pr[c][i] * scale : 0.0f;
-          store8_stream<T>(out_re + row * Sk + ch * 8, o8);
+          for (int k = 0; k < V; ++k) o8[k] = ((bits[c] >> k) & 1u) ? pr[c][k] * scale : 0.0f;
+          store_piece<T>(out_re + row * Sk + pc * V, o8);
         }
       }
     }
@@ -335,16 +399,16 @@ struct Shape {
   int ch;
 };
 
-// One chunk per lane while the row fits in a wave (every access of a wave is then one
-// contiguous run of 16-byte pieces), more chunks per lane for longer rows.
-// ch == 0: row too long for registers.
-Shape pick_shape(int chunks) {
-  int lanes = 4;
-  while (lanes < 64 && lanes < chunks) lanes <<= 1;
-  const int need = (chunks + lanes - 1) / lanes;
-  static const int allowed[] = {1, 2, 3, 4, 6, 8};
+// One piece per lane while the row fits in a wave (every access of a wave is then one
+// contiguous run of 16-byte pieces), more pieces per lane for longer rows.  min_lanes: 4 for
+// bfloat16, 8 for float32 (the lanes that share a mask word).  ch == 0: row too long.
+Shape pick_shape(int pieces, int min_lanes) {
+  int lanes = min_lanes;
+  while (lanes < 64 && lanes < pieces) lanes <<= 1;
+  const int need = (pieces + lanes - 1) / lanes;
+  static const int allowed[] = {1, 2, 3, 4, 6, 8, 12, 16};
   for (int a : allowed)
-    if (a >= need) return {lanes, a};
+    if (a >= need) return {lanes, lanes == 64 || a == 1 ? a : 0};
   return {0, 0};
 }
 
@@ -370,6 +434,8 @@ int row_grid(int64_t rows, int lanes, int blocks_per_cu) {
     case 6404: LAUNCH(64, 4); break;                                                       \
     case 6406: LAUNCH(64, 6); break;                                                       \
     case 6408: LAUNCH(64, 8); break;                                                       \
+    case 6412: LAUNCH(64, 12); break;                                                      \
+    case 6416: LAUNCH(64, 16); break;                                                      \
     default: return TEMPO_ERR_UNSUPPORTED;                                                 \
   }
 
@@ -389,7 +455,8 @@ tempo_status launch_attn_fwd(const void* scores, const int32_t* key_len, int cau
   t = t < 0.0 ? 0.0 : (t > 65536.0 ? 65536.0 : t);
   rng.t16 = (p == 0.0f) ? 65536u : static_cast<uint32_t>(t);  // floor for t >= 0
   const int bpc = tune_get(kTuneAttnFwdBlocksPerCu);
-  Shape sh = pick_shape(static_cast<int>(Sk / 8));
+  const int vec = dt == TEMPO_F32 ? 4 : 8;
+  Shape sh = pick_shape(static_cast<int>(Sk / vec), 32 / vec);
   if (Sk % 8 == 0 && sh.ch != 0 && B * A <= INT32_MAX) {
     const int slices = static_cast<int>(B * A);
     const int groups = kThreads / sh.lanes;
@@ -444,7 +511,8 @@ tempo_status launch_attn_bwd(const void* dout, const void* probs, const uint32_t
   const int64_t rows = B * A * Sq;
   const float scale = 1.0f / (1.0f - p);
   const int bpc = tune_get(kTuneAttnBwdBlocksPerCu);
-  Shape sh = pick_shape(static_cast<int>(Sk / 8));
+  const int vec = dt == TEMPO_F32 ? 4 : 8;
+  Shape sh = pick_shape(static_cast<int>(Sk / vec), 32 / vec);
   if (Sk % 8 == 0 && sh.ch != 0) {
     const int grid = row_grid(rows, sh.lanes, bpc);
     const bool words = (Sk % 32 == 0);

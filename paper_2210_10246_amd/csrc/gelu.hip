@@ -1,10 +1,11 @@
 // In-place GELU for gfx950: forward writes y and a 1-bit "side of the minimum" mask, backward
 // evaluates GELU'(GELU*^-1(y, m)) from the stored output (Sec. 3.1; App. E.1 eq. 1-2; App. F.1).
 //
-// Both kernels are streaming: every lane owns chunks of 8 consecutive elements (one 16-byte
-// access in bf16, two in f32); the 8 mask bits of a chunk are merged over 4 adjacent lanes so
-// the mask is written and read as whole 32-bit words.  The piecewise-cubic tables live in LDS
-// (one 16-byte row per piece, fetched with a single ds_read_b128 per element).
+// Both kernels are streaming: every lane owns 16-byte pieces (8 bf16 or 4 f32 elements); the
+// mask bits of a piece are merged over the 4 (bf16) or 8 (f32) adjacent lanes that share a
+// word, so the mask is written and read as whole 32-bit words.  float32 evaluates piecewise
+// cubics whose coefficient rows live in LDS (one ds_read_b128 per element); bfloat16 looks the
+// function value up per bit pattern.
 #include "tempo_device.h"
 #include "tempo_host.h"
 
@@ -103,85 +104,85 @@ __device__ __forceinline__ void load_table(f32x4* lds, const uint32_t (*src)[4])
 }
 
 
-// Work decomposition (both kernels): workgroup b owns the contiguous tile of kThreads*K chunks
-// starting at chunk b*kThreads*K; chunk k of lane t is tile_base + k*kThreads + t, so each
-// access of a wave is one contiguous 1 KiB (bf16) run, workgroups are short-lived, and the
-// whole grid sweeps memory front to back.  All of a lane's loads are issued before the table
-// is staged into LDS, so the two latencies overlap.
-template <typename T, int KIND, int K>
-__global__ __launch_bounds__(kThreads) void gelu_fwd_kernel(const T* x, T* y,  // may alias
+// ---- float32 storage: piecewise cubics ------------------------------------------------------
+// Work decomposition: workgroup b owns the contiguous tile of kThreads*K pieces (4 floats each)
+// starting at piece b*kThreads*K; piece k of lane t is tile_base + k*kThreads + t, so each
+// access of a wave is one contiguous 1 KiB run, workgroups are short-lived, and the whole grid
+// sweeps memory front to back.  All of a lane's loads are issued before the table is staged
+// into LDS, so the two latencies overlap.  8 lanes share a 32-bit mask word.
+template <int KIND, int K>
+__global__ __launch_bounds__(kThreads) void gelu_fwd_kernel(const float* x, float* y,  // may alias
                                                             uint32_t* __restrict__ mask,
                                                             int64_t n) {
   __shared__ f32x4 tab[KIND == TEMPO_GELU_ERF ? TEMPO_GELU_FWD_ROWS : 1];
   const float xstar = as_f32(GeluConst<KIND>::xstar);
-  const int lane = threadIdx.x & (kWave - 1);
   const int64_t q_base = static_cast<int64_t>(blockIdx.x) * (kThreads * K) + threadIdx.x;
-  float v[K][8];
+  float v[K][4];
 #pragma unroll
   for (int k = 0; k < K; ++k) {
     const int64_t q = q_base + k * kThreads;
-    const int64_t left = n - q * 8;
+    const int64_t left = n - q * 4;
     if (left > 0) {
-      load8_guarded<T>(x + q * 8, left, v[k], -1.0e30f);
+      load_piece_guarded<float>(x + q * 4, left, v[k], -1.0e30f);
     } else {
 #pragma unroll
-      for (int i = 0; i < 8; ++i) v[k][i] = -1.0e30f;
+      for (int i = 0; i < 4; ++i) v[k][i] = -1.0e30f;  // absent: mask bit 0
     }
   }
   if (KIND == TEMPO_GELU_ERF) load_table<TEMPO_GELU_FWD_ROWS>(tab, tempo_gelu_fwd_table_erf);
 #pragma unroll
   for (int k = 0; k < K; ++k) {
     const int64_t q = q_base + k * kThreads;
-    const int64_t left = n - q * 8;
-    uint32_t byte = 0;
-    float r[8];
+    const int64_t left = n - q * 4;
+    uint32_t bits = 0;
+    float r[4];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
+    for (int i = 0; i < 4; ++i) {
       const float xv = v[k][i];
-      byte |= (xv >= xstar ? 1u : 0u) << i;
+      bits |= (xv >= xstar ? 1u : 0u) << i;
       r[i] = (KIND == TEMPO_GELU_ERF) ? gelu_erf_value(xv, tab) : gelu_tanh_value(xv);
     }
-    // every lane of the wave takes part in the merge; absent chunks contribute zero bits
-    const uint32_t word = merge_quad_bytes(byte, lane & 3);
-    if (left > 0) store8_guarded<T>(y + q * 8, left, r);
-    if ((lane & 3) == 0 && left > 0) mask[q >> 2] = word;
+    // every lane of the wave takes part in the merge; absent pieces contribute zero bits
+    const uint32_t word = merge_mask_word<4>(bits, threadIdx.x);
+    if (left > 0) store_piece_guarded<float>(y + q * 4, left, r);
+    if ((threadIdx.x & 7) == 0 && left > 0) mask[q >> 3] = word;
   }
 }
 
-template <typename T, int KIND, int K>
-__global__ __launch_bounds__(kThreads) void gelu_bwd_kernel(const T* dy,  // may alias dx
-                                                            const T* __restrict__ y,
+template <int KIND, int K>
+__global__ __launch_bounds__(kThreads) void gelu_bwd_kernel(const float* dy,  // may alias dx
+                                                            const float* __restrict__ y,
                                                             const uint32_t* __restrict__ mask,
-                                                            T* dx, int64_t n) {
+                                                            float* dx, int64_t n) {
   __shared__ f32x4 tab[TEMPO_GELU_BWD_ROWS];
   const int64_t q_base = static_cast<int64_t>(blockIdx.x) * (kThreads * K) + threadIdx.x;
-  float g[K][8], o[K][8];
+  float g[K][4], o[K][4];
   uint32_t w[K];
 #pragma unroll
   for (int k = 0; k < K; ++k) {
     const int64_t q = q_base + k * kThreads;
-    const int64_t left = n - q * 8;
+    const int64_t left = n - q * 4;
     w[k] = 0;
     if (left > 0) {
-      load8_guarded<T>(dy + q * 8, left, g[k], 0.0f);
-      load8_guarded<T>(y + q * 8, left, o[k], 0.0f);
-      w[k] = __builtin_nontemporal_load(mask + (q >> 2));
+      load_piece_guarded<float>(dy + q * 4, left, g[k], 0.0f);
+      load_piece_guarded<float>(y + q * 4, left, o[k], 0.0f);
+      w[k] = __builtin_nontemporal_load(mask + (q >> 3));
     }
   }
   load_table<TEMPO_GELU_BWD_ROWS>(tab, GeluConst<KIND>::bwd_table());
 #pragma unroll
   for (int k = 0; k < K; ++k) {
     const int64_t q = q_base + k * kThreads;
-    const int64_t left = n - q * 8;
+    const int64_t left = n - q * 4;
     if (left <= 0) continue;
-    const uint32_t byte = w[k] >> (8 * static_cast<int>(q & 3));
-    float r[8];
+    const uint32_t bits = w[k] >> (4 * static_cast<int>(q & 7));
+    float r[4];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const bool right = (byte >> i) & 1u;
+    for (int i = 0; i < 4; ++i) {
+      const bool right = (bits >> i) & 1u;
       r[i] = g[k][i] * gelu_composite<KIND>(o[k][i], right, tab);
     }
-    store8_guarded<T>(dx + q * 8, left, r);
+    store_piece_guarded<float>(dx + q * 4, left, r);
   }
 }
 
@@ -341,7 +342,7 @@ __global__ __launch_bounds__(kLutThreads) void gelu_fwd_lut_kernel(const bf16_t*
     uint32_t byte;
     gelu_fwd_lut_chunk(w[k], lut, yw, byte);
     // every lane of the wave takes part in the merge; absent chunks contribute zero bits
-    const uint32_t word = merge_quad_bytes(byte, lane & 3);
+    const uint32_t word = merge_mask_word<8>(byte, lane);
     if (full) {
       stg_stream(y + q * 8, yw);
       if ((lane & 3) == 0) mask[q >> 2] = word;
@@ -412,10 +413,10 @@ int lut_grid(int64_t n, int k) {
 }
 
 
-int tile_grid(int64_t n, int k) {
-  const int64_t n_chunks = (n + 7) / 8;
+int tile_grid(int64_t n, int k) {  // float32 pieces of 4 elements
+  const int64_t n_pieces = (n + 3) / 4;
   const int64_t per_block = static_cast<int64_t>(kThreads) * k;
-  return static_cast<int>((n_chunks + per_block - 1) / per_block);
+  return static_cast<int>((n_pieces + per_block - 1) / per_block);
 }
 
 int pick_k(int tuned) { return tuned >= 4 ? 4 : (tuned >= 2 ? 2 : 1); }
@@ -425,26 +426,14 @@ int pick_k(int tuned) { return tuned >= 4 ? 4 : (tuned >= 2 ? 2 : 1); }
 #define TEMPO_GELU_DISPATCH(KERNEL, ...)                                                     \
   do {                                                                                       \
     const int grid = tile_grid(n, k);                                                        \
-    if (dt == TEMPO_F32) {                                                                   \
-      if (kind == TEMPO_GELU_ERF) {                                                          \
-        if (k == 1) TEMPO_GO(KERNEL, float, TEMPO_GELU_ERF, 1, __VA_ARGS__);                 \
-        else if (k == 2) TEMPO_GO(KERNEL, float, TEMPO_GELU_ERF, 2, __VA_ARGS__);            \
-        else TEMPO_GO(KERNEL, float, TEMPO_GELU_ERF, 4, __VA_ARGS__);                        \
-      } else {                                                                               \
-        if (k == 1) TEMPO_GO(KERNEL, float, TEMPO_GELU_TANH, 1, __VA_ARGS__);                \
-        else if (k == 2) TEMPO_GO(KERNEL, float, TEMPO_GELU_TANH, 2, __VA_ARGS__);           \
-        else TEMPO_GO(KERNEL, float, TEMPO_GELU_TANH, 4, __VA_ARGS__);                       \
-      }                                                                                      \
+    if (kind == TEMPO_GELU_ERF) {                                                            \
+      if (k == 1) hipLaunchKernelGGL((KERNEL<TEMPO_GELU_ERF, 1>), dim3(grid), dim3(kThreads), 0, st, __VA_ARGS__);       \
+      else if (k == 2) hipLaunchKernelGGL((KERNEL<TEMPO_GELU_ERF, 2>), dim3(grid), dim3(kThreads), 0, st, __VA_ARGS__);  \
+      else hipLaunchKernelGGL((KERNEL<TEMPO_GELU_ERF, 4>), dim3(grid), dim3(kThreads), 0, st, __VA_ARGS__);              \
     } else {                                                                                 \
-      if (kind == TEMPO_GELU_ERF) {                                                          \
-        if (k == 1) TEMPO_GO(KERNEL, bf16_t, TEMPO_GELU_ERF, 1, __VA_ARGS__);                \
-        else if (k == 2) TEMPO_GO(KERNEL, bf16_t, TEMPO_GELU_ERF, 2, __VA_ARGS__);           \
-        else TEMPO_GO(KERNEL, bf16_t, TEMPO_GELU_ERF, 4, __VA_ARGS__);                       \
-      } else {                                                                               \
-        if (k == 1) TEMPO_GO(KERNEL, bf16_t, TEMPO_GELU_TANH, 1, __VA_ARGS__);               \
-        else if (k == 2) TEMPO_GO(KERNEL, bf16_t, TEMPO_GELU_TANH, 2, __VA_ARGS__);          \
-        else TEMPO_GO(KERNEL, bf16_t, TEMPO_GELU_TANH, 4, __VA_ARGS__);                      \
-      }                                                                                      \
+      if (k == 1) hipLaunchKernelGGL((KERNEL<TEMPO_GELU_TANH, 1>), dim3(grid), dim3(kThreads), 0, st, __VA_ARGS__);      \
+      else if (k == 2) hipLaunchKernelGGL((KERNEL<TEMPO_GELU_TANH, 2>), dim3(grid), dim3(kThreads), 0, st, __VA_ARGS__); \
+      else hipLaunchKernelGGL((KERNEL<TEMPO_GELU_TANH, 4>), dim3(grid), dim3(kThreads), 0, st, __VA_ARGS__);             \
     }                                                                                        \
   } while (0)
 
@@ -470,11 +459,8 @@ tempo_status launch_gelu_fwd(const void* x, void* y, uint32_t* mask, int64_t n, 
                        mask, n);
     return launch_status();
   }
-#define TEMPO_GO(KERNEL, T, KIND, K, ...)                                                    \
-  hipLaunchKernelGGL((KERNEL<T, KIND, K>), dim3(grid), dim3(kThreads), 0, st,                \
-                     static_cast<const T*>(x), static_cast<T*>(y), mask, n)
-  TEMPO_GELU_DISPATCH(gelu_fwd_kernel, 0);
-#undef TEMPO_GO
+  TEMPO_GELU_DISPATCH(gelu_fwd_kernel, static_cast<const float*>(x), static_cast<float*>(y), mask,
+                      n);
   return launch_status();
 }
 
@@ -486,12 +472,8 @@ tempo_status launch_gelu_bwd(const void* dy, const void* y, const uint32_t* mask
                        static_cast<const bf16_t*>(y), mask, static_cast<bf16_t*>(dx), n);
     return launch_status();
   }
-#define TEMPO_GO(KERNEL, T, KIND, K, ...)                                                    \
-  hipLaunchKernelGGL((KERNEL<T, KIND, K>), dim3(grid), dim3(kThreads), 0, st,                \
-                     static_cast<const T*>(dy), static_cast<const T*>(y), mask,              \
-                     static_cast<T*>(dx), n)
-  TEMPO_GELU_DISPATCH(gelu_bwd_kernel, 0);
-#undef TEMPO_GO
+  TEMPO_GELU_DISPATCH(gelu_bwd_kernel, static_cast<const float*>(dy),
+                      static_cast<const float*>(y), mask, static_cast<float*>(dx), n);
   return launch_status();
 }
 

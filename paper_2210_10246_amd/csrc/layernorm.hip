@@ -1,7 +1,7 @@
 // In-place LayerNorm for gfx950 (Sec. 3.2; App. D.2, D.3).
 //
-// Forward: a group of LANES lanes owns one row, held entirely in registers (CH chunks of 8
-// elements per lane), so x is read once; mean and the biased variance are taken in two
+// Forward: a group of LANES lanes owns one row, held entirely in registers (CH 16-byte pieces
+// per lane, piece c of lane t = c*LANES + t), so x is read once; mean and the biased variance are taken in two
 // register passes; gamma/beta stay in registers across the rows a group walks.
 // Backward: same ownership; xhat is rebuilt from the OUTPUT as (y - beta)/gamma, the two row
 // sums are butterfly-reduced, and the column sums for dgamma/dbeta are carried in registers
@@ -16,51 +16,48 @@ namespace {
 constexpr int kFwdThreads = 256;
 constexpr int kBwdWaves = 8;
 constexpr int kBwdThreads = kBwdWaves * kWave;
-constexpr int kMaxFastM = 4096;      // forward: 64 lanes x 8 chunks x 8 elements
-constexpr int kMaxFastBwdM = 2048;   // backward: the LDS tree needs 16 M bytes (64 KiB limit)
-
-__device__ __forceinline__ void load_param8(const float* p, float (&v)[8]) {
-  Store<float>::load8(p, v);
-}
+constexpr int kMaxFastM = 4096;  // rows longer than this take the generic kernels; the backward
+                                 // LDS tree needs 16*M bytes (64 KiB at 4096)
 
 template <typename T, int LANES, int CH>
 __global__ __launch_bounds__(kFwdThreads) void ln_fwd_kernel(
     const T* x, const float* __restrict__ gamma, const float* __restrict__ beta, T* y,
     float* __restrict__ rstd_out, float* __restrict__ mean_out, int64_t N, int M, float eps) {
   constexpr int kGroups = kFwdThreads / LANES;
+  constexpr int V = Store<T>::kVec;
   const int g = threadIdx.x / LANES;
   const int t = threadIdx.x % LANES;
-  const int chunks = M >> 3;
+  const int chunks = M / V;
   const float inv_m = 1.0f / static_cast<float>(M);
-  float ga[CH][8], be[CH][8];
+  float ga[CH][V], be[CH][V];
 #pragma unroll
   for (int c = 0; c < CH; ++c) {
     const int ch = c * LANES + t;
     if (ch < chunks) {
-      load_param8(gamma + ch * 8, ga[c]);
-      load_param8(beta + ch * 8, be[c]);
+      load_floats<V>(gamma + ch * V, ga[c]);
+      load_floats<V>(beta + ch * V, be[c]);
     } else {
 #pragma unroll
-      for (int i = 0; i < 8; ++i) ga[c][i] = be[c][i] = 0.0f;
+      for (int i = 0; i < V; ++i) ga[c][i] = be[c][i] = 0.0f;
     }
   }
   for (int64_t row = static_cast<int64_t>(blockIdx.x) * kGroups + g; row < N;
        row += static_cast<int64_t>(gridDim.x) * kGroups) {
     const T* xr = x + row * M;
     T* yr = y + row * M;
-    float v[CH][8];
+    float v[CH][V];
     float sum = 0.0f;
 #pragma unroll
     for (int c = 0; c < CH; ++c) {
       const int ch = c * LANES + t;
       if (ch < chunks) {
-        load8_stream<T>(xr + ch * 8, v[c]);
+        load_piece<T>(xr + ch * V, v[c]);
       } else {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) v[c][i] = 0.0f;
+        for (int i = 0; i < V; ++i) v[c][i] = 0.0f;
       }
 #pragma unroll
-      for (int i = 0; i < 8; ++i) sum += v[c][i];
+      for (int i = 0; i < V; ++i) sum += v[c][i];
     }
     const float mu = group_sum<LANES>(sum) * inv_m;
     float sq = 0.0f;
@@ -68,7 +65,7 @@ __global__ __launch_bounds__(kFwdThreads) void ln_fwd_kernel(
     for (int c = 0; c < CH; ++c) {
       const int ch = c * LANES + t;
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
+      for (int i = 0; i < V; ++i) {
         const float d = v[c][i] - mu;
         v[c][i] = d;
         sq += (ch < chunks) ? d * d : 0.0f;
@@ -80,10 +77,10 @@ __global__ __launch_bounds__(kFwdThreads) void ln_fwd_kernel(
     for (int c = 0; c < CH; ++c) {
       const int ch = c * LANES + t;
       if (ch < chunks) {
-        float o[8];
+        float o[V];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) o[i] = fmaf(v[c][i] * rs, ga[c][i], be[c][i]);
-        store8_stream<T>(yr + ch * 8, o);
+        for (int i = 0; i < V; ++i) o[i] = fmaf(v[c][i] * rs, ga[c][i], be[c][i]);
+        store_piece<T>(yr + ch * V, o);
       }
     }
     if (t == 0) {
@@ -147,11 +144,12 @@ __global__ __launch_bounds__(kBwdThreads) void ln_bwd_kernel(
     float* __restrict__ partial, int64_t N, int M) {
   extern __shared__ float lds[];  // [kBwdWaves/2][2][M] floats (>= 3*M)
   constexpr int kGroups = kBwdThreads / LANES;
+  constexpr int V = Store<T>::kVec;
   const int g = threadIdx.x / LANES;
   const int t = threadIdx.x % LANES;
   const int wave = threadIdx.x / kWave;
   const int lane = threadIdx.x & (kWave - 1);
-  const int chunks = M >> 3;
+  const int chunks = M / V;
   const float inv_m = 1.0f / static_cast<float>(M);
   const int64_t batch_rows = kGroups * R;
   // gamma, 1/gamma and beta/gamma live in LDS (the first 3*M floats; the same memory is
@@ -159,11 +157,11 @@ __global__ __launch_bounds__(kBwdThreads) void ln_bwd_kernel(
   float* p_ga = lds;
   float* p_rg = lds + M;
   float* p_bg = lds + 2 * M;
-  float acc_g[CH][8], acc_b[CH][8];
+  float acc_g[CH][V], acc_b[CH][V];
 #pragma unroll
   for (int c = 0; c < CH; ++c) {
 #pragma unroll
-    for (int i = 0; i < 8; ++i) acc_g[c][i] = acc_b[c][i] = 0.0f;
+    for (int i = 0; i < V; ++i) acc_g[c][i] = acc_b[c][i] = 0.0f;
   }
 
   auto fetch = [&](int64_t base, Raw<T> (&fd)[R][CH], Raw<T> (&fy)[R][CH], float (&fs)[R]) {
@@ -176,8 +174,8 @@ __global__ __launch_bounds__(kBwdThreads) void ln_bwd_kernel(
         for (int c = 0; c < CH; ++c) {
           const int ch = c * LANES + t;
           if (ch < chunks) {
-            fd[r][c].load(dy + row * M + ch * 8);
-            fy[r][c].load(y + row * M + ch * 8);
+            fd[r][c].load(dy + row * M + ch * V);
+            fy[r][c].load(y + row * M + ch * V);
           }
         }
         fs[r] = rstd[row];
@@ -217,14 +215,14 @@ __global__ __launch_bounds__(kBwdThreads) void ln_bwd_kernel(
       for (int c = 0; c < CH; ++c) {
         const int ch = c * LANES + t;
         if (ch < chunks) {
-          float d8[8], y8[8], ga[8], rg[8], bg[8];
+          float d8[V], y8[V], ga[V], rg[V], bg[V];
           rd[r][c].unpack(d8);
           ry[r][c].unpack(y8);
-          load_param8(p_ga + ch * 8, ga);
-          load_param8(p_rg + ch * 8, rg);
-          load_param8(p_bg + ch * 8, bg);
+          load_floats<V>(p_ga + ch * V, ga);
+          load_floats<V>(p_rg + ch * V, rg);
+          load_floats<V>(p_bg + ch * V, bg);
 #pragma unroll
-          for (int i = 0; i < 8; ++i) {
+          for (int i = 0; i < V; ++i) {
             const float h = fmaf(y8[i], rg[i], -bg[i]);  // xhat = (y - beta) / gamma
             const float q = d8[i] * ga[i];
             c1[r] = fmaf(q, h, c1[r]);
@@ -249,18 +247,18 @@ __global__ __launch_bounds__(kBwdThreads) void ln_bwd_kernel(
       for (int c = 0; c < CH; ++c) {
         const int ch = c * LANES + t;
         if (ch < chunks) {
-          float d8[8], y8[8], o[8], ga[8], rg[8], bg[8];
+          float d8[V], y8[V], o[V], ga[V], rg[V], bg[V];
           rd[r][c].unpack(d8);
           ry[r][c].unpack(y8);
-          load_param8(p_ga + ch * 8, ga);
-          load_param8(p_rg + ch * 8, rg);
-          load_param8(p_bg + ch * 8, bg);
+          load_floats<V>(p_ga + ch * V, ga);
+          load_floats<V>(p_rg + ch * V, rg);
+          load_floats<V>(p_bg + ch * V, bg);
 #pragma unroll
-          for (int i = 0; i < 8; ++i) {
+          for (int i = 0; i < V; ++i) {
             const float h = fmaf(y8[i], rg[i], -bg[i]);
             o[i] = rs[r] * (d8[i] * ga[i] - fmaf(h, c1[r], c2[r]));
           }
-          store8_stream<T>(dx + row * M + ch * 8, o);
+          store_piece<T>(dx + row * M + ch * V, o);
         }
       }
     }
@@ -284,7 +282,7 @@ __global__ __launch_bounds__(kBwdThreads) void ln_bwd_kernel(
 #pragma unroll
   for (int c = 0; c < CH; ++c) {
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
+    for (int i = 0; i < V; ++i) {
 #pragma unroll
       for (int m = LANES; m < kWave; m <<= 1) {
         acc_g[c][i] += __shfl_xor(acc_g[c][i], m, kWave);
@@ -302,8 +300,8 @@ __global__ __launch_bounds__(kBwdThreads) void ln_bwd_kernel(
       for (int c = 0; c < CH; ++c) {
         const int ch = c * LANES + t;
         if (ch < chunks) {
-          Store<float>::store8(slot + ch * 8, acc_g[c]);
-          Store<float>::store8(slot + M + ch * 8, acc_b[c]);
+          store_floats<V>(slot + ch * V, acc_g[c]);
+          store_floats<V>(slot + M + ch * V, acc_b[c]);
         }
       }
     }
@@ -314,11 +312,11 @@ __global__ __launch_bounds__(kBwdThreads) void ln_bwd_kernel(
       for (int c = 0; c < CH; ++c) {
         const int ch = c * LANES + t;
         if (ch < chunks) {
-          float a[8], b[8];
-          Store<float>::load8(slot + ch * 8, a);
-          Store<float>::load8(slot + M + ch * 8, b);
+          float a[V], b[V];
+          load_floats<V>(slot + ch * V, a);
+          load_floats<V>(slot + M + ch * V, b);
 #pragma unroll
-          for (int i = 0; i < 8; ++i) {
+          for (int i = 0; i < V; ++i) {
             acc_g[c][i] += a[i];
             acc_b[c][i] += b[i];
           }
@@ -332,8 +330,8 @@ __global__ __launch_bounds__(kBwdThreads) void ln_bwd_kernel(
     for (int c = 0; c < CH; ++c) {
       const int ch = c * LANES + t;
       if (ch < chunks) {
-        Store<float>::store8(slot + ch * 8, acc_g[c]);
-        Store<float>::store8(slot + M + ch * 8, acc_b[c]);
+        store_floats<V>(slot + ch * V, acc_g[c]);
+        store_floats<V>(slot + M + ch * V, acc_b[c]);
       }
     }
   }
@@ -422,20 +420,23 @@ struct Shape {
   int ch;
 };
 
-// Lanes per row and chunks per lane for a row of `chunks` 8-element chunks: least padding,
-// then the widest group.  ch == 0: no register-resident shape fits.
-Shape pick_shape(int chunks) {
-  static const int allowed[] = {1, 2, 3, 4, 6, 8};
+// Lanes per row and pieces per lane for a row of `pieces` 16-byte pieces: least padding, then
+// the widest group.  ch == 0: no register-resident shape fits.
+Shape pick_shape(int pieces) {
+  static const int wide[] = {1, 2, 3, 4, 6, 8, 12, 16};  // 64 lanes
+  static const int narrow[] = {1, 2, 3};                 // 32 and 16 lanes
   Shape best = {0, 0};
   int best_waste = 1 << 30;
   for (int lanes = 64; lanes >= 16; lanes >>= 1) {
-    const int need = (chunks + lanes - 1) / lanes;
-    for (int a : allowed) {
-      if (a >= need) {
-        const int waste = lanes * a - chunks;
+    const int need = (pieces + lanes - 1) / lanes;
+    const int* allowed = lanes == 64 ? wide : narrow;
+    const int count = lanes == 64 ? 8 : 3;
+    for (int k = 0; k < count; ++k) {
+      if (allowed[k] >= need) {
+        const int waste = lanes * allowed[k] - pieces;
         if (waste < best_waste) {
           best_waste = waste;
-          best = {lanes, a};
+          best = {lanes, allowed[k]};
         }
         break;
       }
@@ -454,24 +455,21 @@ Shape pick_shape(int chunks) {
     case 6404: LAUNCH(64, 4); break;                                                       \
     case 6406: LAUNCH(64, 6); break;                                                       \
     case 6408: LAUNCH(64, 8); break;                                                       \
+    case 6412: LAUNCH(64, 12); break;                                                      \
+    case 6416: LAUNCH(64, 16); break;                                                      \
     case 3201: LAUNCH(32, 1); break;                                                       \
     case 3202: LAUNCH(32, 2); break;                                                       \
     case 3203: LAUNCH(32, 3); break;                                                       \
-    case 3204: LAUNCH(32, 4); break;                                                       \
-    case 3206: LAUNCH(32, 6); break;                                                       \
-    case 3208: LAUNCH(32, 8); break;                                                       \
     case 1601: LAUNCH(16, 1); break;                                                       \
     case 1602: LAUNCH(16, 2); break;                                                       \
     case 1603: LAUNCH(16, 3); break;                                                       \
-    case 1604: LAUNCH(16, 4); break;                                                       \
-    case 1606: LAUNCH(16, 6); break;                                                       \
-    case 1608: LAUNCH(16, 8); break;                                                       \
     default: return TEMPO_ERR_UNSUPPORTED;                                                 \
   }
 
-static bool fast_shape(int64_t M, Shape* sh, int64_t max_m = kMaxFastM) {
-  if (M % 8 != 0 || M > max_m) return false;
-  *sh = pick_shape(static_cast<int>(M / 8));
+static bool fast_shape(int64_t M, tempo_dtype dt, Shape* sh) {
+  const int vec = dt == TEMPO_F32 ? 4 : 8;
+  if (M % vec != 0 || M > kMaxFastM) return false;
+  *sh = pick_shape(static_cast<int>(M / vec));
   return sh->ch != 0;
 }
 
@@ -480,7 +478,7 @@ tempo_status launch_layernorm_fwd(const void* x, const float* gamma, const float
                                   tempo_dtype dt, hipStream_t st) {
   Shape sh;
   const int64_t cap = static_cast<int64_t>(compute_units()) * tune_get(kTuneLnFwdBlocksPerCu);
-  if (fast_shape(M, &sh)) {
+  if (fast_shape(M, dt, &sh)) {
     const int groups = kFwdThreads / sh.lanes;
     const int64_t want = (N + groups - 1) / groups;
     const int grid = static_cast<int>(want < cap ? want : cap);
@@ -524,7 +522,8 @@ struct BwdPlan {
 };
 static BwdPlan bwd_plan(int64_t N, const Shape& sh, tempo_dtype dt) {
   const int tuned = tune_get(kTuneLnBwdRowsPerGroup);
-  const int regs_per_row = sh.ch * (dt == TEMPO_F32 ? 16 : 8);  // dy and y, packed
+  const int regs_per_row = sh.ch * 8;  // dy and y, 4 registers per packed piece
+  (void)dt;
   const int64_t groups = kBwdThreads / sh.lanes;
   const int cus = compute_units();
   auto batches = [&](int r) { return (N + groups * r - 1) / (groups * r); };
@@ -542,7 +541,7 @@ static BwdPlan bwd_plan(int64_t N, const Shape& sh, tempo_dtype dt) {
 
 int layernorm_bwd_blocks(int64_t N, int64_t M, tempo_dtype dt) {
   Shape sh;
-  if (fast_shape(M, &sh, kMaxFastBwdM)) return bwd_plan(N, sh, dt).grid;
+  if (fast_shape(M, dt, &sh)) return bwd_plan(N, sh, dt).grid;
   return static_cast<int>(N > 4096 ? 4096 : (N < 1 ? 1 : N));  // one row per workgroup, strided
 }
 
@@ -552,7 +551,7 @@ tempo_status launch_layernorm_bwd(const void* dy, const void* y, const float* ga
                                   tempo_dtype dt, hipStream_t st) {
   Shape sh;
   const int grid = layernorm_bwd_blocks(N, M, dt);
-  if (fast_shape(M, &sh, kMaxFastBwdM)) {
+  if (fast_shape(M, dt, &sh)) {
     const size_t lds_bytes = static_cast<size_t>(kBwdWaves / 2) * 2 * M * sizeof(float);
     const BwdPlan plan = bwd_plan(N, sh, dt);
 #define TEMPO_LAUNCH_R(T, L, C, RR, LP)                                                      \
