@@ -142,12 +142,14 @@ __device__ __forceinline__ uint32_t load_keep_bits(const uint32_t* keep_bits, in
   }
 }
 
-// Work unit = one "row set": the kThreads/LANES consecutive query rows of one [Sq, Sk] slice
-// that a workgroup handles at once (one row per lane group, CH 16-byte pieces per lane, piece
-// c of lane t = c*LANES + t).  With the default launch cap every row set has its own
-// workgroup, so the grid sweeps memory front to back; under a smaller cap workgroups walk the
-// row sets grid-stride and fetch the next row before computing on the current one.
-template <typename T, int LANES, int CH, bool WORDS>
+// Work unit = one "row set": kGroups*R consecutive query rows of one [Sq, Sk] slice, where
+// kGroups = kThreads/LANES lane groups each own R rows (rows base + r*kGroups + g) and CH
+// 16-byte pieces per row (piece c of lane t = c*LANES + t).  All R rows of a group are fetched
+// before any arithmetic: short rows would otherwise leave one 16-byte load per lane in
+// flight, too little to cover the memory latency at 32 waves per compute unit.  With the
+// default launch cap every row set has its own workgroup and the grid sweeps memory front to
+// back; under a smaller cap workgroups walk the row sets grid-stride.
+template <typename T, int LANES, int CH, int R, bool WORDS>
 __global__ __launch_bounds__(kThreads) void attn_fwd_kernel(
     const T* scores, const int32_t* __restrict__ key_len, int causal, T* probs,
     T* __restrict__ out, uint32_t* __restrict__ keep_bits, int slices, int A, int Sq, int Sk,
@@ -157,54 +159,42 @@ __global__ __launch_bounds__(kThreads) void attn_fwd_kernel(
   const int g = threadIdx.x / LANES;
   const int t = threadIdx.x % LANES;
   const int pieces = Sk / V;
-  const int sets_per_slice = (Sq + kGroups - 1) / kGroups;
+  const int sets_per_slice = (Sq + kGroups * R - 1) / (kGroups * R);
   const int64_t total_sets = static_cast<int64_t>(slices) * sets_per_slice;
   const int64_t total_pieces = static_cast<int64_t>(slices) * Sq * pieces;
 
-  // limit (number of leading columns in the softmax) of this lane group's row in row set rs;
-  // -1 if the group has no row there
-  auto locate = [&](int64_t rs, int64_t& row) -> int {
+  for (int64_t rs = blockIdx.x; rs < total_sets; rs += gridDim.x) {
     const int slice = static_cast<int>(rs / sets_per_slice);
-    const int i = static_cast<int>(rs % sets_per_slice) * kGroups + g;
-    row = static_cast<int64_t>(slice) * Sq + i;
-    if (i >= Sq) return -1;
+    const int i0 = static_cast<int>(rs % sets_per_slice) * (kGroups * R) + g;
     const int key_limit = key_len ? min(max(key_len[slice / A], 0), Sk) : Sk;
-    return row_limit(i, key_limit, causal, Sq, Sk);
-  };
-  auto fetch = [&](Raw<T> (&raw)[CH], int64_t row, int limit) {
+    // limit = number of leading columns of the row that take part in the softmax; -1: no row
+    int limit[R];
+    Raw<T> raw[R][CH];
 #pragma unroll
-    for (int c = 0; c < CH; ++c) {
-      const int col0 = (c * LANES + t) * V;
-      if (col0 < limit) raw[c].load(scores + row * Sk + col0);
+    for (int r = 0; r < R; ++r) {
+      const int i = i0 + r * kGroups;
+      limit[r] = (i < Sq) ? row_limit(i, key_limit, causal, Sq, Sk) : -1;
+      const T* sr = scores + (static_cast<int64_t>(slice) * Sq + i) * Sk;
+#pragma unroll
+      for (int c = 0; c < CH; ++c) {
+        const int col0 = (c * LANES + t) * V;
+        if (col0 < limit[r]) raw[r][c].load(sr + col0);
+      }
     }
-  };
-
-  int64_t rs = blockIdx.x;
-  if (rs >= total_sets) return;
-  int64_t row;
-  int limit = locate(rs, row);
-  Raw<T> cur[CH];
-  fetch(cur, row, limit);
-  for (; rs < total_sets; rs += gridDim.x) {
-    const int64_t rs_next = rs + gridDim.x;
-    int64_t row_next = 0;
-    int limit_next = -1;
-    Raw<T> nxt[CH];
-    if (rs_next < total_sets) {
-      limit_next = locate(rs_next, row_next);
-      fetch(nxt, row_next, limit_next);
-    }
-    if (limit >= 0) {  // uniform over the lane group
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      if (limit[r] < 0) continue;  // uniform over the lane group
+      const int64_t row = static_cast<int64_t>(slice) * Sq + i0 + r * kGroups;
       float v[CH][V];
       float mx = -INFINITY;
 #pragma unroll
       for (int c = 0; c < CH; ++c) {
         const int col0 = (c * LANES + t) * V;
-        if (col0 < limit) {
-          cur[c].unpack(v[c]);
-          if (col0 + V > limit) {  // the piece the limit falls into
+        if (col0 < limit[r]) {
+          raw[r][c].unpack(v[c]);
+          if (col0 + V > limit[r]) {  // the piece the limit falls into
 #pragma unroll
-            for (int k = 0; k < V; ++k) v[c][k] = (col0 + k < limit) ? v[c][k] : -INFINITY;
+            for (int k = 0; k < V; ++k) v[c][k] = (col0 + k < limit[r]) ? v[c][k] : -INFINITY;
           }
 #pragma unroll
           for (int k = 0; k < V; ++k) mx = fmaxf(mx, v[c][k]);
@@ -216,7 +206,7 @@ __global__ __launch_bounds__(kThreads) void attn_fwd_kernel(
 #pragma unroll
       for (int c = 0; c < CH; ++c) {
         const int col0 = (c * LANES + t) * V;
-        if (col0 < limit) {
+        if (col0 < limit[r]) {
 #pragma unroll
           for (int k = 0; k < V; ++k) {
             const float e = __builtin_amdgcn_exp2f(fmaf(v[c][k], kLog2e, -shift));
@@ -251,14 +241,10 @@ __global__ __launch_bounds__(kThreads) void attn_fwd_kernel(
                                   total_pieces);
       }
     }
-#pragma unroll
-    for (int c = 0; c < CH; ++c) cur[c] = nxt[c];
-    row = row_next;
-    limit = limit_next;
   }
 }
 
-template <typename T, int LANES, int CH, bool WORDS>
+template <typename T, int LANES, int CH, int R, bool WORDS>
 __global__ __launch_bounds__(kThreads) void attn_bwd_kernel(
     const T* dout, const T* __restrict__ probs, const uint32_t* __restrict__ keep_bits,
     T* dscores, T* __restrict__ out_re, int64_t rows, int Sk, float scale) {
@@ -267,44 +253,62 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_kernel(
   const int g = threadIdx.x / LANES;
   const int t = threadIdx.x % LANES;
   const int pieces = Sk / V;
-  for (int64_t row = static_cast<int64_t>(blockIdx.x) * kGroups + g; row < rows;
-       row += static_cast<int64_t>(gridDim.x) * kGroups) {
-    const int64_t piece0 = row * pieces;
-    float dp[CH][V], pr[CH][V];
-    uint32_t bits[CH];
-    float dot = 0.0f;
+  for (int64_t base = static_cast<int64_t>(blockIdx.x) * (kGroups * R); base < rows;
+       base += static_cast<int64_t>(gridDim.x) * (kGroups * R)) {
+    Raw<T> rdo[R][CH], rp[R][CH];
+    uint32_t bits[R][CH];
 #pragma unroll
-    for (int c = 0; c < CH; ++c) {
-      const int pc = c * LANES + t;
-      if (pc < pieces) {
-        load_piece<T>(dout + row * Sk + pc * V, dp[c]);
-        load_piece<T>(probs + row * Sk + pc * V, pr[c]);
-        bits[c] = load_keep_bits<T, WORDS>(keep_bits, piece0 + pc);
-      } else {
-        bits[c] = 0;
+    for (int r = 0; r < R; ++r) {
+      const int64_t row = base + r * kGroups + g;
 #pragma unroll
-        for (int k = 0; k < V; ++k) dp[c][k] = pr[c][k] = 0.0f;
-      }
-#pragma unroll
-      for (int k = 0; k < V; ++k) {
-        dp[c][k] = ((bits[c] >> k) & 1u) ? dp[c][k] * scale : 0.0f;
-        dot = fmaf(dp[c][k], pr[c][k], dot);
+      for (int c = 0; c < CH; ++c) {
+        const int pc = c * LANES + t;
+        bits[r][c] = 0;
+        if (row < rows && pc < pieces) {
+          rdo[r][c].load(dout + row * Sk + pc * V);
+          rp[r][c].load(probs + row * Sk + pc * V);
+          bits[r][c] = load_keep_bits<T, WORDS>(keep_bits, row * pieces + pc);
+        }
       }
     }
-    dot = group_sum<LANES>(dot);
 #pragma unroll
-    for (int c = 0; c < CH; ++c) {
-      const int pc = c * LANES + t;
-      if (pc < pieces) {
-        float ds[V];
+    for (int r = 0; r < R; ++r) {
+      const int64_t row = base + r * kGroups + g;
+      if (row >= rows) continue;  // uniform over the lane group
+      float dp[CH][V], pr[CH][V];
+      float dot = 0.0f;
 #pragma unroll
-        for (int k = 0; k < V; ++k) ds[k] = pr[c][k] * (dp[c][k] - dot);
-        store_piece<T>(dscores + row * Sk + pc * V, ds);
-        if (out_re) {
-          float o8[V];
+      for (int c = 0; c < CH; ++c) {
+        const int pc = c * LANES + t;
+        if (pc < pieces) {
+          rdo[r][c].unpack(dp[c]);
+          rp[r][c].unpack(pr[c]);
+        } else {
 #pragma unroll
-          for (int k = 0; k < V; ++k) o8[k] = ((bits[c] >> k) & 1u) ? pr[c][k] * scale : 0.0f;
-          store_piece<T>(out_re + row * Sk + pc * V, o8);
+          for (int k = 0; k < V; ++k) dp[c][k] = pr[c][k] = 0.0f;
+        }
+#pragma unroll
+        for (int k = 0; k < V; ++k) {
+          dp[c][k] = ((bits[r][c] >> k) & 1u) ? dp[c][k] * scale : 0.0f;
+          dot = fmaf(dp[c][k], pr[c][k], dot);
+        }
+      }
+      dot = group_sum<LANES>(dot);
+#pragma unroll
+      for (int c = 0; c < CH; ++c) {
+        const int pc = c * LANES + t;
+        if (pc < pieces) {
+          float ds[V];
+#pragma unroll
+          for (int k = 0; k < V; ++k) ds[k] = pr[c][k] * (dp[c][k] - dot);
+          store_piece<T>(dscores + row * Sk + pc * V, ds);
+          if (out_re) {
+            float o8[V];
+#pragma unroll
+            for (int k = 0; k < V; ++k)
+              o8[k] = ((bits[r][c] >> k) & 1u) ? pr[c][k] * scale : 0.0f;
+            store_piece<T>(out_re + row * Sk + pc * V, o8);
+          }
         }
       }
     }
@@ -412,8 +416,15 @@ Shape pick_shape(int pieces, int min_lanes) {
   return {0, 0};
 }
 
-int row_grid(int64_t rows, int lanes, int blocks_per_cu) {
-  const int groups = kThreads / lanes;
+// Rows a lane group fetches at once: up to `tuned`, never more than 4 pieces per lane in all.
+int attn_rows(int ch, int tuned) {
+  const int want = ch == 1 ? 4 : (ch == 2 ? 2 : 1);
+  const int cap = tuned >= 4 ? 4 : (tuned >= 2 ? 2 : 1);
+  return want < cap ? want : cap;
+}
+
+int row_grid(int64_t rows, int lanes, int blocks_per_cu, int rows_per_group = 1) {
+  const int groups = (kThreads / lanes) * rows_per_group;
   const int64_t want = (rows + groups - 1) / groups;
   const int64_t cap = static_cast<int64_t>(compute_units()) * blocks_per_cu;
   const int64_t b = want < cap ? want : cap;
@@ -422,6 +433,7 @@ int row_grid(int64_t rows, int lanes, int blocks_per_cu) {
 
 }  // namespace
 
+// LAUNCH(lanes, pieces per lane); the rows per lane group come from attn_rows().
 #define TEMPO_ATTN_DISPATCH(LAUNCH)                                                        \
   switch (sh.lanes * 100 + sh.ch) {                                                        \
     case 401: LAUNCH(4, 1); break;                                                         \
@@ -459,28 +471,38 @@ tempo_status launch_attn_fwd(const void* scores, const int32_t* key_len, int cau
   Shape sh = pick_shape(static_cast<int>(Sk / vec), 32 / vec);
   if (Sk % 8 == 0 && sh.ch != 0 && B * A <= INT32_MAX) {
     const int slices = static_cast<int>(B * A);
-    const int groups = kThreads / sh.lanes;
-    const int64_t total_sets = static_cast<int64_t>(slices) * ((Sq + groups - 1) / groups);
+    const int rr = attn_rows(sh.ch, tune_get(kTuneAttnFwdRows));
+    const int rows_per_set = (kThreads / sh.lanes) * rr;
+    const int64_t total_sets =
+        static_cast<int64_t>(slices) * ((Sq + rows_per_set - 1) / rows_per_set);
     const int64_t cap = static_cast<int64_t>(compute_units()) * bpc;
     const dim3 grid(static_cast<unsigned>(total_sets < cap ? total_sets : cap));
     const bool words = (Sk % 32 == 0);
-#define TEMPO_LAUNCH_T(T, L, C, W)                                                           \
-  hipLaunchKernelGGL((attn_fwd_kernel<T, L, C, W>), grid, dim3(kThreads), 0, st,             \
+#define TEMPO_LAUNCH_T(T, L, C, RR, W)                                                       \
+  hipLaunchKernelGGL((attn_fwd_kernel<T, L, C, RR, W>), grid, dim3(kThreads), 0, st,         \
                      static_cast<const T*>(scores), key_len, causal, static_cast<T*>(probs), \
                      static_cast<T*>(out), keep_bits, slices, static_cast<int>(A),           \
                      static_cast<int>(Sq), static_cast<int>(Sk), scale, rng)
+#define TEMPO_LAUNCH_W(T, L, C, RR)                                                          \
+  do {                                                                                       \
+    if (words) TEMPO_LAUNCH_T(T, L, C, RR, true);                                            \
+    else TEMPO_LAUNCH_T(T, L, C, RR, false);                                                 \
+  } while (0)
+#define TEMPO_LAUNCH_RR(T, L, C)                                                             \
+  do {                                                                                       \
+    if (C == 1 && rr == 4) TEMPO_LAUNCH_W(T, L, C, 4);                                       \
+    else if (C <= 2 && rr >= 2) TEMPO_LAUNCH_W(T, L, C, 2);                                  \
+    else TEMPO_LAUNCH_W(T, L, C, 1);                                                         \
+  } while (0)
 #define TEMPO_LAUNCH(L, C)                                                                   \
   do {                                                                                       \
-    if (dt == TEMPO_F32) {                                                                   \
-      if (words) TEMPO_LAUNCH_T(float, L, C, true);                                          \
-      else TEMPO_LAUNCH_T(float, L, C, false);                                               \
-    } else {                                                                                 \
-      if (words) TEMPO_LAUNCH_T(bf16_t, L, C, true);                                         \
-      else TEMPO_LAUNCH_T(bf16_t, L, C, false);                                              \
-    }                                                                                        \
+    if (dt == TEMPO_F32) TEMPO_LAUNCH_RR(float, L, C);                                       \
+    else TEMPO_LAUNCH_RR(bf16_t, L, C);                                                      \
   } while (0)
     TEMPO_ATTN_DISPATCH(TEMPO_LAUNCH)
 #undef TEMPO_LAUNCH
+#undef TEMPO_LAUNCH_RR
+#undef TEMPO_LAUNCH_W
 #undef TEMPO_LAUNCH_T
     return launch_status();
   }
@@ -514,25 +536,34 @@ tempo_status launch_attn_bwd(const void* dout, const void* probs, const uint32_t
   const int vec = dt == TEMPO_F32 ? 4 : 8;
   Shape sh = pick_shape(static_cast<int>(Sk / vec), 32 / vec);
   if (Sk % 8 == 0 && sh.ch != 0) {
-    const int grid = row_grid(rows, sh.lanes, bpc);
+    const int rr = attn_rows(sh.ch, tune_get(kTuneAttnBwdRows));
+    const int grid = row_grid(rows, sh.lanes, bpc, rr);
     const bool words = (Sk % 32 == 0);
-#define TEMPO_LAUNCH_T(T, L, C, W)                                                           \
-  hipLaunchKernelGGL((attn_bwd_kernel<T, L, C, W>), dim3(grid), dim3(kThreads), 0, st,       \
+#define TEMPO_LAUNCH_T(T, L, C, RR, W)                                                       \
+  hipLaunchKernelGGL((attn_bwd_kernel<T, L, C, RR, W>), dim3(grid), dim3(kThreads), 0, st,   \
                      static_cast<const T*>(dout), static_cast<const T*>(probs), keep_bits,   \
                      static_cast<T*>(dscores), static_cast<T*>(out_re), rows,                \
                      static_cast<int>(Sk), scale)
+#define TEMPO_LAUNCH_W(T, L, C, RR)                                                          \
+  do {                                                                                       \
+    if (words) TEMPO_LAUNCH_T(T, L, C, RR, true);                                            \
+    else TEMPO_LAUNCH_T(T, L, C, RR, false);                                                 \
+  } while (0)
+#define TEMPO_LAUNCH_RR(T, L, C)                                                             \
+  do {                                                                                       \
+    if (C == 1 && rr == 4) TEMPO_LAUNCH_W(T, L, C, 4);                                       \
+    else if (C <= 2 && rr >= 2) TEMPO_LAUNCH_W(T, L, C, 2);                                  \
+    else TEMPO_LAUNCH_W(T, L, C, 1);                                                         \
+  } while (0)
 #define TEMPO_LAUNCH(L, C)                                                                   \
   do {                                                                                       \
-    if (dt == TEMPO_F32) {                                                                   \
-      if (words) TEMPO_LAUNCH_T(float, L, C, true);                                          \
-      else TEMPO_LAUNCH_T(float, L, C, false);                                               \
-    } else {                                                                                 \
-      if (words) TEMPO_LAUNCH_T(bf16_t, L, C, true);                                         \
-      else TEMPO_LAUNCH_T(bf16_t, L, C, false);                                              \
-    }                                                                                        \
+    if (dt == TEMPO_F32) TEMPO_LAUNCH_RR(float, L, C);                                       \
+    else TEMPO_LAUNCH_RR(bf16_t, L, C);                                                      \
   } while (0)
     TEMPO_ATTN_DISPATCH(TEMPO_LAUNCH)
 #undef TEMPO_LAUNCH
+#undef TEMPO_LAUNCH_RR
+#undef TEMPO_LAUNCH_W
 #undef TEMPO_LAUNCH_T
     return launch_status();
   }

@@ -16,7 +16,9 @@ enum TuneKey {
   kTuneLnBwdRowsPerGroup = 3,   // rows each lane group walks (sets the grid and the workspace)
   kTuneAttnFwdBlocksPerCu = 4,  // cap on workgroups per compute unit
   kTuneAttnBwdBlocksPerCu = 5,
-  kTuneCount = 6
+  kTuneAttnFwdRows = 6,         // rows a lane group fetches at once (1, 2 or 4)
+  kTuneAttnBwdRows = 7,
+  kTuneCount = 8
 };
 int tune_get(TuneKey k);
 int compute_units();
