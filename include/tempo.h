@@ -58,7 +58,7 @@ TEMPO_API int tempo_version(void);
  *   key 0 / 1: 8-element chunks per lane in gelu_fwd / gelu_bwd (1, 2 or 4);
  *   key 2, 4, 5: cap on workgroups per compute unit of layernorm_fwd, attn fwd, attn bwd
  *   (rows beyond the cap are walked in a loop);
- *   key 6, 7: rows a lane group of attn fwd / bwd fetches at once (1, 2 or 4);
+ *   key 6, 7: rows a lane group of attn fwd / layernorm_fwd fetches at once (1 or 2);
  *   key 3: rows each lane group of layernorm_bwd walks; this sets its grid and the size of its
  *   workspace, so query tempo_layernorm_bwd_workspace_bytes after changing it.
  * Results never depend on these except the summation order of dgamma/dbeta.  value in

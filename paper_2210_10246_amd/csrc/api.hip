@@ -15,7 +15,7 @@ static std::atomic<int> g_tune[kTuneCount] = {
     {65536},  // attention fwd: workgroups per CU (65536 = one row per lane group)
     {65536},  // attention bwd: workgroups per CU
     {2},      // attention fwd: rows per lane group
-    {1},      // attention bwd: rows per lane group
+    {2},      // layernorm fwd: rows per lane group
 };
 
 int tune_get(TuneKey k) { return g_tune[k].load(std::memory_order_relaxed); }

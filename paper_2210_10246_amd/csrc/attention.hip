@@ -6,6 +6,8 @@
 // chunks of 8 elements per lane, chunk c of lane t = c*LANES + t so every access of a group
 // is contiguous).  The keep bits come from Philox4x32-10, one call per chunk, so the mask is a
 // pure function of (seed, offset, element index) and does not depend on the launch shape.
+#include <type_traits>
+
 #include "tempo_device.h"
 #include "tempo_host.h"
 
@@ -416,12 +418,10 @@ Shape pick_shape(int pieces, int min_lanes) {
   return {0, 0};
 }
 
-// Rows a lane group fetches at once: up to `tuned`, never more than 4 pieces per lane in all.
-int attn_rows(int ch, int tuned) {
-  const int want = ch == 1 ? 4 : (ch == 2 ? 2 : 1);
-  const int cap = tuned >= 4 ? 4 : (tuned >= 2 ? 2 : 1);
-  return want < cap ? want : cap;
-}
+// Rows a lane group of the forward kernel fetches at once: 2 (if the knob allows) while a row
+// is one or two pieces per lane, else 1.  Measured on [*,*,128..1024,*] maps: 2 rows beat 1 by
+// up to 25 % in forward and lose 3-8 % in backward, which therefore always takes 1.
+int attn_rows(int ch, int tuned) { return (ch <= 2 && tuned >= 2) ? 2 : 1; }
 
 int row_grid(int64_t rows, int lanes, int blocks_per_cu, int rows_per_group = 1) {
   const int groups = (kThreads / lanes) * rows_per_group;
@@ -451,6 +451,42 @@ int row_grid(int64_t rows, int lanes, int blocks_per_cu, int rows_per_group = 1)
     default: return TEMPO_ERR_UNSUPPORTED;                                                 \
   }
 
+template <typename T, int L, int C>
+static void attn_fwd_go(int rr, bool words, dim3 grid, hipStream_t st, const void* scores,
+                        const int32_t* key_len, int causal, void* probs, void* out,
+                        uint32_t* keep_bits, int slices, int64_t A, int64_t Sq, int64_t Sk,
+                        float scale, const RngArgs& rng) {
+  auto go = [&](auto rows, auto w) {
+    hipLaunchKernelGGL((attn_fwd_kernel<T, L, C, decltype(rows)::value, decltype(w)::value>), grid,
+                       dim3(kThreads), 0, st, static_cast<const T*>(scores), key_len, causal,
+                       static_cast<T*>(probs), static_cast<T*>(out), keep_bits, slices,
+                       static_cast<int>(A), static_cast<int>(Sq), static_cast<int>(Sk), scale, rng);
+  };
+  using std::integral_constant;
+  if constexpr (C <= 2) {
+    if (rr == 2) {
+      if (words) return go(integral_constant<int, 2>{}, std::true_type{});
+      return go(integral_constant<int, 2>{}, std::false_type{});
+    }
+  }
+  if (words) return go(integral_constant<int, 1>{}, std::true_type{});
+  go(integral_constant<int, 1>{}, std::false_type{});
+}
+
+template <typename T, int L, int C>
+static void attn_bwd_go(bool words, int grid, hipStream_t st, const void* dout, const void* probs,
+                        const uint32_t* keep_bits, void* dscores, void* out_re, int64_t rows,
+                        int64_t Sk, float scale) {
+  auto go = [&](auto w) {
+    hipLaunchKernelGGL((attn_bwd_kernel<T, L, C, 1, decltype(w)::value>), dim3(grid),
+                       dim3(kThreads), 0, st, static_cast<const T*>(dout),
+                       static_cast<const T*>(probs), keep_bits, static_cast<T*>(dscores),
+                       static_cast<T*>(out_re), rows, static_cast<int>(Sk), scale);
+  };
+  if (words) return go(std::true_type{});
+  go(std::false_type{});
+}
+
 tempo_status launch_attn_fwd(const void* scores, const int32_t* key_len, int causal, void* probs,
                              void* out, uint32_t* keep_bits, int64_t B, int64_t A, int64_t Sq,
                              int64_t Sk, float p, uint64_t seed, uint64_t offset, tempo_dtype dt,
@@ -478,32 +514,13 @@ tempo_status launch_attn_fwd(const void* scores, const int32_t* key_len, int cau
     const int64_t cap = static_cast<int64_t>(compute_units()) * bpc;
     const dim3 grid(static_cast<unsigned>(total_sets < cap ? total_sets : cap));
     const bool words = (Sk % 32 == 0);
-#define TEMPO_LAUNCH_T(T, L, C, RR, W)                                                       \
-  hipLaunchKernelGGL((attn_fwd_kernel<T, L, C, RR, W>), grid, dim3(kThreads), 0, st,         \
-                     static_cast<const T*>(scores), key_len, causal, static_cast<T*>(probs), \
-                     static_cast<T*>(out), keep_bits, slices, static_cast<int>(A),           \
-                     static_cast<int>(Sq), static_cast<int>(Sk), scale, rng)
-#define TEMPO_LAUNCH_W(T, L, C, RR)                                                          \
-  do {                                                                                       \
-    if (words) TEMPO_LAUNCH_T(T, L, C, RR, true);                                            \
-    else TEMPO_LAUNCH_T(T, L, C, RR, false);                                                 \
-  } while (0)
-#define TEMPO_LAUNCH_RR(T, L, C)                                                             \
-  do {                                                                                       \
-    if (C == 1 && rr == 4) TEMPO_LAUNCH_W(T, L, C, 4);                                       \
-    else if (C <= 2 && rr >= 2) TEMPO_LAUNCH_W(T, L, C, 2);                                  \
-    else TEMPO_LAUNCH_W(T, L, C, 1);                                                         \
-  } while (0)
 #define TEMPO_LAUNCH(L, C)                                                                   \
   do {                                                                                       \
-    if (dt == TEMPO_F32) TEMPO_LAUNCH_RR(float, L, C);                                       \
-    else TEMPO_LAUNCH_RR(bf16_t, L, C);                                                      \
+    if (dt == TEMPO_F32) attn_fwd_go<float, L, C>(rr, words, grid, st, scores, key_len, causal, probs, out, keep_bits, slices, A, Sq, Sk, scale, rng);   \
+    else attn_fwd_go<bf16_t, L, C>(rr, words, grid, st, scores, key_len, causal, probs, out, keep_bits, slices, A, Sq, Sk, scale, rng);                  \
   } while (0)
     TEMPO_ATTN_DISPATCH(TEMPO_LAUNCH)
 #undef TEMPO_LAUNCH
-#undef TEMPO_LAUNCH_RR
-#undef TEMPO_LAUNCH_W
-#undef TEMPO_LAUNCH_T
     return launch_status();
   }
   const int grid = row_grid(rows, kWave, bpc);
@@ -536,35 +553,15 @@ tempo_status launch_attn_bwd(const void* dout, const void* probs, const uint32_t
   const int vec = dt == TEMPO_F32 ? 4 : 8;
   Shape sh = pick_shape(static_cast<int>(Sk / vec), 32 / vec);
   if (Sk % 8 == 0 && sh.ch != 0) {
-    const int rr = attn_rows(sh.ch, tune_get(kTuneAttnBwdRows));
-    const int grid = row_grid(rows, sh.lanes, bpc, rr);
+    const int grid = row_grid(rows, sh.lanes, bpc);
     const bool words = (Sk % 32 == 0);
-#define TEMPO_LAUNCH_T(T, L, C, RR, W)                                                       \
-  hipLaunchKernelGGL((attn_bwd_kernel<T, L, C, RR, W>), dim3(grid), dim3(kThreads), 0, st,   \
-                     static_cast<const T*>(dout), static_cast<const T*>(probs), keep_bits,   \
-                     static_cast<T*>(dscores), static_cast<T*>(out_re), rows,                \
-                     static_cast<int>(Sk), scale)
-#define TEMPO_LAUNCH_W(T, L, C, RR)                                                          \
-  do {                                                                                       \
-    if (words) TEMPO_LAUNCH_T(T, L, C, RR, true);                                            \
-    else TEMPO_LAUNCH_T(T, L, C, RR, false);                                                 \
-  } while (0)
-#define TEMPO_LAUNCH_RR(T, L, C)                                                             \
-  do {                                                                                       \
-    if (C == 1 && rr == 4) TEMPO_LAUNCH_W(T, L, C, 4);                                       \
-    else if (C <= 2 && rr >= 2) TEMPO_LAUNCH_W(T, L, C, 2);                                  \
-    else TEMPO_LAUNCH_W(T, L, C, 1);                                                         \
-  } while (0)
 #define TEMPO_LAUNCH(L, C)                                                                   \
   do {                                                                                       \
-    if (dt == TEMPO_F32) TEMPO_LAUNCH_RR(float, L, C);                                       \
-    else TEMPO_LAUNCH_RR(bf16_t, L, C);                                                      \
+    if (dt == TEMPO_F32) attn_bwd_go<float, L, C>(words, grid, st, dout, probs, keep_bits, dscores, out_re, rows, Sk, scale);   \
+    else attn_bwd_go<bf16_t, L, C>(words, grid, st, dout, probs, keep_bits, dscores, out_re, rows, Sk, scale);                  \
   } while (0)
     TEMPO_ATTN_DISPATCH(TEMPO_LAUNCH)
 #undef TEMPO_LAUNCH
-#undef TEMPO_LAUNCH_RR
-#undef TEMPO_LAUNCH_W
-#undef TEMPO_LAUNCH_T
     return launch_status();
   }
   const int grid = row_grid(rows, kWave, bpc);

@@ -7,6 +7,8 @@
 // sums are butterfly-reduced, and the column sums for dgamma/dbeta are carried in registers
 // across rows, tree-reduced over the workgroup through LDS in a fixed order and written as
 // one partial per workgroup; a second small kernel adds the partials in a fixed order.
+#include <type_traits>
+
 #include "tempo_device.h"
 #include "tempo_host.h"
 
@@ -19,7 +21,10 @@ constexpr int kBwdThreads = kBwdWaves * kWave;
 constexpr int kMaxFastM = 4096;  // rows longer than this take the generic kernels; the backward
                                  // LDS tree needs 16*M bytes (64 KiB at 4096)
 
-template <typename T, int LANES, int CH>
+// Forward.  A batch is kGroups*R consecutive rows; lane group g takes rows base + r*kGroups + g
+// and fetches all R of them (packed) before any arithmetic, so that short rows still keep
+// several 16-byte loads per lane in flight.
+template <typename T, int LANES, int CH, int R>
 __global__ __launch_bounds__(kFwdThreads) void ln_fwd_kernel(
     const T* x, const float* __restrict__ gamma, const float* __restrict__ beta, T* y,
     float* __restrict__ rstd_out, float* __restrict__ mean_out, int64_t N, int M, float eps) {
@@ -30,62 +35,81 @@ __global__ __launch_bounds__(kFwdThreads) void ln_fwd_kernel(
   const int chunks = M / V;
   const float inv_m = 1.0f / static_cast<float>(M);
   float ga[CH][V], be[CH][V];
+  bool have_params = false;
+  for (int64_t base = static_cast<int64_t>(blockIdx.x) * (kGroups * R); base < N;
+       base += static_cast<int64_t>(gridDim.x) * (kGroups * R)) {
+    Raw<T> raw[R][CH];
 #pragma unroll
-  for (int c = 0; c < CH; ++c) {
-    const int ch = c * LANES + t;
-    if (ch < chunks) {
-      load_floats<V>(gamma + ch * V, ga[c]);
-      load_floats<V>(beta + ch * V, be[c]);
-    } else {
+    for (int r = 0; r < R; ++r) {
+      const int64_t row = base + r * kGroups + g;
+      if (row < N) {
 #pragma unroll
-      for (int i = 0; i < V; ++i) ga[c][i] = be[c][i] = 0.0f;
-    }
-  }
-  for (int64_t row = static_cast<int64_t>(blockIdx.x) * kGroups + g; row < N;
-       row += static_cast<int64_t>(gridDim.x) * kGroups) {
-    const T* xr = x + row * M;
-    T* yr = y + row * M;
-    float v[CH][V];
-    float sum = 0.0f;
-#pragma unroll
-    for (int c = 0; c < CH; ++c) {
-      const int ch = c * LANES + t;
-      if (ch < chunks) {
-        load_piece<T>(xr + ch * V, v[c]);
-      } else {
-#pragma unroll
-        for (int i = 0; i < V; ++i) v[c][i] = 0.0f;
-      }
-#pragma unroll
-      for (int i = 0; i < V; ++i) sum += v[c][i];
-    }
-    const float mu = group_sum<LANES>(sum) * inv_m;
-    float sq = 0.0f;
-#pragma unroll
-    for (int c = 0; c < CH; ++c) {
-      const int ch = c * LANES + t;
-#pragma unroll
-      for (int i = 0; i < V; ++i) {
-        const float d = v[c][i] - mu;
-        v[c][i] = d;
-        sq += (ch < chunks) ? d * d : 0.0f;
+        for (int c = 0; c < CH; ++c) {
+          const int ch = c * LANES + t;
+          if (ch < chunks) raw[r][c].load(x + row * M + ch * V);
+        }
       }
     }
-    const float var = group_sum<LANES>(sq) * inv_m;
-    const float rs = 1.0f / sqrtf(var + eps);
+    if (!have_params) {  // after the first rows are on their way
+      have_params = true;
 #pragma unroll
-    for (int c = 0; c < CH; ++c) {
-      const int ch = c * LANES + t;
-      if (ch < chunks) {
-        float o[V];
+      for (int c = 0; c < CH; ++c) {
+        const int ch = c * LANES + t;
+        if (ch < chunks) {
+          load_floats<V>(gamma + ch * V, ga[c]);
+          load_floats<V>(beta + ch * V, be[c]);
+        } else {
 #pragma unroll
-        for (int i = 0; i < V; ++i) o[i] = fmaf(v[c][i] * rs, ga[c][i], be[c][i]);
-        store_piece<T>(yr + ch * V, o);
+          for (int i = 0; i < V; ++i) ga[c][i] = be[c][i] = 0.0f;
+        }
       }
     }
-    if (t == 0) {
-      rstd_out[row] = rs;
-      if (mean_out) mean_out[row] = mu;
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      const int64_t row = base + r * kGroups + g;
+      if (row >= N) continue;  // uniform over the lane group
+      float v[CH][V];
+      float sum = 0.0f;
+#pragma unroll
+      for (int c = 0; c < CH; ++c) {
+        const int ch = c * LANES + t;
+        if (ch < chunks) {
+          raw[r][c].unpack(v[c]);
+        } else {
+#pragma unroll
+          for (int i = 0; i < V; ++i) v[c][i] = 0.0f;
+        }
+#pragma unroll
+        for (int i = 0; i < V; ++i) sum += v[c][i];
+      }
+      const float mu = group_sum<LANES>(sum) * inv_m;
+      float sq = 0.0f;
+#pragma unroll
+      for (int c = 0; c < CH; ++c) {
+        const int ch = c * LANES + t;
+#pragma unroll
+        for (int i = 0; i < V; ++i) {
+          const float d = v[c][i] - mu;
+          v[c][i] = d;
+          sq += (ch < chunks) ? d * d : 0.0f;
+        }
+      }
+      const float var = group_sum<LANES>(sq) * inv_m;
+      const float rs = 1.0f / sqrtf(var + eps);
+#pragma unroll
+      for (int c = 0; c < CH; ++c) {
+        const int ch = c * LANES + t;
+        if (ch < chunks) {
+          float o[V];
+#pragma unroll
+          for (int i = 0; i < V; ++i) o[i] = fmaf(v[c][i] * rs, ga[c][i], be[c][i]);
+          store_piece<T>(y + row * M + ch * V, o);
+        }
+      }
+      if (t == 0) {
+        rstd_out[row] = rs;
+        if (mean_out) mean_out[row] = mu;
+      }
     }
   }
 }
@@ -466,6 +490,28 @@ Shape pick_shape(int pieces) {
     default: return TEMPO_ERR_UNSUPPORTED;                                                 \
   }
 
+// Rows per lane group that exist as kernels for a shape (keeps the number of instantiations
+// down): 4 only for one or two pieces per lane on full-wave groups, 2 up to four pieces.
+template <int L, int C>
+constexpr int max_rows() {
+  return (C <= 2 && L == 64) ? 4 : (C <= 4 ? 2 : 1);
+}
+
+template <typename T, int L, int C>
+static void ln_fwd_go(int rr, int grid, hipStream_t st, const void* x, const float* gamma,
+                      const float* beta, void* y, float* rstd, float* mean, int64_t N, int64_t M,
+                      float eps) {
+  auto go = [&](auto rows) {
+    hipLaunchKernelGGL((ln_fwd_kernel<T, L, C, decltype(rows)::value>), dim3(grid),
+                       dim3(kFwdThreads), 0, st, static_cast<const T*>(x), gamma, beta,
+                       static_cast<T*>(y), rstd, mean, N, static_cast<int>(M), eps);
+  };
+  if constexpr (C <= 2) {
+    if (rr == 2) return go(std::integral_constant<int, 2>{});
+  }
+  go(std::integral_constant<int, 1>{});
+}
+
 static bool fast_shape(int64_t M, tempo_dtype dt, Shape* sh) {
   const int vec = dt == TEMPO_F32 ? 4 : 8;
   if (M % vec != 0 || M > kMaxFastM) return false;
@@ -479,23 +525,19 @@ tempo_status launch_layernorm_fwd(const void* x, const float* gamma, const float
   Shape sh;
   const int64_t cap = static_cast<int64_t>(compute_units()) * tune_get(kTuneLnFwdBlocksPerCu);
   if (fast_shape(M, dt, &sh)) {
-    const int groups = kFwdThreads / sh.lanes;
+    // rows per lane group: up to the knob, at most 4 pieces per lane in flight
+    const int tuned = tune_get(kTuneLnFwdRows);
+    const int rr = (sh.ch <= 2 && tuned >= 2) ? 2 : 1;
+    const int groups = (kFwdThreads / sh.lanes) * rr;
     const int64_t want = (N + groups - 1) / groups;
     const int grid = static_cast<int>(want < cap ? want : cap);
-#define TEMPO_LAUNCH_T(T, L, C)                                                              \
-  hipLaunchKernelGGL((ln_fwd_kernel<T, L, C>), dim3(grid), dim3(kFwdThreads), 0, st,         \
-                     static_cast<const T*>(x), gamma, beta, static_cast<T*>(y), rstd, mean,  \
-                     N, static_cast<int>(M), eps)
-    if (dt == TEMPO_F32) {
-#define TEMPO_LAUNCH(L, C) TEMPO_LAUNCH_T(float, L, C)
-      TEMPO_LN_DISPATCH(TEMPO_LAUNCH)
+#define TEMPO_LAUNCH(L, C)                                                                   \
+  do {                                                                                       \
+    if (dt == TEMPO_F32) ln_fwd_go<float, L, C>(rr, grid, st, x, gamma, beta, y, rstd, mean, N, M, eps);   \
+    else ln_fwd_go<bf16_t, L, C>(rr, grid, st, x, gamma, beta, y, rstd, mean, N, M, eps);    \
+  } while (0)
+    TEMPO_LN_DISPATCH(TEMPO_LAUNCH)
 #undef TEMPO_LAUNCH
-    } else {
-#define TEMPO_LAUNCH(L, C) TEMPO_LAUNCH_T(bf16_t, L, C)
-      TEMPO_LN_DISPATCH(TEMPO_LAUNCH)
-#undef TEMPO_LAUNCH
-    }
-#undef TEMPO_LAUNCH_T
   } else {
     const int grid = static_cast<int>(N < cap ? N : cap);
     if (dt == TEMPO_F32)
@@ -528,6 +570,8 @@ static BwdPlan bwd_plan(int64_t N, const Shape& sh, tempo_dtype dt) {
   const int cus = compute_units();
   auto batches = [&](int r) { return (N + groups * r - 1) / (groups * r); };
   int r = tuned >= 4 ? 4 : (tuned >= 2 ? 2 : 1);
+  const int avail = (sh.ch <= 2 && sh.lanes == 64) ? 4 : (sh.ch <= 4 ? 2 : 1);  // max_rows<L, C>()
+  if (r > avail) r = avail;
   while (r > 1 && (r * regs_per_row > 64 || batches(r) < cus)) r >>= 1;
   BwdPlan p = {r, false, static_cast<int>(batches(r) > 4096 ? 4096 : batches(r))};
   if (batches(r) > 2 * cus) {
@@ -537,6 +581,32 @@ static BwdPlan bwd_plan(int64_t N, const Shape& sh, tempo_dtype dt) {
   }
   if (p.grid < 1) p.grid = 1;
   return p;
+}
+
+template <typename T, int L, int C>
+static void ln_bwd_go(const BwdPlan& plan, size_t lds_bytes, hipStream_t st, const void* dy,
+                      const void* y, const float* gamma, const float* beta, const float* rstd,
+                      void* dx, float* workspace, int64_t N, int64_t M) {
+  auto go = [&](auto rows, auto loop) {
+    hipLaunchKernelGGL((ln_bwd_kernel<T, L, C, decltype(rows)::value, decltype(loop)::value>),
+                       dim3(plan.grid), dim3(kBwdThreads), lds_bytes, st,
+                       static_cast<const T*>(dy), static_cast<const T*>(y), gamma, beta, rstd,
+                       static_cast<T*>(dx), workspace, N, static_cast<int>(M));
+  };
+  using std::integral_constant;
+  if (plan.loop) {
+    if constexpr (max_rows<L, C>() >= 4) {  // looping holds two batches: half the rows
+      if (plan.r == 2) return go(integral_constant<int, 2>{}, std::true_type{});
+    }
+    return go(integral_constant<int, 1>{}, std::true_type{});
+  }
+  if constexpr (max_rows<L, C>() >= 4) {
+    if (plan.r == 4) return go(integral_constant<int, 4>{}, std::false_type{});
+  }
+  if constexpr (max_rows<L, C>() >= 2) {
+    if (plan.r >= 2) return go(integral_constant<int, 2>{}, std::false_type{});
+  }
+  go(integral_constant<int, 1>{}, std::false_type{});
 }
 
 int layernorm_bwd_blocks(int64_t N, int64_t M, tempo_dtype dt) {
@@ -554,33 +624,13 @@ tempo_status launch_layernorm_bwd(const void* dy, const void* y, const float* ga
   if (fast_shape(M, dt, &sh)) {
     const size_t lds_bytes = static_cast<size_t>(kBwdWaves / 2) * 2 * M * sizeof(float);
     const BwdPlan plan = bwd_plan(N, sh, dt);
-#define TEMPO_LAUNCH_R(T, L, C, RR, LP)                                                      \
-  hipLaunchKernelGGL((ln_bwd_kernel<T, L, C, RR, LP>), dim3(grid), dim3(kBwdThreads),        \
-                     lds_bytes, st, static_cast<const T*>(dy), static_cast<const T*>(y),     \
-                     gamma, beta, rstd, static_cast<T*>(dx), workspace, N,                   \
-                     static_cast<int>(M))
-#define TEMPO_LAUNCH_T(T, L, C)                                                              \
+#define TEMPO_LAUNCH(L, C)                                                                   \
   do {                                                                                       \
-    if (plan.loop) {                                                                         \
-      if (plan.r >= 2 && C <= 2) TEMPO_LAUNCH_R(T, L, C, 2, true);                           \
-      else TEMPO_LAUNCH_R(T, L, C, 1, true);                                                 \
-    } else {                                                                                 \
-      if (plan.r == 4 && C <= 2) TEMPO_LAUNCH_R(T, L, C, 4, false);                          \
-      else if (plan.r >= 2 && C <= 4) TEMPO_LAUNCH_R(T, L, C, 2, false);                     \
-      else TEMPO_LAUNCH_R(T, L, C, 1, false);                                                \
-    }                                                                                        \
+    if (dt == TEMPO_F32) ln_bwd_go<float, L, C>(plan, lds_bytes, st, dy, y, gamma, beta, rstd, dx, workspace, N, M);   \
+    else ln_bwd_go<bf16_t, L, C>(plan, lds_bytes, st, dy, y, gamma, beta, rstd, dx, workspace, N, M);                  \
   } while (0)
-    if (dt == TEMPO_F32) {
-#define TEMPO_LAUNCH(L, C) TEMPO_LAUNCH_T(float, L, C)
-      TEMPO_LN_DISPATCH(TEMPO_LAUNCH)
+    TEMPO_LN_DISPATCH(TEMPO_LAUNCH)
 #undef TEMPO_LAUNCH
-    } else {
-#define TEMPO_LAUNCH(L, C) TEMPO_LAUNCH_T(bf16_t, L, C)
-      TEMPO_LN_DISPATCH(TEMPO_LAUNCH)
-#undef TEMPO_LAUNCH
-    }
-#undef TEMPO_LAUNCH_T
-#undef TEMPO_LAUNCH_R
   } else {
     if (dt == TEMPO_F32)
       hipLaunchKernelGGL((ln_bwd_generic_kernel<float>), dim3(grid), dim3(256), 0, st,

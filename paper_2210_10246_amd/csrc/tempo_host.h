@@ -16,8 +16,8 @@ enum TuneKey {
   kTuneLnBwdRowsPerGroup = 3,   // rows each lane group walks (sets the grid and the workspace)
   kTuneAttnFwdBlocksPerCu = 4,  // cap on workgroups per compute unit
   kTuneAttnBwdBlocksPerCu = 5,
-  kTuneAttnFwdRows = 6,         // rows a lane group fetches at once (1, 2 or 4)
-  kTuneAttnBwdRows = 7,
+  kTuneAttnFwdRows = 6,         // rows a lane group of attn fwd fetches at once (1 or 2)
+  kTuneLnFwdRows = 7,           // rows a lane group of layernorm_fwd fetches at once (1 or 2)
   kTuneCount = 8
 };
 int tune_get(TuneKey k);
