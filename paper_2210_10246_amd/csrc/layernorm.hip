@@ -7,6 +7,7 @@
 // sums are butterfly-reduced, and the column sums for dgamma/dbeta are carried in registers
 // across rows, tree-reduced over the workgroup through LDS in a fixed order and written as
 // one partial per workgroup; a second small kernel adds the partials in a fixed order.
+#include <atomic>
 #include <type_traits>
 
 #include "tempo_device.h"
@@ -583,30 +584,59 @@ static BwdPlan bwd_plan(int64_t N, const Shape& sh, tempo_dtype dt) {
   return p;
 }
 
+// Launches the register-resident backward kernel; returns the number of workgroups used (the
+// number of partial slots written).  A looping launch is trimmed to the workgroups that are
+// resident at once, so that no second round of workgroups repeats the reduction epilogue.
 template <typename T, int L, int C>
-static void ln_bwd_go(const BwdPlan& plan, size_t lds_bytes, hipStream_t st, const void* dy,
-                      const void* y, const float* gamma, const float* beta, const float* rstd,
-                      void* dx, float* workspace, int64_t N, int64_t M) {
+static int ln_bwd_go(const BwdPlan& plan, size_t lds_bytes, hipStream_t st, const void* dy,
+                     const void* y, const float* gamma, const float* beta, const float* rstd,
+                     void* dx, float* workspace, int64_t N, int64_t M) {
+  int grid = plan.grid;
   auto go = [&](auto rows, auto loop) {
-    hipLaunchKernelGGL((ln_bwd_kernel<T, L, C, decltype(rows)::value, decltype(loop)::value>),
-                       dim3(plan.grid), dim3(kBwdThreads), lds_bytes, st,
+    auto kernel = ln_bwd_kernel<T, L, C, decltype(rows)::value, decltype(loop)::value>;
+    if (decltype(loop)::value) {
+      static std::atomic<int> resident{0};  // workgroups per compute unit, per instantiation
+      int per_cu = resident.load(std::memory_order_relaxed);
+      if (per_cu == 0) {
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, kBwdThreads,
+                                                         lds_bytes) != hipSuccess || per_cu < 1) {
+          (void)hipGetLastError();
+          per_cu = 1;
+        }
+        resident.store(per_cu, std::memory_order_relaxed);
+      }
+      const int fit = per_cu * compute_units();
+      if (grid > fit) grid = fit;
+    }
+    hipLaunchKernelGGL(kernel, dim3(grid), dim3(kBwdThreads), lds_bytes, st,
                        static_cast<const T*>(dy), static_cast<const T*>(y), gamma, beta, rstd,
                        static_cast<T*>(dx), workspace, N, static_cast<int>(M));
   };
   using std::integral_constant;
   if (plan.loop) {
     if constexpr (max_rows<L, C>() >= 4) {  // looping holds two batches: half the rows
-      if (plan.r == 2) return go(integral_constant<int, 2>{}, std::true_type{});
+      if (plan.r == 2) {
+        go(integral_constant<int, 2>{}, std::true_type{});
+        return grid;
+      }
     }
-    return go(integral_constant<int, 1>{}, std::true_type{});
+    go(integral_constant<int, 1>{}, std::true_type{});
+    return grid;
   }
   if constexpr (max_rows<L, C>() >= 4) {
-    if (plan.r == 4) return go(integral_constant<int, 4>{}, std::false_type{});
+    if (plan.r == 4) {
+      go(integral_constant<int, 4>{}, std::false_type{});
+      return grid;
+    }
   }
   if constexpr (max_rows<L, C>() >= 2) {
-    if (plan.r >= 2) return go(integral_constant<int, 2>{}, std::false_type{});
+    if (plan.r >= 2) {
+      go(integral_constant<int, 2>{}, std::false_type{});
+      return grid;
+    }
   }
   go(integral_constant<int, 1>{}, std::false_type{});
+  return grid;
 }
 
 int layernorm_bwd_blocks(int64_t N, int64_t M, tempo_dtype dt) {
@@ -620,14 +650,14 @@ tempo_status launch_layernorm_bwd(const void* dy, const void* y, const float* ga
                                   float* dbeta, float* workspace, int64_t N, int64_t M,
                                   tempo_dtype dt, hipStream_t st) {
   Shape sh;
-  const int grid = layernorm_bwd_blocks(N, M, dt);
+  int grid = layernorm_bwd_blocks(N, M, dt);  // upper bound: the workspace has this many slots
   if (fast_shape(M, dt, &sh)) {
     const size_t lds_bytes = static_cast<size_t>(kBwdWaves / 2) * 2 * M * sizeof(float);
     const BwdPlan plan = bwd_plan(N, sh, dt);
 #define TEMPO_LAUNCH(L, C)                                                                   \
   do {                                                                                       \
-    if (dt == TEMPO_F32) ln_bwd_go<float, L, C>(plan, lds_bytes, st, dy, y, gamma, beta, rstd, dx, workspace, N, M);   \
-    else ln_bwd_go<bf16_t, L, C>(plan, lds_bytes, st, dy, y, gamma, beta, rstd, dx, workspace, N, M);                  \
+    if (dt == TEMPO_F32) grid = ln_bwd_go<float, L, C>(plan, lds_bytes, st, dy, y, gamma, beta, rstd, dx, workspace, N, M);   \
+    else grid = ln_bwd_go<bf16_t, L, C>(plan, lds_bytes, st, dy, y, gamma, beta, rstd, dx, workspace, N, M);                  \
   } while (0)
     TEMPO_LN_DISPATCH(TEMPO_LAUNCH)
 #undef TEMPO_LAUNCH
