@@ -33,6 +33,8 @@ def parse():
     ap.add_argument("--config", type=int, default=1, help="workload configuration index (0-4)")
     ap.add_argument("--batch", type=int, default=None, help="batch override (config 4 sweep)")
     ap.add_argument("--dtype", choices=["f32", "bf16"], default=None)
+    ap.add_argument("--seq", type=int, default=None, help="sequence length override (shape sweeps)")
+    ap.add_argument("--hidden", type=int, default=None, help="hidden size override; heads = hidden/64")
     ap.add_argument("--kernel-iters", type=int, default=60, help="launches per kernel timing loop")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true")
@@ -55,6 +57,8 @@ def algorithmic_bytes(cfg):
         "layernorm_bwd": N * M * 3 * e + 4 * N + 16 * M,
         "attn_fwd": n_a * 3 * e + n_a / 8,
         "attn_bwd": n_a * 4 * e + n_a / 8,
+        # variant outside the step: backward that draws the keep bits again, no mask read
+        "attn_bwd_regen": n_a * 4 * e,
     }
 
 
@@ -95,6 +99,13 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs the MI355X"
     dev = torch.device("cuda:0")
     cfg = W.config(args.config, batch=args.batch, dtype=args.dtype)
+    if args.seq is not None or args.hidden is not None:
+        from dataclasses import replace
+        hidden = args.hidden or cfg.hidden
+        seq = args.seq or cfg.seq
+        lo, hi = (seq // 2, seq) if cfg.mask == "padding" else (0, 0)
+        cfg = replace(cfg, seq=seq, hidden=hidden, heads=hidden // 64, len_lo=lo, len_hi=hi,
+                      name=f"{cfg.name}-s{seq}-h{hidden}")
     dt = cfg.dtype
     tdt = W.torch_dtype(dt)
     e = cfg.elem_bytes
@@ -143,11 +154,14 @@ def main():
     def k_attn_fwd(s): B.tempo_attn_softmax_dropout_fwd(s["s"], key_len, causal, s["P"], s["out"], s["k"], p, seed, 0)
     def k_attn_bwd(s): B.tempo_attn_softmax_dropout_bwd(s["do"], s["P"], s["k"], s["dS"], s["out_re"], p)
 
+    def k_attn_bwd_regen(s): B.tempo_attn_softmax_dropout_bwd_regen(s["do"], s["P"], s["dS"], s["out_re"], p, seed, 0)
+
     kernels = {
         "gelu_fwd": (k_gelu_fwd, gelu_b), "gelu_bwd": (k_gelu_bwd, gelu_b),
         "layernorm_fwd": (k_ln_fwd, ln_b), "layernorm_bwd": (k_ln_bwd, ln_b),
         "attn_fwd": (k_attn_fwd, attn_b), "attn_bwd": (k_attn_bwd, attn_b),
     }
+    variants = {"attn_bwd_regen": (k_attn_bwd_regen, attn_b)}   # timed, not part of the step
 
     # every set gets a valid forward state once (backward kernels read y / P / masks)
     for s in gelu_b.sets: k_gelu_fwd(s)
@@ -200,7 +214,7 @@ def main():
     # around a replayed graph of kernel_iters back-to-back launches over rotating buffers
     per_kernel = {}
     if not args.no_kernel_timing:
-        for name, (fn, bufs) in kernels.items():
+        for name, (fn, bufs) in {**kernels, **variants}.items():
             if args.only is not None and name != args.only:
                 continue
             for _ in range(max(3, bufs.n)):
@@ -245,7 +259,8 @@ def main():
     value = step_bytes / (ms_per_step * 1e-3) * 1e-9 if ms_per_step == ms_per_step else None
     roofline = None
     if per_kernel:
-        weight = {k: v["us"] * (2 if k.startswith("layernorm") else 1) for k, v in per_kernel.items()}
+        weight = {k: v["us"] * (2 if k.startswith("layernorm") else 1) for k, v in per_kernel.items()
+                  if k in kernels} or {k: v["us"] for k, v in per_kernel.items()}
         dom = max(weight, key=weight.get)
         k = per_kernel[dom]
         roofline = {"kernel": dom, "bound": "hbm", "achieved": k["GB/s"], "peak": HBM_PEAK_GBS,

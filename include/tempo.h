@@ -167,6 +167,36 @@ TEMPO_API tempo_status tempo_attn_softmax_dropout_bwd(const void* dout, const vo
                                             int64_t B, int64_t A, int64_t Sq, int64_t Sk, float p,
                                             tempo_dtype dt, void* hip_stream);
 
+/*
+ * The same backward with no stored mask                                   [Sec. 3.3; App. E.4]
+ *   Sec. 3.3 weighs keeping the dropout mask against producing it again.  Because the keep
+ *   decision of element e is a pure function of (seed, offset, e) (the dropout contract of the
+ *   forward above), backward can draw the bits again: pass the p, seed and offset of the forward
+ *   call and keep no mask at all (forward's keep_bits output still has to be a valid buffer; it
+ *   can be a transient).  Results are bit-identical to tempo_attn_softmax_dropout_bwd on the
+ *   forward's mask.  Costs one generator call per 8 elements instead of 1/8 byte of traffic.
+ *   Arguments as above.
+ */
+TEMPO_API tempo_status tempo_attn_softmax_dropout_bwd_regen(const void* dout, const void* probs,
+                                            void* dscores, void* out_recomputed,
+                                            int64_t B, int64_t A, int64_t Sq, int64_t Sk, float p,
+                                            uint64_t seed, uint64_t offset,
+                                            tempo_dtype dt, void* hip_stream);
+
+/*
+ * Mask layout conversion: packed bits <-> one byte per element        [Sec. 3.3 (8-bit masks)]
+ *   The paper's implementation keeps the dropout mask as one byte per element; this library
+ *   keeps one bit (bit e & 31 of word e >> 5).  These two calls convert between the layouts,
+ *   e.g. to hand a mask to, or take one from, code that expects boolean bytes.
+ *   bits  [ceil(n/32)] device words;  bytes [n] device bytes, both 16-byte aligned.
+ *   bits_to_bytes writes 0 or 1 per element.  bytes_to_bits sets bit e iff bytes[e] != 0 and
+ *   writes 0 into the unused high bits of the last word.  n == 0 is a no-op.
+ */
+TEMPO_API tempo_status tempo_mask_bits_to_bytes(const uint32_t* bits, uint8_t* bytes, int64_t n,
+                                            void* hip_stream);
+TEMPO_API tempo_status tempo_mask_bytes_to_bits(const uint8_t* bytes, uint32_t* bits, int64_t n,
+                                            void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

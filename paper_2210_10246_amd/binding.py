@@ -40,6 +40,10 @@ _SIGNATURES = {
                                               _i64, _f32, _u64, _u64, _int, _vp]),
     "tempo_attn_softmax_dropout_bwd": (_int, [_vp, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _i64,
                                               _f32, _int, _vp]),
+    "tempo_attn_softmax_dropout_bwd_regen": (_int, [_vp, _vp, _vp, _vp, _i64, _i64, _i64, _i64,
+                                                    _f32, _u64, _u64, _int, _vp]),
+    "tempo_mask_bits_to_bytes": (_int, [_vp, _vp, _i64, _vp]),
+    "tempo_mask_bytes_to_bits": (_int, [_vp, _vp, _i64, _vp]),
 }
 
 _lib = None
@@ -157,3 +161,21 @@ def tempo_attn_softmax_dropout_bwd(dout, probs, keep_bits, dscores, out_recomput
     _check(load().tempo_attn_softmax_dropout_bwd(
         _ptr(dout), _ptr(probs), _ptr(keep_bits), _ptr(dscores), _ptr(out_recomputed),
         B, A, Sq, Sk, p, _DT[probs.dtype], _stream(stream)), "tempo_attn_softmax_dropout_bwd")
+
+
+def tempo_attn_softmax_dropout_bwd_regen(dout, probs, dscores, out_recomputed, p, seed, offset,
+                                         stream=None):
+    B, A, Sq, Sk = probs.shape
+    _check(load().tempo_attn_softmax_dropout_bwd_regen(
+        _ptr(dout), _ptr(probs), _ptr(dscores), _ptr(out_recomputed), B, A, Sq, Sk, p, seed,
+        offset, _DT[probs.dtype], _stream(stream)), "tempo_attn_softmax_dropout_bwd_regen")
+
+
+def tempo_mask_bits_to_bytes(bits, bytes_, n, stream=None):
+    _check(load().tempo_mask_bits_to_bytes(_ptr(bits), _ptr(bytes_), n, _stream(stream)),
+           "tempo_mask_bits_to_bytes")
+
+
+def tempo_mask_bytes_to_bits(bytes_, bits, n, stream=None):
+    _check(load().tempo_mask_bytes_to_bits(_ptr(bytes_), _ptr(bits), n, _stream(stream)),
+           "tempo_mask_bytes_to_bits")

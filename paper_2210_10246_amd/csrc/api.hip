@@ -184,4 +184,38 @@ tempo_status tempo_attn_softmax_dropout_bwd(const void* dout, const void* probs,
                          static_cast<hipStream_t>(hip_stream));
 }
 
+tempo_status tempo_attn_softmax_dropout_bwd_regen(const void* dout, const void* probs,
+                                                  void* dscores, void* out_recomputed, int64_t B,
+                                                  int64_t A, int64_t Sq, int64_t Sk, float p,
+                                                  uint64_t seed, uint64_t offset, tempo_dtype dt,
+                                                  void* hip_stream) {
+  if (B < 0 || A < 0 || Sq < 0 || Sk < 0 || !dtype_ok(dt) || !prob_ok(p) || Sq > INT32_MAX ||
+      Sk > INT32_MAX)
+    return TEMPO_ERR_INVALID_ARG;
+  if (B == 0 || A == 0 || Sq == 0 || Sk == 0) return TEMPO_OK;
+  if (!dout || !probs || !dscores) return TEMPO_ERR_INVALID_ARG;
+  if (!aligned16(dout) || !aligned16(probs) || !aligned16(dscores) || !aligned16(out_recomputed))
+    return TEMPO_ERR_UNSUPPORTED;
+  return launch_attn_bwd_regen(dout, probs, dscores, out_recomputed, B, A, Sq, Sk, p, seed,
+                               offset, dt, static_cast<hipStream_t>(hip_stream));
+}
+
+tempo_status tempo_mask_bits_to_bytes(const uint32_t* bits, uint8_t* bytes, int64_t n,
+                                      void* hip_stream) {
+  if (n < 0) return TEMPO_ERR_INVALID_ARG;
+  if (n == 0) return TEMPO_OK;
+  if (!bits || !bytes) return TEMPO_ERR_INVALID_ARG;
+  if (!aligned16(bits) || !aligned16(bytes)) return TEMPO_ERR_UNSUPPORTED;
+  return launch_mask_bits_to_bytes(bits, bytes, n, static_cast<hipStream_t>(hip_stream));
+}
+
+tempo_status tempo_mask_bytes_to_bits(const uint8_t* bytes, uint32_t* bits, int64_t n,
+                                      void* hip_stream) {
+  if (n < 0) return TEMPO_ERR_INVALID_ARG;
+  if (n == 0) return TEMPO_OK;
+  if (!bits || !bytes) return TEMPO_ERR_INVALID_ARG;
+  if (!aligned16(bits) || !aligned16(bytes)) return TEMPO_ERR_UNSUPPORTED;
+  return launch_mask_bytes_to_bits(bytes, bits, n, static_cast<hipStream_t>(hip_stream));
+}
+
 }  // extern "C"

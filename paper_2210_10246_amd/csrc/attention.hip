@@ -3,9 +3,10 @@
 // Forward keeps only P (the softmax output) and a 1-bit keep mask; the dropout output is a
 // transient.  Backward rebuilds the dropout output from (P, mask) by one multiply and derives
 // the score gradient from P alone.  A group of LANES lanes owns one row in registers (CH
-// chunks of 8 elements per lane, chunk c of lane t = c*LANES + t so every access of a group
-// is contiguous).  The keep bits come from Philox4x32-10, one call per chunk, so the mask is a
-// pure function of (seed, offset, element index) and does not depend on the launch shape.
+// 16-byte pieces per lane, piece c of lane t = c*LANES + t so every access of a group is
+// contiguous).  The keep bits come from Philox4x32-10, one call per 8 elements, so the mask is
+// a pure function of (seed, offset, element index) and does not depend on the launch shape;
+// backward can therefore also draw the bits again instead of reading a stored mask.
 #include <type_traits>
 
 #include "tempo_device.h"
@@ -246,10 +247,15 @@ __global__ __launch_bounds__(kThreads) void attn_fwd_kernel(
   }
 }
 
-template <typename T, int LANES, int CH, int R, bool WORDS>
+// MASK says where backward takes the keep bits from: the stored mask read as whole words
+// (Sk % 32 == 0) or as bytes, or the generator (no mask is read; Sec. 3.3 weighs storing the
+// mask against drawing it again).
+enum MaskSource { kMaskWords, kMaskBytes, kMaskRegen };
+
+template <typename T, int LANES, int CH, int R, MaskSource MASK>
 __global__ __launch_bounds__(kThreads) void attn_bwd_kernel(
     const T* dout, const T* __restrict__ probs, const uint32_t* __restrict__ keep_bits,
-    T* dscores, T* __restrict__ out_re, int64_t rows, int Sk, float scale) {
+    T* dscores, T* __restrict__ out_re, int64_t rows, int Sk, float scale, RngArgs rng) {
   constexpr int kGroups = kThreads / LANES;
   constexpr int V = Store<T>::kVec;
   const int g = threadIdx.x / LANES;
@@ -269,9 +275,15 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_kernel(
         if (row < rows && pc < pieces) {
           rdo[r][c].load(dout + row * Sk + pc * V);
           rp[r][c].load(probs + row * Sk + pc * V);
-          bits[r][c] = load_keep_bits<T, WORDS>(keep_bits, row * pieces + pc);
+          if constexpr (MASK != kMaskRegen)
+            bits[r][c] = load_keep_bits<T, MASK == kMaskWords>(keep_bits, row * pieces + pc);
         }
       }
+    }
+    if constexpr (MASK == kMaskRegen) {  // every lane takes part: lane pairs share draws
+#pragma unroll
+      for (int r = 0; r < R; ++r)
+        lane_keep_bits<T, LANES, CH>((base + r * kGroups + g) * pieces, t, rng, bits[r]);
     }
 #pragma unroll
     for (int r = 0; r < R; ++r) {
@@ -372,10 +384,14 @@ __global__ __launch_bounds__(kThreads) void keep_words_kernel(uint32_t* __restri
   }
 }
 
-template <typename T>
+template <typename T, bool REGEN>
 __global__ __launch_bounds__(kThreads) void attn_bwd_generic_kernel(
     const T* dout, const T* __restrict__ probs, const uint32_t* __restrict__ keep_bits,
-    T* dscores, T* __restrict__ out_re, int64_t rows, int Sk, float scale) {
+    T* dscores, T* __restrict__ out_re, int64_t rows, int Sk, float scale, RngArgs rng) {
+  auto kept = [&](int64_t e) -> bool {
+    if constexpr (REGEN) return keep_bit_of(e, rng);
+    else return (keep_bits[e >> 5] >> (e & 31)) & 1u;
+  };
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = threadIdx.x / kWave;
   constexpr int kWaves = kThreads / kWave;
@@ -384,14 +400,14 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_generic_kernel(
     float dot = 0.0f;
     for (int j = lane; j < Sk; j += kWave) {
       const int64_t e = row * Sk + j;
-      const bool k = (keep_bits[e >> 5] >> (e & 31)) & 1u;
+      const bool k = kept(e);
       const float dp = k ? Store<T>::load1(dout + e) * scale : 0.0f;
       dot = fmaf(dp, Store<T>::load1(probs + e), dot);
     }
     dot = group_sum<kWave>(dot);
     for (int j = lane; j < Sk; j += kWave) {
       const int64_t e = row * Sk + j;
-      const bool k = (keep_bits[e >> 5] >> (e & 31)) & 1u;
+      const bool k = kept(e);
       const float p = Store<T>::load1(probs + e);
       const float dp = k ? Store<T>::load1(dout + e) * scale : 0.0f;
       Store<T>::store1(dscores + e, p * (dp - dot));
@@ -474,17 +490,31 @@ static void attn_fwd_go(int rr, bool words, dim3 grid, hipStream_t st, const voi
 }
 
 template <typename T, int L, int C>
-static void attn_bwd_go(bool words, int grid, hipStream_t st, const void* dout, const void* probs,
-                        const uint32_t* keep_bits, void* dscores, void* out_re, int64_t rows,
-                        int64_t Sk, float scale) {
-  auto go = [&](auto w) {
-    hipLaunchKernelGGL((attn_bwd_kernel<T, L, C, 1, decltype(w)::value>), dim3(grid),
+static void attn_bwd_go(MaskSource mask, int grid, hipStream_t st, const void* dout,
+                        const void* probs, const uint32_t* keep_bits, void* dscores, void* out_re,
+                        int64_t rows, int64_t Sk, float scale, const RngArgs& rng) {
+  auto go = [&](auto m) {
+    hipLaunchKernelGGL((attn_bwd_kernel<T, L, C, 1, decltype(m)::value>), dim3(grid),
                        dim3(kThreads), 0, st, static_cast<const T*>(dout),
                        static_cast<const T*>(probs), keep_bits, static_cast<T*>(dscores),
-                       static_cast<T*>(out_re), rows, static_cast<int>(Sk), scale);
+                       static_cast<T*>(out_re), rows, static_cast<int>(Sk), scale, rng);
   };
-  if (words) return go(std::true_type{});
-  go(std::false_type{});
+  using std::integral_constant;
+  if (mask == kMaskWords) return go(integral_constant<MaskSource, kMaskWords>{});
+  if (mask == kMaskBytes) return go(integral_constant<MaskSource, kMaskBytes>{});
+  go(integral_constant<MaskSource, kMaskRegen>{});
+}
+
+static RngArgs make_rng(float p, uint64_t seed, uint64_t offset) {
+  RngArgs rng;
+  rng.seed_lo = static_cast<uint32_t>(seed);
+  rng.seed_hi = static_cast<uint32_t>(seed >> 32);
+  rng.off_lo = static_cast<uint32_t>(offset);
+  rng.off_hi = static_cast<uint32_t>(offset >> 32);
+  double t = (1.0 - static_cast<double>(p)) * 65536.0 + 0.5;
+  t = t < 0.0 ? 0.0 : (t > 65536.0 ? 65536.0 : t);
+  rng.t16 = (p == 0.0f) ? 65536u : static_cast<uint32_t>(t);  // floor for t >= 0
+  return rng;
 }
 
 tempo_status launch_attn_fwd(const void* scores, const int32_t* key_len, int causal, void* probs,
@@ -494,14 +524,7 @@ tempo_status launch_attn_fwd(const void* scores, const int32_t* key_len, int cau
   const int64_t rows = B * A * Sq;
   const int64_t rows_per_batch = A * Sq;
   const float scale = 1.0f / (1.0f - p);
-  RngArgs rng;
-  rng.seed_lo = static_cast<uint32_t>(seed);
-  rng.seed_hi = static_cast<uint32_t>(seed >> 32);
-  rng.off_lo = static_cast<uint32_t>(offset);
-  rng.off_hi = static_cast<uint32_t>(offset >> 32);
-  double t = (1.0 - static_cast<double>(p)) * 65536.0 + 0.5;
-  t = t < 0.0 ? 0.0 : (t > 65536.0 ? 65536.0 : t);
-  rng.t16 = (p == 0.0f) ? 65536u : static_cast<uint32_t>(t);  // floor for t >= 0
+  const RngArgs rng = make_rng(p, seed, offset);
   const int bpc = tune_get(kTuneAttnFwdBlocksPerCu);
   const int vec = dt == TEMPO_F32 ? 4 : 8;
   Shape sh = pick_shape(static_cast<int>(Sk / vec), 32 / vec);
@@ -544,38 +567,60 @@ tempo_status launch_attn_fwd(const void* scores, const int32_t* key_len, int cau
   return launch_status();
 }
 
-tempo_status launch_attn_bwd(const void* dout, const void* probs, const uint32_t* keep_bits,
-                             void* dscores, void* out_re, int64_t B, int64_t A, int64_t Sq,
-                             int64_t Sk, float p, tempo_dtype dt, hipStream_t st) {
+// keep_bits == nullptr: no stored mask, the bits are drawn again from (seed, offset).
+static tempo_status attn_bwd_any(const void* dout, const void* probs, const uint32_t* keep_bits,
+                                 void* dscores, void* out_re, int64_t B, int64_t A, int64_t Sq,
+                                 int64_t Sk, float p, const RngArgs& rng, tempo_dtype dt,
+                                 hipStream_t st) {
   const int64_t rows = B * A * Sq;
   const float scale = 1.0f / (1.0f - p);
+  const bool regen = keep_bits == nullptr;
   const int bpc = tune_get(kTuneAttnBwdBlocksPerCu);
   const int vec = dt == TEMPO_F32 ? 4 : 8;
   Shape sh = pick_shape(static_cast<int>(Sk / vec), 32 / vec);
   if (Sk % 8 == 0 && sh.ch != 0) {
     const int grid = row_grid(rows, sh.lanes, bpc);
-    const bool words = (Sk % 32 == 0);
+    const MaskSource mask = regen ? kMaskRegen : (Sk % 32 == 0 ? kMaskWords : kMaskBytes);
 #define TEMPO_LAUNCH(L, C)                                                                   \
   do {                                                                                       \
-    if (dt == TEMPO_F32) attn_bwd_go<float, L, C>(words, grid, st, dout, probs, keep_bits, dscores, out_re, rows, Sk, scale);   \
-    else attn_bwd_go<bf16_t, L, C>(words, grid, st, dout, probs, keep_bits, dscores, out_re, rows, Sk, scale);                  \
+    if (dt == TEMPO_F32) attn_bwd_go<float, L, C>(mask, grid, st, dout, probs, keep_bits, dscores, out_re, rows, Sk, scale, rng);   \
+    else attn_bwd_go<bf16_t, L, C>(mask, grid, st, dout, probs, keep_bits, dscores, out_re, rows, Sk, scale, rng);                  \
   } while (0)
     TEMPO_ATTN_DISPATCH(TEMPO_LAUNCH)
 #undef TEMPO_LAUNCH
     return launch_status();
   }
   const int grid = row_grid(rows, kWave, bpc);
-  if (dt == TEMPO_F32)
-    hipLaunchKernelGGL((attn_bwd_generic_kernel<float>), dim3(grid), dim3(kThreads), 0, st,
-                       static_cast<const float*>(dout), static_cast<const float*>(probs),
-                       keep_bits, static_cast<float*>(dscores), static_cast<float*>(out_re), rows,
-                       static_cast<int>(Sk), scale);
-  else
-    hipLaunchKernelGGL((attn_bwd_generic_kernel<bf16_t>), dim3(grid), dim3(kThreads), 0, st,
-                       static_cast<const bf16_t*>(dout), static_cast<const bf16_t*>(probs),
-                       keep_bits, static_cast<bf16_t*>(dscores), static_cast<bf16_t*>(out_re),
-                       rows, static_cast<int>(Sk), scale);
+  auto go = [&](auto tag, auto re) {
+    using T = decltype(tag);
+    hipLaunchKernelGGL((attn_bwd_generic_kernel<T, decltype(re)::value>), dim3(grid),
+                       dim3(kThreads), 0, st, static_cast<const T*>(dout),
+                       static_cast<const T*>(probs), keep_bits, static_cast<T*>(dscores),
+                       static_cast<T*>(out_re), rows, static_cast<int>(Sk), scale, rng);
+  };
+  if (dt == TEMPO_F32) {
+    if (regen) go(float{}, std::true_type{});
+    else go(float{}, std::false_type{});
+  } else {
+    if (regen) go(bf16_t{}, std::true_type{});
+    else go(bf16_t{}, std::false_type{});
+  }
   return launch_status();
+}
+
+tempo_status launch_attn_bwd(const void* dout, const void* probs, const uint32_t* keep_bits,
+                             void* dscores, void* out_re, int64_t B, int64_t A, int64_t Sq,
+                             int64_t Sk, float p, tempo_dtype dt, hipStream_t st) {
+  return attn_bwd_any(dout, probs, keep_bits, dscores, out_re, B, A, Sq, Sk, p,
+                      make_rng(0.0f, 0, 0), dt, st);
+}
+
+tempo_status launch_attn_bwd_regen(const void* dout, const void* probs, void* dscores,
+                                   void* out_re, int64_t B, int64_t A, int64_t Sq, int64_t Sk,
+                                   float p, uint64_t seed, uint64_t offset, tempo_dtype dt,
+                                   hipStream_t st) {
+  return attn_bwd_any(dout, probs, nullptr, dscores, out_re, B, A, Sq, Sk, p,
+                      make_rng(p, seed, offset), dt, st);
 }
 
 }  // namespace tempo

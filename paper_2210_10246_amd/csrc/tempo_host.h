@@ -46,5 +46,13 @@ tempo_status launch_attn_fwd(const void* scores, const int32_t* key_len, int cau
 tempo_status launch_attn_bwd(const void* dout, const void* probs, const uint32_t* keep_bits,
                              void* dscores, void* out_re, int64_t B, int64_t A, int64_t Sq,
                              int64_t Sk, float p, tempo_dtype dt, hipStream_t st);
+tempo_status launch_attn_bwd_regen(const void* dout, const void* probs, void* dscores,
+                                   void* out_re, int64_t B, int64_t A, int64_t Sq, int64_t Sk,
+                                   float p, uint64_t seed, uint64_t offset, tempo_dtype dt,
+                                   hipStream_t st);
+tempo_status launch_mask_bits_to_bytes(const uint32_t* bits, uint8_t* bytes, int64_t n,
+                                       hipStream_t st);
+tempo_status launch_mask_bytes_to_bits(const uint8_t* bytes, uint32_t* bits, int64_t n,
+                                       hipStream_t st);
 
 }  // namespace tempo

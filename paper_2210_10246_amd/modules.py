@@ -97,39 +97,49 @@ class InplaceLayerNorm(nn.Module):
 
 class _AttentionCoreFn(torch.autograd.Function):
     @staticmethod
-    def forward(ctx, scores, v, key_len, causal, p, seed, offset):
+    def forward(ctx, scores, v, key_len, causal, p, seed, offset, store_mask):
         scores = scores.contiguous()
         probs = torch.empty_like(scores)
         out = torch.empty_like(scores)          # transient: freed when forward returns
         keep = _words(scores.numel(), scores.device)
         B.tempo_attn_softmax_dropout_fwd(scores, key_len, causal, probs, out, keep, p, seed, offset)
-        ctx.p = p
-        ctx.save_for_backward(probs, keep, v)
+        ctx.rng = (p, seed, offset)
+        ctx.store_mask = store_mask
+        if store_mask:
+            ctx.save_for_backward(probs, v, keep)
+        else:                                   # the mask is a transient too: drawn again later
+            ctx.save_for_backward(probs, v)
         return torch.matmul(out, v)
 
     @staticmethod
     def backward(ctx, dctx):
-        probs, keep, v = ctx.saved_tensors
+        probs, v = ctx.saved_tensors[:2]
         dout = torch.matmul(dctx, v.transpose(-1, -2)).contiguous()
         out_re = torch.empty_like(probs)
         dscores = torch.empty_like(probs)
-        B.tempo_attn_softmax_dropout_bwd(dout, probs, keep, dscores, out_re, ctx.p)
+        p, seed, offset = ctx.rng
+        if ctx.store_mask:
+            B.tempo_attn_softmax_dropout_bwd(dout, probs, ctx.saved_tensors[2], dscores, out_re, p)
+        else:
+            B.tempo_attn_softmax_dropout_bwd_regen(dout, probs, dscores, out_re, p, seed, offset)
         dv = torch.matmul(out_re.transpose(-1, -2), dctx)
-        return dscores, dv, None, None, None, None, None
+        return dscores, dv, None, None, None, None, None, None
 
 
 class TempoAttentionCore(nn.Module):
     """context = dropout(softmax(mask(scores))) @ V for scores [B, A, Sq, Sk] already scaled by
-    1/sqrt(d).  Each forward in training mode draws a fresh mask: the counter offset advances."""
+    1/sqrt(d).  Each forward in training mode draws a fresh mask: the counter offset advances.
+    store_mask=False keeps no mask for backward, which then draws the same bits again."""
 
-    def __init__(self, p: float = 0.1, seed: int = 0x5EED):
+    def __init__(self, p: float = 0.1, seed: int = 0x5EED, store_mask: bool = True):
         super().__init__()
-        self.p, self.seed, self.offset = p, seed, 0
+        self.p, self.seed, self.offset, self.store_mask = p, seed, 0, store_mask
 
     def forward(self, scores, v, key_len=None, causal=False):
         p = self.p if self.training else 0.0
         self.offset += 1
-        return _AttentionCoreFn.apply(scores, v, key_len, causal, p, self.seed, self.offset)
+        return _AttentionCoreFn.apply(scores, v, key_len, causal, p, self.seed, self.offset,
+                                      self.store_mask)
 
 
 class TempoEncoderLayer(nn.Module):

@@ -111,6 +111,24 @@ def test_encoder_layer_keeps_fewer_activation_bytes(M):
           f"saved {saved / tokens:.0f} (expected >= {0.85 * expected / tokens:.0f})")
 
 
+def test_attention_core_without_stored_mask(M):
+    """store_mask=False: same gradients bit for bit, and the mask leaves the stash."""
+    torch.manual_seed(3)
+    Bn, A, S, d = 2, 4, 96, 32
+    scores = torch.randn(Bn, A, S, S, device="cuda", requires_grad=True)
+    v = torch.randn(Bn, A, S, d, device="cuda", requires_grad=True)
+    dctx = torch.randn(Bn, A, S, d, device="cuda")
+    res = {}
+    for store in (True, False):
+        core = M.TempoAttentionCore(0.1, seed=5, store_mask=store).cuda().train()
+        stash, out = _stashed_bytes(lambda: core(scores, v))
+        res[store] = (stash, out, torch.autograd.grad(out, (scores, v), dctx))
+    assert torch.equal(res[True][1], res[False][1])
+    for a, b in zip(res[True][2], res[False][2]):
+        assert torch.equal(a, b)
+    assert res[True][0] - res[False][0] == scores.numel() // 8
+
+
 def test_modules_in_bf16(M):
     torch.manual_seed(2)
     gelu = M.InplaceGELU().cuda()

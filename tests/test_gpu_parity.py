@@ -288,6 +288,72 @@ def test_attn_bwd(B, case, dt):
     assert torch.equal(dod, dsd)
 
 
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+@pytest.mark.parametrize("case", ATTN_CASES, ids=lambda c: "x".join(map(str, c)))
+def test_attn_bwd_without_stored_mask(B, case, dt):
+    """Backward that draws the keep bits again from (seed, offset) against the oracle's backward
+    on the oracle's mask, and bit for bit against the mask-reading backward."""
+    rng = np.random.default_rng(hash(case[:4]) % (1 << 31) + 2)
+    s, key_len, causal, p = _attn_inputs(case, dt, rng)
+    seed, offset = 0xC0FFEE0000000001, (1 << 40) + 3
+    P, _, K = O.attn_softmax_dropout_fwd(s, key_len, causal, p, seed, offset, dt)
+    dout = stored(rng, s.shape, dt)
+    dS_ref, out_re_ref = O.attn_softmax_dropout_bwd(dout, P, K, p, dt)
+    dod, Pd = dev(dout, dt), dev(P, dt)
+    dsd, ord_ = torch.empty_like(dod), torch.empty_like(dod)
+    B.tempo_attn_softmax_dropout_bwd_regen(dod, Pd, dsd, ord_, float(p), seed, offset)
+    torch.cuda.synchronize()
+    assert rel_err(host(dsd), dS_ref) <= TOL[dt]
+    assert rel_err(host(ord_), out_re_ref) <= TOL[dt]
+    assert np.array_equal(host(ord_) != 0, (K & (P != 0)))
+    md = torch.from_numpy(O.pack_bits(K).view(np.int32)).cuda()
+    ds2, or2 = torch.empty_like(dod), torch.empty_like(dod)
+    B.tempo_attn_softmax_dropout_bwd(dod, Pd, md, ds2, or2, float(p))
+    torch.cuda.synchronize()
+    assert torch.equal(dsd, ds2) and torch.equal(ord_, or2)
+
+
+@pytest.mark.parametrize("n", [1, 15, 16, 17, 31, 32, 33, 4096, 100_003, 3_000_000])
+def test_mask_layout_conversion(B, n):
+    rng = np.random.default_rng(n)
+    K = rng.random(n) < 0.9
+    bits = torch.from_numpy(O.pack_bits(K).view(np.int32)).cuda()
+    pad = (-n) % 16
+    bytes_d = torch.full((n + pad,), 7, dtype=torch.uint8, device="cuda")
+    B.tempo_mask_bits_to_bytes(bits, bytes_d, n)
+    torch.cuda.synchronize()
+    got = bytes_d.cpu().numpy()
+    assert np.array_equal(got[:n], K.astype(np.uint8))
+    assert np.all(got[n:] == 7), "wrote past n"
+    # and back; any non-zero byte counts as kept
+    src = K.astype(np.uint8) * rng.integers(1, 256, n).astype(np.uint8)
+    src_d = torch.from_numpy(src).cuda()
+    back = torch.full((B.mask_words(n) + 4,), -1, dtype=torch.int32, device="cuda")
+    B.tempo_mask_bytes_to_bits(src_d, back, n)
+    torch.cuda.synchronize()
+    w = words(back)
+    assert np.array_equal(w[:B.mask_words(n)], O.pack_bits(K))
+    assert np.all(w[B.mask_words(n):] == 0xFFFFFFFF), "wrote past the last word"
+
+
+def test_byte_mask_from_forward_feeds_backward(B):
+    """A mask kept as bytes (the paper's layout) converts back to the bits backward reads."""
+    rng = np.random.default_rng(77)
+    s = stored(rng, (2, 3, 48, 96), "bf16")
+    sd = dev(s, "bf16")
+    Pd, od = torch.empty_like(sd), torch.empty_like(sd)
+    n = s.size
+    md = torch.empty(B.mask_words(n), dtype=torch.int32, device="cuda")
+    B.tempo_attn_softmax_dropout_fwd(sd, None, False, Pd, od, md, 0.1, 11, 12)
+    kept = torch.empty(n, dtype=torch.uint8, device="cuda")
+    B.tempo_mask_bits_to_bytes(md, kept, n)
+    K = O.dropout_keep(n, np.float32(0.1), 11, 12)
+    assert np.array_equal(kept.cpu().numpy(), K.astype(np.uint8))
+    md2 = torch.zeros_like(md)
+    B.tempo_mask_bytes_to_bits(kept, md2, n)
+    assert torch.equal(md, md2)
+
+
 def test_mask_does_not_depend_on_launch_shape(B):
     rng = np.random.default_rng(5)
     s = stored(rng, (2, 2, 64, 256), "bf16")
