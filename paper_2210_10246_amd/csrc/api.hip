@@ -16,6 +16,8 @@ static std::atomic<int> g_tune[kTuneCount] = {
     {65536},  // attention bwd: workgroups per CU
     {2},      // attention fwd: rows per lane group
     {2},      // layernorm fwd: rows per lane group
+    {2},      // attention fwd: most pieces per lane of a one-wave row
+    {4},      // attention bwd: the same
 };
 
 int tune_get(TuneKey k) { return g_tune[k].load(std::memory_order_relaxed); }

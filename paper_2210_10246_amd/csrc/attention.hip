@@ -145,6 +145,27 @@ __device__ __forceinline__ uint32_t load_keep_bits(const uint32_t* keep_bits, in
   }
 }
 
+// Row reductions.  A row inside one wave: butterflies (every lane ends with the result).  A row
+// spread over LANES/64 waves of the workgroup: butterfly per wave, then one exchange through
+// `slots` (one float per wave of the workgroup) behind a workgroup barrier, so every thread of
+// the workgroup has to call it; consecutive calls must alternate between two slot arrays.
+template <int LANES, bool MAX>
+__device__ __forceinline__ float row_reduce(float v, float* slots) {
+  if constexpr (LANES <= kWave) {
+    return MAX ? group_max<LANES>(v) : group_sum<LANES>(v);
+  } else {
+    v = MAX ? group_max<kWave>(v) : group_sum<kWave>(v);
+    if ((threadIdx.x & (kWave - 1)) == 0) slots[threadIdx.x / kWave] = v;
+    __syncthreads();
+    constexpr int W = LANES / kWave;
+    const int w0 = (threadIdx.x / LANES) * W;
+    float r = slots[w0];
+#pragma unroll
+    for (int k = 1; k < W; ++k) r = MAX ? fmaxf(r, slots[w0 + k]) : r + slots[w0 + k];
+    return r;
+  }
+}
+
 // Work unit = one "row set": kGroups*R consecutive query rows of one [Sq, Sk] slice, where
 // kGroups = kThreads/LANES lane groups each own R rows (rows base + r*kGroups + g) and CH
 // 16-byte pieces per row (piece c of lane t = c*LANES + t).  All R rows of a group are fetched
@@ -152,6 +173,9 @@ __device__ __forceinline__ uint32_t load_keep_bits(const uint32_t* keep_bits, in
 // flight, too little to cover the memory latency at 32 waves per compute unit.  With the
 // default launch cap every row set has its own workgroup and the grid sweeps memory front to
 // back; under a smaller cap workgroups walk the row sets grid-stride.
+// LANES = 128 or 256 spreads a long row over 2 or 4 waves: the pieces per lane, and with them
+// the registers per lane, stay small enough for many resident waves (a 3072-element bfloat16
+// row on one wave needs over 200 registers per lane, which leaves 2 waves per SIMD).
 template <typename T, int LANES, int CH, int R, bool WORDS>
 __global__ __launch_bounds__(kThreads) void attn_fwd_kernel(
     const T* scores, const int32_t* __restrict__ key_len, int causal, T* probs,
@@ -165,6 +189,8 @@ __global__ __launch_bounds__(kThreads) void attn_fwd_kernel(
   const int sets_per_slice = (Sq + kGroups * R - 1) / (kGroups * R);
   const int64_t total_sets = static_cast<int64_t>(slices) * sets_per_slice;
   const int64_t total_pieces = static_cast<int64_t>(slices) * Sq * pieces;
+  __shared__ float red[2][kThreads / kWave];
+  static_assert(LANES <= kWave || R == 1, "rows over several waves: one row per group");
 
   for (int64_t rs = blockIdx.x; rs < total_sets; rs += gridDim.x) {
     const int slice = static_cast<int>(rs / sets_per_slice);
@@ -186,7 +212,10 @@ __global__ __launch_bounds__(kThreads) void attn_fwd_kernel(
     }
 #pragma unroll
     for (int r = 0; r < R; ++r) {
-      if (limit[r] < 0) continue;  // uniform over the lane group
+      // no row: uniform over the lane group; a group of several waves walks on (no loads, no
+      // stores) because the reductions below hold workgroup barriers
+      const bool live = limit[r] >= 0;
+      if (LANES <= kWave && !live) continue;
       const int64_t row = static_cast<int64_t>(slice) * Sq + i0 + r * kGroups;
       float v[CH][V];
       float mx = -INFINITY;
@@ -203,7 +232,7 @@ __global__ __launch_bounds__(kThreads) void attn_fwd_kernel(
           for (int k = 0; k < V; ++k) mx = fmaxf(mx, v[c][k]);
         }
       }
-      mx = group_max<LANES>(mx);
+      mx = row_reduce<LANES, true>(mx, red[0]);
       const float shift = (mx == -INFINITY) ? 0.0f : mx * kLog2e;
       float sum = 0.0f;
 #pragma unroll
@@ -221,7 +250,7 @@ __global__ __launch_bounds__(kThreads) void attn_fwd_kernel(
           for (int k = 0; k < V; ++k) v[c][k] = 0.0f;
         }
       }
-      sum = group_sum<LANES>(sum);
+      sum = row_reduce<LANES, false>(sum, red[1]);
       const float rinv = (sum > 0.0f) ? __builtin_amdgcn_rcpf(sum) : 0.0f;
       const int64_t piece0 = row * pieces;
       uint32_t bits[CH];
@@ -229,7 +258,7 @@ __global__ __launch_bounds__(kThreads) void attn_fwd_kernel(
 #pragma unroll
       for (int c = 0; c < CH; ++c) {
         const int pc = c * LANES + t;
-        const bool valid = pc < pieces;
+        const bool valid = live && pc < pieces;
         if (valid) {
           float p8[V], o8[V];
 #pragma unroll
@@ -261,8 +290,11 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_kernel(
   const int g = threadIdx.x / LANES;
   const int t = threadIdx.x % LANES;
   const int pieces = Sk / V;
+  __shared__ float red[2][kThreads / kWave];
+  static_assert(LANES <= kWave || R == 1, "rows over several waves: one row per group");
+  int flip = 0;  // one reduction per row set: consecutive sets alternate between the slot arrays
   for (int64_t base = static_cast<int64_t>(blockIdx.x) * (kGroups * R); base < rows;
-       base += static_cast<int64_t>(gridDim.x) * (kGroups * R)) {
+       base += static_cast<int64_t>(gridDim.x) * (kGroups * R), flip ^= 1) {
     Raw<T> rdo[R][CH], rp[R][CH];
     uint32_t bits[R][CH];
 #pragma unroll
@@ -288,13 +320,16 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_kernel(
 #pragma unroll
     for (int r = 0; r < R; ++r) {
       const int64_t row = base + r * kGroups + g;
-      if (row >= rows) continue;  // uniform over the lane group
+      // no row: uniform over the lane group; a group of several waves walks on (the reduction
+      // holds a workgroup barrier) with zeros and stores nothing
+      const bool live = row < rows;
+      if (LANES <= kWave && !live) continue;
       float dp[CH][V], pr[CH][V];
       float dot = 0.0f;
 #pragma unroll
       for (int c = 0; c < CH; ++c) {
         const int pc = c * LANES + t;
-        if (pc < pieces) {
+        if (live && pc < pieces) {
           rdo[r][c].unpack(dp[c]);
           rp[r][c].unpack(pr[c]);
         } else {
@@ -307,11 +342,11 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_kernel(
           dot = fmaf(dp[c][k], pr[c][k], dot);
         }
       }
-      dot = group_sum<LANES>(dot);
+      dot = row_reduce<LANES, false>(dot, red[flip]);
 #pragma unroll
       for (int c = 0; c < CH; ++c) {
         const int pc = c * LANES + t;
-        if (pc < pieces) {
+        if (live && pc < pieces) {
           float ds[V];
 #pragma unroll
           for (int k = 0; k < V; ++k) ds[k] = pr[c][k] * (dp[c][k] - dot);
@@ -434,6 +469,22 @@ Shape pick_shape(int pieces, int min_lanes) {
   return {0, 0};
 }
 
+// A row whose pieces per lane on one wave would exceed max_ch is spread over 2 or 4 waves (at
+// most 4 pieces per lane there).
+Shape pick_wide_shape(int pieces, int min_lanes, int max_ch) {
+  const Shape one = pick_shape(pieces, min_lanes);
+  if (one.lanes == kWave && (one.ch == 0 || one.ch > max_ch)) {
+    for (int lanes = 2 * kWave; lanes <= kThreads; lanes *= 2) {
+      const int need = (pieces + lanes - 1) / lanes;
+      if (need <= max_ch || lanes == kThreads) {
+        if (need <= 4) return {lanes, need};
+        break;
+      }
+    }
+  }
+  return one;
+}
+
 // Rows a lane group of the forward kernel fetches at once: 2 (if the knob allows) while a row
 // is one or two pieces per lane, else 1.  Measured on [*,*,128..1024,*] maps: 2 rows beat 1 by
 // up to 25 % in forward and lose 3-8 % in backward, which therefore always takes 1.
@@ -467,6 +518,19 @@ int row_grid(int64_t rows, int lanes, int blocks_per_cu, int rows_per_group = 1)
     default: return TEMPO_ERR_UNSUPPORTED;                                                 \
   }
 
+#define TEMPO_ATTN_WIDE_DISPATCH(LAUNCH)                                                   \
+  switch (sh.lanes * 100 + sh.ch) {                                                        \
+    case 12801: LAUNCH(128, 1); break;                                                     \
+    case 12802: LAUNCH(128, 2); break;                                                     \
+    case 12803: LAUNCH(128, 3); break;                                                     \
+    case 12804: LAUNCH(128, 4); break;                                                     \
+    case 25601: LAUNCH(256, 1); break;                                                     \
+    case 25602: LAUNCH(256, 2); break;                                                     \
+    case 25603: LAUNCH(256, 3); break;                                                     \
+    case 25604: LAUNCH(256, 4); break;                                                     \
+    default: return TEMPO_ERR_UNSUPPORTED;                                                 \
+  }
+
 template <typename T, int L, int C>
 static void attn_fwd_go(int rr, bool words, dim3 grid, hipStream_t st, const void* scores,
                         const int32_t* key_len, int causal, void* probs, void* out,
@@ -479,7 +543,7 @@ static void attn_fwd_go(int rr, bool words, dim3 grid, hipStream_t st, const voi
                        static_cast<int>(A), static_cast<int>(Sq), static_cast<int>(Sk), scale, rng);
   };
   using std::integral_constant;
-  if constexpr (C <= 2) {
+  if constexpr (C <= 2 && L <= kWave) {
     if (rr == 2) {
       if (words) return go(integral_constant<int, 2>{}, std::true_type{});
       return go(integral_constant<int, 2>{}, std::false_type{});
@@ -527,10 +591,11 @@ tempo_status launch_attn_fwd(const void* scores, const int32_t* key_len, int cau
   const RngArgs rng = make_rng(p, seed, offset);
   const int bpc = tune_get(kTuneAttnFwdBlocksPerCu);
   const int vec = dt == TEMPO_F32 ? 4 : 8;
-  Shape sh = pick_shape(static_cast<int>(Sk / vec), 32 / vec);
+  Shape sh = pick_wide_shape(static_cast<int>(Sk / vec), 32 / vec,
+                            tune_get(kTuneAttnFwdMaxPieces));
   if (Sk % 8 == 0 && sh.ch != 0 && B * A <= INT32_MAX) {
     const int slices = static_cast<int>(B * A);
-    const int rr = attn_rows(sh.ch, tune_get(kTuneAttnFwdRows));
+    const int rr = sh.lanes > kWave ? 1 : attn_rows(sh.ch, tune_get(kTuneAttnFwdRows));
     const int rows_per_set = (kThreads / sh.lanes) * rr;
     const int64_t total_sets =
         static_cast<int64_t>(slices) * ((Sq + rows_per_set - 1) / rows_per_set);
@@ -542,7 +607,11 @@ tempo_status launch_attn_fwd(const void* scores, const int32_t* key_len, int cau
     if (dt == TEMPO_F32) attn_fwd_go<float, L, C>(rr, words, grid, st, scores, key_len, causal, probs, out, keep_bits, slices, A, Sq, Sk, scale, rng);   \
     else attn_fwd_go<bf16_t, L, C>(rr, words, grid, st, scores, key_len, causal, probs, out, keep_bits, slices, A, Sq, Sk, scale, rng);                  \
   } while (0)
-    TEMPO_ATTN_DISPATCH(TEMPO_LAUNCH)
+    if (sh.lanes > kWave) {
+      TEMPO_ATTN_WIDE_DISPATCH(TEMPO_LAUNCH)
+    } else {
+      TEMPO_ATTN_DISPATCH(TEMPO_LAUNCH)
+    }
 #undef TEMPO_LAUNCH
     return launch_status();
   }
@@ -577,7 +646,8 @@ static tempo_status attn_bwd_any(const void* dout, const void* probs, const uint
   const bool regen = keep_bits == nullptr;
   const int bpc = tune_get(kTuneAttnBwdBlocksPerCu);
   const int vec = dt == TEMPO_F32 ? 4 : 8;
-  Shape sh = pick_shape(static_cast<int>(Sk / vec), 32 / vec);
+  Shape sh = pick_wide_shape(static_cast<int>(Sk / vec), 32 / vec,
+                            tune_get(kTuneAttnBwdMaxPieces));
   if (Sk % 8 == 0 && sh.ch != 0) {
     const int grid = row_grid(rows, sh.lanes, bpc);
     const MaskSource mask = regen ? kMaskRegen : (Sk % 32 == 0 ? kMaskWords : kMaskBytes);
@@ -586,7 +656,11 @@ static tempo_status attn_bwd_any(const void* dout, const void* probs, const uint
     if (dt == TEMPO_F32) attn_bwd_go<float, L, C>(mask, grid, st, dout, probs, keep_bits, dscores, out_re, rows, Sk, scale, rng);   \
     else attn_bwd_go<bf16_t, L, C>(mask, grid, st, dout, probs, keep_bits, dscores, out_re, rows, Sk, scale, rng);                  \
   } while (0)
-    TEMPO_ATTN_DISPATCH(TEMPO_LAUNCH)
+    if (sh.lanes > kWave) {
+      TEMPO_ATTN_WIDE_DISPATCH(TEMPO_LAUNCH)
+    } else {
+      TEMPO_ATTN_DISPATCH(TEMPO_LAUNCH)
+    }
 #undef TEMPO_LAUNCH
     return launch_status();
   }

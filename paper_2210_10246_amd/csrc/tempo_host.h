@@ -18,7 +18,9 @@ enum TuneKey {
   kTuneAttnBwdBlocksPerCu = 5,
   kTuneAttnFwdRows = 6,         // rows a lane group of attn fwd fetches at once (1 or 2)
   kTuneLnFwdRows = 7,           // rows a lane group of layernorm_fwd fetches at once (1 or 2)
-  kTuneCount = 8
+  kTuneAttnFwdMaxPieces = 8,    // attn fwd: pieces per lane above which a row takes 2-4 waves
+  kTuneAttnBwdMaxPieces = 9,    // the same for attn bwd
+  kTuneCount = 10
 };
 int tune_get(TuneKey k);
 int compute_units();

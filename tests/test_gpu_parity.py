@@ -214,7 +214,9 @@ ATTN_CASES = [
     (2, 2, 16, 96, "zero_len", 0.1),   # one sequence fully masked
     (1, 2, 33, 2048, "causal", 0.1),
     (1, 1, 9, 3072, "padding", 0.1),
-    (1, 1, 5, 4104, "none", 0.1),      # longer than the register path
+    (1, 1, 5, 4104, "none", 0.1),      # longer than the register path in float32
+    (1, 2, 7, 8192, "causal", 0.1),    # longest row of the register path in bfloat16
+    (2, 1, 5, 1544, "padding", 0.1),   # long row ending inside a mask word
     (2, 2, 64, 160, "padding", 0.0),   # p = 0: everything kept
     (1, 1, 70, 1, "none", 0.1),
 ]
@@ -368,6 +370,50 @@ def test_mask_does_not_depend_on_launch_shape(B):
     B.tempo_set_launch_param(4, old)
     assert torch.equal(masks[0], masks[1]) and torch.equal(masks[0], masks[2])
     assert np.array_equal(words(masks[0]), O.pack_bits(O.dropout_keep(s.size, 0.1, 42, 0)))
+
+
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+def test_attn_row_over_one_or_several_waves(B, dt):
+    """Long rows: the same result whether one wave or 2-4 waves own a row (knob 8); the second
+    lane group of the last row set has no row when Sq is odd."""
+    rng = np.random.default_rng(8)
+    s = stored(rng, (1, 2, 5, 1024), dt, 0.125)
+    key_len = np.array([1000], dtype=np.int32)
+    P_ref, out_ref, K_ref = O.attn_softmax_dropout_fwd(s, key_len, False, np.float32(0.1), 3, 4, dt)
+    sd, kd = dev(s, dt), torch.from_numpy(key_len).cuda()
+    old = B.tempo_get_launch_param(8)
+    try:
+        for max_pieces in (1, 2, 4, 16):
+            B.tempo_set_launch_param(8, max_pieces)
+            Pd, od = torch.full_like(sd, 3.0), torch.full_like(sd, 3.0)
+            md = torch.full((B.mask_words(s.size),), -1, dtype=torch.int32, device="cuda")
+            B.tempo_attn_softmax_dropout_fwd(sd, kd, False, Pd, od, md, 0.1, 3, 4)
+            torch.cuda.synchronize()
+            assert np.array_equal(words(md), O.pack_bits(K_ref)), max_pieces
+            assert rel_err(host(Pd), P_ref) <= TOL[dt], max_pieces
+            assert rel_err(host(od), out_ref) <= TOL[dt], max_pieces
+    finally:
+        B.tempo_set_launch_param(8, old)
+    # backward, knob 9
+    dout = stored(rng, s.shape, dt)
+    dS_ref, out_re_ref = O.attn_softmax_dropout_bwd(dout, P_ref, K_ref, np.float32(0.1), dt)
+    dod, Pd = dev(dout, dt), dev(P_ref, dt)
+    md = torch.from_numpy(O.pack_bits(K_ref).view(np.int32)).cuda()
+    old = B.tempo_get_launch_param(9)
+    try:
+        for max_pieces in (1, 2, 4, 16):
+            B.tempo_set_launch_param(9, max_pieces)
+            for regen in (False, True):
+                dsd, ord_ = torch.full_like(dod, 3.0), torch.full_like(dod, 3.0)
+                if regen:
+                    B.tempo_attn_softmax_dropout_bwd_regen(dod, Pd, dsd, ord_, 0.1, 3, 4)
+                else:
+                    B.tempo_attn_softmax_dropout_bwd(dod, Pd, md, dsd, ord_, 0.1)
+                torch.cuda.synchronize()
+                assert rel_err(host(dsd), dS_ref) <= TOL[dt], (max_pieces, regen)
+                assert rel_err(host(ord_), out_re_ref) <= TOL[dt], (max_pieces, regen)
+    finally:
+        B.tempo_set_launch_param(9, old)
 
 
 def test_non_default_stream(B):
