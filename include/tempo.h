@@ -59,12 +59,12 @@ TEMPO_API int tempo_version(void);
  *   key 2, 4, 5: cap on workgroups per compute unit of layernorm_fwd, attn fwd, attn bwd
  *   (rows beyond the cap are walked in a loop);
  *   key 6, 7: rows a lane group of attn fwd / layernorm_fwd fetches at once (1 or 2);
- *   key 8, 9: attn fwd / bwd: 16-byte pieces per lane above which a row is spread over 2 or 4
- *   waves instead of one (16 or more: never);
- *   key 3: rows each lane group of layernorm_bwd walks; this sets its grid and the size of its
- *   workspace, so query tempo_layernorm_bwd_workspace_bytes after changing it.
+ *   key 8, 9, 10, 11: attn fwd / attn bwd / layernorm_fwd / layernorm_bwd: 16-byte pieces per
+ *   lane above which a row is spread over 2 or 4 waves instead of one (16 or more: never);
+ *   key 3: rows each lane group of layernorm_bwd walks; keys 3 and 11 set its grid and the
+ *   size of its workspace, so query tempo_layernorm_bwd_workspace_bytes after changing them.
  * Results never depend on these except the summation order of dgamma/dbeta and of the softmax
- * denominator and of the backward's row sum (keys 8, 9).  value in
+ * denominator and the other row sums (keys 8-11).  value in
  * [1, 65536].  tempo_set_launch_param returns TEMPO_OK or TEMPO_ERR_INVALID_ARG; the getter
  * returns -1 for an unknown key.
  */

@@ -10,7 +10,7 @@ namespace tempo {
 static std::atomic<int> g_tune[kTuneCount] = {
     {4},      // gelu fwd: chunks per lane
     {2},      // gelu bwd: chunks per lane
-    {65536},  // layernorm fwd: workgroups per CU (65536 = one row per lane group)
+    {3},      // layernorm fwd: workgroups per CU (beyond that they loop with prefetch)
     {4},      // layernorm bwd: rows per lane group
     {65536},  // attention fwd: workgroups per CU (65536 = one row per lane group)
     {65536},  // attention bwd: workgroups per CU
@@ -18,6 +18,8 @@ static std::atomic<int> g_tune[kTuneCount] = {
     {2},      // layernorm fwd: rows per lane group
     {2},      // attention fwd: most pieces per lane of a one-wave row
     {4},      // attention bwd: the same
+    {4},      // layernorm fwd: the same
+    {4},      // layernorm bwd: the same
 };
 
 int tune_get(TuneKey k) { return g_tune[k].load(std::memory_order_relaxed); }

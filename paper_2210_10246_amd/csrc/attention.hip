@@ -145,27 +145,6 @@ __device__ __forceinline__ uint32_t load_keep_bits(const uint32_t* keep_bits, in
   }
 }
 
-// Row reductions.  A row inside one wave: butterflies (every lane ends with the result).  A row
-// spread over LANES/64 waves of the workgroup: butterfly per wave, then one exchange through
-// `slots` (one float per wave of the workgroup) behind a workgroup barrier, so every thread of
-// the workgroup has to call it; consecutive calls must alternate between two slot arrays.
-template <int LANES, bool MAX>
-__device__ __forceinline__ float row_reduce(float v, float* slots) {
-  if constexpr (LANES <= kWave) {
-    return MAX ? group_max<LANES>(v) : group_sum<LANES>(v);
-  } else {
-    v = MAX ? group_max<kWave>(v) : group_sum<kWave>(v);
-    if ((threadIdx.x & (kWave - 1)) == 0) slots[threadIdx.x / kWave] = v;
-    __syncthreads();
-    constexpr int W = LANES / kWave;
-    const int w0 = (threadIdx.x / LANES) * W;
-    float r = slots[w0];
-#pragma unroll
-    for (int k = 1; k < W; ++k) r = MAX ? fmaxf(r, slots[w0 + k]) : r + slots[w0 + k];
-    return r;
-  }
-}
-
 // Work unit = one "row set": kGroups*R consecutive query rows of one [Sq, Sk] slice, where
 // kGroups = kThreads/LANES lane groups each own R rows (rows base + r*kGroups + g) and CH
 // 16-byte pieces per row (piece c of lane t = c*LANES + t).  All R rows of a group are fetched

@@ -24,8 +24,11 @@ constexpr int kMaxFastM = 4096;  // rows longer than this take the generic kerne
 
 // Forward.  A batch is kGroups*R consecutive rows; lane group g takes rows base + r*kGroups + g
 // and fetches all R of them (packed) before any arithmetic, so that short rows still keep
-// several 16-byte loads per lane in flight.
-template <typename T, int LANES, int CH, int R>
+// several 16-byte loads per lane in flight.  LOOP = false: one batch per workgroup (the grid
+// must cover every batch).  LOOP = true: workgroups walk the batches grid-stride, fetching the
+// next batch before they compute on the current one, and load gamma/beta once: for long rows
+// the parameters (8 bytes per column from L2) otherwise outweigh the row itself.
+template <typename T, int LANES, int CH, int R, bool LOOP>
 __global__ __launch_bounds__(kFwdThreads) void ln_fwd_kernel(
     const T* x, const float* __restrict__ gamma, const float* __restrict__ beta, T* y,
     float* __restrict__ rstd_out, float* __restrict__ mean_out, int64_t N, int M, float eps) {
@@ -35,11 +38,10 @@ __global__ __launch_bounds__(kFwdThreads) void ln_fwd_kernel(
   const int t = threadIdx.x % LANES;
   const int chunks = M / V;
   const float inv_m = 1.0f / static_cast<float>(M);
-  float ga[CH][V], be[CH][V];
-  bool have_params = false;
-  for (int64_t base = static_cast<int64_t>(blockIdx.x) * (kGroups * R); base < N;
-       base += static_cast<int64_t>(gridDim.x) * (kGroups * R)) {
-    Raw<T> raw[R][CH];
+  __shared__ float red[2][kFwdThreads / kWave];
+  static_assert(LANES <= kWave || R == 1, "rows over several waves: one row per group");
+
+  auto fetch = [&](int64_t base, Raw<T> (&f)[R][CH]) {
 #pragma unroll
     for (int r = 0; r < R; ++r) {
       const int64_t row = base + r * kGroups + g;
@@ -47,34 +49,48 @@ __global__ __launch_bounds__(kFwdThreads) void ln_fwd_kernel(
 #pragma unroll
         for (int c = 0; c < CH; ++c) {
           const int ch = c * LANES + t;
-          if (ch < chunks) raw[r][c].load(x + row * M + ch * V);
+          if (ch < chunks) f[r][c].load(x + row * M + ch * V);
         }
       }
     }
-    if (!have_params) {  // after the first rows are on their way
-      have_params = true;
+  };
+
+  int64_t base = static_cast<int64_t>(blockIdx.x) * (kGroups * R);
+  if (base >= N) return;  // uniform over the workgroup
+  Raw<T> raw[R][CH];
+  fetch(base, raw);
+  // parameters after the first rows are on their way; they stay in registers for every batch
+  float ga[CH][V], be[CH][V];
 #pragma unroll
-      for (int c = 0; c < CH; ++c) {
-        const int ch = c * LANES + t;
-        if (ch < chunks) {
-          load_floats<V>(gamma + ch * V, ga[c]);
-          load_floats<V>(beta + ch * V, be[c]);
-        } else {
+  for (int c = 0; c < CH; ++c) {
+    const int ch = c * LANES + t;
+    if (ch < chunks) {
+      load_floats<V>(gamma + ch * V, ga[c]);
+      load_floats<V>(beta + ch * V, be[c]);
+    } else {
 #pragma unroll
-          for (int i = 0; i < V; ++i) ga[c][i] = be[c][i] = 0.0f;
-        }
-      }
+      for (int i = 0; i < V; ++i) ga[c][i] = be[c][i] = 0.0f;
+    }
+  }
+  while (true) {
+    const int64_t next = base + static_cast<int64_t>(gridDim.x) * (kGroups * R);
+    Raw<T> ahead[R][CH];  // unused (and eliminated) without LOOP
+    if constexpr (LOOP) {
+      if (next < N) fetch(next, ahead);
     }
 #pragma unroll
     for (int r = 0; r < R; ++r) {
       const int64_t row = base + r * kGroups + g;
-      if (row >= N) continue;  // uniform over the lane group
+      // no row: uniform over the lane group; a group of several waves walks on with zeros
+      // (the reductions hold workgroup barriers) and stores nothing
+      const bool live = row < N;
+      if (LANES <= kWave && !live) continue;
       float v[CH][V];
       float sum = 0.0f;
 #pragma unroll
       for (int c = 0; c < CH; ++c) {
         const int ch = c * LANES + t;
-        if (ch < chunks) {
+        if (live && ch < chunks) {
           raw[r][c].unpack(v[c]);
         } else {
 #pragma unroll
@@ -83,7 +99,7 @@ __global__ __launch_bounds__(kFwdThreads) void ln_fwd_kernel(
 #pragma unroll
         for (int i = 0; i < V; ++i) sum += v[c][i];
       }
-      const float mu = group_sum<LANES>(sum) * inv_m;
+      const float mu = row_reduce<LANES, false>(sum, red[0]) * inv_m;
       float sq = 0.0f;
 #pragma unroll
       for (int c = 0; c < CH; ++c) {
@@ -95,22 +111,33 @@ __global__ __launch_bounds__(kFwdThreads) void ln_fwd_kernel(
           sq += (ch < chunks) ? d * d : 0.0f;
         }
       }
-      const float var = group_sum<LANES>(sq) * inv_m;
+      const float var = row_reduce<LANES, false>(sq, red[1]) * inv_m;
       const float rs = 1.0f / sqrtf(var + eps);
 #pragma unroll
       for (int c = 0; c < CH; ++c) {
         const int ch = c * LANES + t;
-        if (ch < chunks) {
+        if (live && ch < chunks) {
           float o[V];
 #pragma unroll
           for (int i = 0; i < V; ++i) o[i] = fmaf(v[c][i] * rs, ga[c][i], be[c][i]);
           store_piece<T>(y + row * M + ch * V, o);
         }
       }
-      if (t == 0) {
+      if (t == 0 && live) {
         rstd_out[row] = rs;
         if (mean_out) mean_out[row] = mu;
       }
+    }
+    if constexpr (!LOOP) {
+      break;
+    } else {
+      if (next >= N) break;  // uniform over the workgroup
+#pragma unroll
+      for (int r = 0; r < R; ++r) {
+#pragma unroll
+        for (int c = 0; c < CH; ++c) raw[r][c] = ahead[r][c];
+      }
+      base = next;
     }
   }
 }
@@ -177,6 +204,9 @@ __global__ __launch_bounds__(kBwdThreads) void ln_bwd_kernel(
   const int chunks = M / V;
   const float inv_m = 1.0f / static_cast<float>(M);
   const int64_t batch_rows = kGroups * R;
+  __shared__ float2 red[2][kBwdWaves];
+  static_assert(LANES <= kWave || R == 1, "rows over several waves: one row per group");
+  int flip = 0;
   // gamma, 1/gamma and beta/gamma live in LDS (the first 3*M floats; the same memory is
   // reused by the reduction tree at the end), the column sums in registers
   float* p_ga = lds;
@@ -260,8 +290,10 @@ __global__ __launch_bounds__(kBwdThreads) void ln_bwd_kernel(
     }
 #pragma unroll
     for (int r = 0; r < R; ++r) {
-      c1[r] = group_sum<LANES>(c1[r]) * inv_m;
-      c2[r] = group_sum<LANES>(c2[r]) * inv_m;
+      row_sum2<LANES>(c1[r], c2[r], red[flip]);
+      flip ^= 1;
+      c1[r] *= inv_m;
+      c2[r] *= inv_m;
     }
     // pass 2: dx, recomputing xhat and dy*gamma from the packed registers
 #pragma unroll
@@ -303,7 +335,8 @@ __global__ __launch_bounds__(kBwdThreads) void ln_bwd_kernel(
     }
   }
   // Column sums: first over the groups that share a wave (fixed butterfly), then a binary tree
-  // over the waves through LDS.
+  // over the waves through LDS.  When a row takes W > 1 waves, wave w holds the columns of
+  // part w % W of the row: the tree only pairs waves W apart or more and stops at W waves.
 #pragma unroll
   for (int c = 0; c < CH; ++c) {
 #pragma unroll
@@ -316,8 +349,9 @@ __global__ __launch_bounds__(kBwdThreads) void ln_bwd_kernel(
     }
   }
   const bool owner = lane < LANES;  // one copy per wave
+  constexpr int kRowWaves = LANES > kWave ? LANES / kWave : 1;
 #pragma unroll
-  for (int half = kBwdWaves / 2; half >= 1; half >>= 1) {
+  for (int half = kBwdWaves / 2; half >= kRowWaves; half >>= 1) {
     __syncthreads();
     if (wave >= half && wave < 2 * half && owner) {
       float* slot = lds + static_cast<size_t>(wave - half) * 2 * M;
@@ -349,7 +383,7 @@ __global__ __launch_bounds__(kBwdThreads) void ln_bwd_kernel(
       }
     }
   }
-  if (wave == 0 && owner) {
+  if (wave < kRowWaves && owner) {
     float* slot = partial + static_cast<size_t>(blockIdx.x) * 2 * M;
 #pragma unroll
     for (int c = 0; c < CH; ++c) {
@@ -470,6 +504,21 @@ Shape pick_shape(int pieces) {
   return best;
 }
 
+// A row whose pieces per lane on one wave would exceed max_ch is spread over 2 or 4 waves (at
+// most 4 pieces per lane there).
+Shape widen_shape(Shape one, int pieces, int max_ch, int max_lanes) {
+  if (one.lanes == kWave && (one.ch == 0 || one.ch > max_ch)) {
+    for (int lanes = 2 * kWave; lanes <= max_lanes; lanes *= 2) {
+      const int need = (pieces + lanes - 1) / lanes;
+      if (need <= max_ch || lanes == max_lanes) {
+        if (need <= 4) return {lanes, need};
+        break;
+      }
+    }
+  }
+  return one;
+}
+
 }  // namespace
 
 #define TEMPO_LN_DISPATCH(LAUNCH)                                                          \
@@ -488,6 +537,14 @@ Shape pick_shape(int pieces) {
     case 1601: LAUNCH(16, 1); break;                                                       \
     case 1602: LAUNCH(16, 2); break;                                                       \
     case 1603: LAUNCH(16, 3); break;                                                       \
+    case 12801: LAUNCH(128, 1); break;                                                     \
+    case 12802: LAUNCH(128, 2); break;                                                     \
+    case 12803: LAUNCH(128, 3); break;                                                     \
+    case 12804: LAUNCH(128, 4); break;                                                     \
+    case 25601: LAUNCH(256, 1); break;                                                     \
+    case 25602: LAUNCH(256, 2); break;                                                     \
+    case 25603: LAUNCH(256, 3); break;                                                     \
+    case 25604: LAUNCH(256, 4); break;                                                     \
     default: return TEMPO_ERR_UNSUPPORTED;                                                 \
   }
 
@@ -495,28 +552,35 @@ Shape pick_shape(int pieces) {
 // down): 4 only for one or two pieces per lane on full-wave groups, 2 up to four pieces.
 template <int L, int C>
 constexpr int max_rows() {
-  return (C <= 2 && L == 64) ? 4 : (C <= 4 ? 2 : 1);
+  return L > 64 ? 1 : ((C <= 2 && L == 64) ? 4 : (C <= 4 ? 2 : 1));
 }
 
 template <typename T, int L, int C>
-static void ln_fwd_go(int rr, int grid, hipStream_t st, const void* x, const float* gamma,
+static void ln_fwd_go(int rr, bool loop, int grid, hipStream_t st, const void* x, const float* gamma,
                       const float* beta, void* y, float* rstd, float* mean, int64_t N, int64_t M,
                       float eps) {
-  auto go = [&](auto rows) {
-    hipLaunchKernelGGL((ln_fwd_kernel<T, L, C, decltype(rows)::value>), dim3(grid),
-                       dim3(kFwdThreads), 0, st, static_cast<const T*>(x), gamma, beta,
+  auto go = [&](auto rows, auto lp) {
+    hipLaunchKernelGGL((ln_fwd_kernel<T, L, C, decltype(rows)::value, decltype(lp)::value>),
+                       dim3(grid), dim3(kFwdThreads), 0, st, static_cast<const T*>(x), gamma, beta,
                        static_cast<T*>(y), rstd, mean, N, static_cast<int>(M), eps);
   };
-  if constexpr (C <= 2) {
-    if (rr == 2) return go(std::integral_constant<int, 2>{});
+  using std::integral_constant;
+  if constexpr (C <= 2 && L <= 64) {
+    if (rr == 2) {
+      if (loop) return go(integral_constant<int, 2>{}, std::true_type{});
+      return go(integral_constant<int, 2>{}, std::false_type{});
+    }
   }
-  go(std::integral_constant<int, 1>{});
+  if (loop) return go(integral_constant<int, 1>{}, std::true_type{});
+  go(integral_constant<int, 1>{}, std::false_type{});
 }
 
-static bool fast_shape(int64_t M, tempo_dtype dt, Shape* sh) {
+static bool fast_shape(int64_t M, tempo_dtype dt, bool backward, Shape* sh) {
   const int vec = dt == TEMPO_F32 ? 4 : 8;
   if (M % vec != 0 || M > kMaxFastM) return false;
-  *sh = pick_shape(static_cast<int>(M / vec));
+  const int pieces = static_cast<int>(M / vec);
+  *sh = widen_shape(pick_shape(pieces), pieces,
+                    tune_get(backward ? kTuneLnBwdMaxPieces : kTuneLnFwdMaxPieces), 256);
   return sh->ch != 0;
 }
 
@@ -525,17 +589,18 @@ tempo_status launch_layernorm_fwd(const void* x, const float* gamma, const float
                                   tempo_dtype dt, hipStream_t st) {
   Shape sh;
   const int64_t cap = static_cast<int64_t>(compute_units()) * tune_get(kTuneLnFwdBlocksPerCu);
-  if (fast_shape(M, dt, &sh)) {
+  if (fast_shape(M, dt, false, &sh)) {
     // rows per lane group: up to the knob, at most 4 pieces per lane in flight
     const int tuned = tune_get(kTuneLnFwdRows);
-    const int rr = (sh.ch <= 2 && tuned >= 2) ? 2 : 1;
+    const int rr = (sh.ch <= 2 && sh.lanes <= kWave && tuned >= 2) ? 2 : 1;
     const int groups = (kFwdThreads / sh.lanes) * rr;
     const int64_t want = (N + groups - 1) / groups;
-    const int grid = static_cast<int>(want < cap ? want : cap);
+    const bool loop = want > cap;
+    const int grid = static_cast<int>(loop ? cap : want);
 #define TEMPO_LAUNCH(L, C)                                                                   \
   do {                                                                                       \
-    if (dt == TEMPO_F32) ln_fwd_go<float, L, C>(rr, grid, st, x, gamma, beta, y, rstd, mean, N, M, eps);   \
-    else ln_fwd_go<bf16_t, L, C>(rr, grid, st, x, gamma, beta, y, rstd, mean, N, M, eps);    \
+    if (dt == TEMPO_F32) ln_fwd_go<float, L, C>(rr, loop, grid, st, x, gamma, beta, y, rstd, mean, N, M, eps);   \
+    else ln_fwd_go<bf16_t, L, C>(rr, loop, grid, st, x, gamma, beta, y, rstd, mean, N, M, eps);    \
   } while (0)
     TEMPO_LN_DISPATCH(TEMPO_LAUNCH)
 #undef TEMPO_LAUNCH
@@ -571,7 +636,8 @@ static BwdPlan bwd_plan(int64_t N, const Shape& sh, tempo_dtype dt) {
   const int cus = compute_units();
   auto batches = [&](int r) { return (N + groups * r - 1) / (groups * r); };
   int r = tuned >= 4 ? 4 : (tuned >= 2 ? 2 : 1);
-  const int avail = (sh.ch <= 2 && sh.lanes == 64) ? 4 : (sh.ch <= 4 ? 2 : 1);  // max_rows<L, C>()
+  const int avail =  // max_rows<L, C>()
+      sh.lanes > 64 ? 1 : ((sh.ch <= 2 && sh.lanes == 64) ? 4 : (sh.ch <= 4 ? 2 : 1));
   if (r > avail) r = avail;
   while (r > 1 && (r * regs_per_row > 64 || batches(r) < cus)) r >>= 1;
   BwdPlan p = {r, false, static_cast<int>(batches(r) > 4096 ? 4096 : batches(r))};
@@ -641,7 +707,7 @@ static int ln_bwd_go(const BwdPlan& plan, size_t lds_bytes, hipStream_t st, cons
 
 int layernorm_bwd_blocks(int64_t N, int64_t M, tempo_dtype dt) {
   Shape sh;
-  if (fast_shape(M, dt, &sh)) return bwd_plan(N, sh, dt).grid;
+  if (fast_shape(M, dt, true, &sh)) return bwd_plan(N, sh, dt).grid;
   return static_cast<int>(N > 4096 ? 4096 : (N < 1 ? 1 : N));  // one row per workgroup, strided
 }
 
@@ -651,7 +717,7 @@ tempo_status launch_layernorm_bwd(const void* dy, const void* y, const float* ga
                                   tempo_dtype dt, hipStream_t st) {
   Shape sh;
   int grid = layernorm_bwd_blocks(N, M, dt);  // upper bound: the workspace has this many slots
-  if (fast_shape(M, dt, &sh)) {
+  if (fast_shape(M, dt, true, &sh)) {
     const size_t lds_bytes = static_cast<size_t>(kBwdWaves / 2) * 2 * M * sizeof(float);
     const BwdPlan plan = bwd_plan(N, sh, dt);
 #define TEMPO_LAUNCH(L, C)                                                                   \

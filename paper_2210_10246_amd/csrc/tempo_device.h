@@ -193,6 +193,53 @@ __device__ __forceinline__ float group_max(float v) {
   return v;
 }
 
+// Row reductions for rows owned by LANES consecutive threads of a workgroup.  A row inside
+// one wave: butterflies.  A row spread over LANES/64 waves: butterfly per wave, then one
+// exchange through `slots` (one entry per wave of the workgroup) behind a workgroup barrier, so
+// every thread of the workgroup has to make the call; consecutive calls must alternate between
+// two slot arrays (a fast wave may already write its next value while a slow one still reads).
+// Every lane of the row ends with the same result.
+template <int LANES, bool MAX>
+__device__ __forceinline__ float row_reduce(float v, float* slots) {
+  if constexpr (LANES <= kWave) {
+    return MAX ? group_max<LANES>(v) : group_sum<LANES>(v);
+  } else {
+    v = MAX ? group_max<kWave>(v) : group_sum<kWave>(v);
+    if ((threadIdx.x & (kWave - 1)) == 0) slots[threadIdx.x / kWave] = v;
+    __syncthreads();
+    constexpr int W = LANES / kWave;
+    const int w0 = (threadIdx.x / LANES) * W;
+    float r = slots[w0];
+#pragma unroll
+    for (int k = 1; k < W; ++k) r = MAX ? fmaxf(r, slots[w0 + k]) : r + slots[w0 + k];
+    return r;
+  }
+}
+
+// Two sums at once (one barrier for both); slots holds two floats per wave of the workgroup.
+template <int LANES>
+__device__ __forceinline__ void row_sum2(float& a, float& b, float2* slots) {
+  if constexpr (LANES <= kWave) {
+    a = group_sum<LANES>(a);
+    b = group_sum<LANES>(b);
+  } else {
+    a = group_sum<kWave>(a);
+    b = group_sum<kWave>(b);
+    if ((threadIdx.x & (kWave - 1)) == 0) slots[threadIdx.x / kWave] = make_float2(a, b);
+    __syncthreads();
+    constexpr int W = LANES / kWave;
+    const int w0 = (threadIdx.x / LANES) * W;
+    float2 r = slots[w0];
+#pragma unroll
+    for (int k = 1; k < W; ++k) {
+      r.x += slots[w0 + k].x;
+      r.y += slots[w0 + k].y;
+    }
+    a = r.x;
+    b = r.y;
+  }
+}
+
 // Merge the per-piece mask bits of the lanes that share a 32-bit mask word: 4 lanes with 8 bits
 // each (bfloat16 pieces) or 8 lanes with 4 bits each (float32 pieces).  `lane` is the index of
 // the lane's piece within its row/tile (only its low bits matter).  Every lane of the sharing

@@ -20,7 +20,9 @@ enum TuneKey {
   kTuneLnFwdRows = 7,           // rows a lane group of layernorm_fwd fetches at once (1 or 2)
   kTuneAttnFwdMaxPieces = 8,    // attn fwd: pieces per lane above which a row takes 2-4 waves
   kTuneAttnBwdMaxPieces = 9,    // the same for attn bwd
-  kTuneCount = 10
+  kTuneLnFwdMaxPieces = 10,     // the same for layernorm_fwd
+  kTuneLnBwdMaxPieces = 11,     // and layernorm_bwd
+  kTuneCount = 12
 };
 int tune_get(TuneKey k);
 int compute_units();

@@ -200,6 +200,78 @@ def test_layernorm_bwd(B, shape, dt):
         B.tempo_layernorm_bwd(dyd, yd, gd, bd, rd, dxd, dgd, dbd, ws[:16])
 
 
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+@pytest.mark.parametrize("shape", [(37, 2048), (5, 3072), (9, 4096), (3, 1032), (600, 1536)])
+def test_layernorm_row_over_one_or_several_waves(B, shape, dt):
+    """Long rows: the same results whether one wave or 2-4 waves own a row (knobs 10, 11),
+    with row counts that leave lane groups without a row in the last batch."""
+    N, M = shape
+    eps = 1e-5
+    rng = np.random.default_rng(N * 31 + M)
+    x = stored(rng, shape, dt)
+    gamma = O.round_to_dtype(1 + 0.1 * rng.standard_normal(M), "f32")
+    beta = O.round_to_dtype(0.1 * rng.standard_normal(M), "f32")
+    dy = stored(rng, shape, dt)
+    y, rstd, mean = O.layernorm_fwd(x, gamma, beta, eps, dt)
+    dx_ref, dg_ref, db_ref = O.layernorm_bwd(dy, y, gamma, beta, rstd, dt)
+    xd, dyd, yd0 = dev(x, dt), dev(dy, dt), dev(y, dt)
+    gd, bd, rd0 = dev(gamma, "f32"), dev(beta, "f32"), dev(rstd, "f32")
+    old = B.tempo_get_launch_param(10), B.tempo_get_launch_param(11)
+    try:
+        for max_pieces in (1, 2, 4, 16):
+            B.tempo_set_launch_param(10, max_pieces)
+            B.tempo_set_launch_param(11, max_pieces)
+            yd = torch.full_like(xd, 3.0)
+            rd = torch.full((N,), 3.0, dtype=torch.float32, device="cuda")
+            md = torch.full((N,), 3.0, dtype=torch.float32, device="cuda")
+            B.tempo_layernorm_fwd(xd, gd, bd, yd, rd, md, eps)
+            torch.cuda.synchronize()
+            assert rel_err(host(yd), y) <= TOL[dt], max_pieces
+            assert rel_err(host(rd), rstd) <= TOL["f32"], max_pieces
+            assert rel_err(host(md), mean) <= TOL["f32"], max_pieces
+            dxd = torch.full_like(dyd, 3.0)
+            dgd = torch.full((M,), 3.0, dtype=torch.float32, device="cuda")
+            dbd = torch.full((M,), 3.0, dtype=torch.float32, device="cuda")
+            ws = torch.empty(B.tempo_layernorm_bwd_workspace_bytes(N, M), dtype=torch.uint8, device="cuda")
+            B.tempo_layernorm_bwd(dyd, yd0, gd, bd, rd0, dxd, dgd, dbd, ws)
+            torch.cuda.synchronize()
+            assert rel_err(host(dxd), dx_ref) <= TOL[dt], max_pieces
+            assert rel_err(host(dgd), dg_ref) <= 2 * TOL["f32"], max_pieces
+            assert rel_err(host(dbd), db_ref) <= 2 * TOL["f32"], max_pieces
+    finally:
+        B.tempo_set_launch_param(10, old[0])
+        B.tempo_set_launch_param(11, old[1])
+
+
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+@pytest.mark.parametrize("shape", [(3001, 768), (2100, 2048), (1101, 4096), (4099, 256)])
+def test_layernorm_fwd_looping_workgroups(B, shape, dt):
+    """More row batches than workgroups: workgroups walk the batches, prefetching the next."""
+    N, M = shape
+    rng = np.random.default_rng(N + M)
+    x = stored(rng, shape, dt)
+    gamma = O.round_to_dtype(1 + 0.1 * rng.standard_normal(M), "f32")
+    beta = O.round_to_dtype(0.1 * rng.standard_normal(M), "f32")
+    y, rstd, mean = O.layernorm_fwd(x, gamma, beta, 1e-5, dt)
+    xd, gd, bd = dev(x, dt), dev(gamma, "f32"), dev(beta, "f32")
+    old = B.tempo_get_launch_param(2), B.tempo_get_launch_param(10)
+    try:
+        for cap, max_pieces in ((1, 16), (1, 2), (65536, 16)):
+            B.tempo_set_launch_param(2, cap)
+            B.tempo_set_launch_param(10, max_pieces)
+            yd = torch.full_like(xd, 3.0)
+            rd = torch.full((N,), 3.0, dtype=torch.float32, device="cuda")
+            md = torch.full((N,), 3.0, dtype=torch.float32, device="cuda")
+            B.tempo_layernorm_fwd(xd, gd, bd, yd, rd, md, 1e-5)
+            torch.cuda.synchronize()
+            assert rel_err(host(yd), y) <= TOL[dt], (cap, max_pieces)
+            assert rel_err(host(rd), rstd) <= TOL["f32"], (cap, max_pieces)
+            assert rel_err(host(md), mean) <= TOL["f32"], (cap, max_pieces)
+    finally:
+        B.tempo_set_launch_param(2, old[0])
+        B.tempo_set_launch_param(10, old[1])
+
+
 # ------------------------------------------------------------------ attention softmax -> dropout
 ATTN_CASES = [
     # B, A, Sq, Sk, mask, p
