@@ -197,16 +197,27 @@ def main():
             step(i % PHASES)
         torch.cuda.synchronize()
         if use_graph:
+            # one graph per step, and one holding PHASES consecutive steps: the timed loop
+            # replays the long one steps // PHASES times and single steps for the remainder
             graphs = [capture(lambda ph=ph: step(ph)) for ph in range(PHASES)]
-            for gph in graphs:
+            def all_phases():
+                for ph in range(PHASES):
+                    step(ph)
+            cycle = capture(all_phases)
+            for gph in graphs + [cycle]:
                 gph.replay()
-            run = lambda i: graphs[i % PHASES].replay()
+            def run_steps(k):
+                for _ in range(k // PHASES):
+                    cycle.replay()
+                for i in range(k % PHASES):
+                    graphs[i].replay()
         else:
-            run = lambda i: step(i % PHASES)
+            def run_steps(k):
+                for i in range(k):
+                    step(i % PHASES)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        for i in range(args.steps):
-            run(i)
+        run_steps(args.steps)
         torch.cuda.synchronize()
         ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
 

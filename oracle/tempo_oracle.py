@@ -12,6 +12,9 @@ What is pinned and by what (tests/test_oracle_*.py):
                       minimum location printed in Sec. 3.1 (x ~ -0.75179)
   gelu_bwd            autograd of PyTorch's float64 GELU on the unrounded output;
                       central finite differences; closed-form extremes of GELU'
+  kind "silu"         (the same recipe on another single-minimum activation, Sec. 5.1)
+                      PyTorch float64 silu + autograd; the minimum in closed form through
+                      the Lambert W function: x* = -(1 + W(1/e)), y* = -W(1/e)
   layernorm_fwd/bwd   PyTorch float64 layer_norm + autograd; the output-based gradient of
                       App. D.3 against the input-based twin; finite differences;
                       row invariants (sum dx = 0, sum dx*xhat = 0)
@@ -40,6 +43,8 @@ _INV_SQRT_2PI = 1.0 / math.sqrt(2.0 * math.pi)
 _TANH_CUBIC = 0.044715
 
 GELU_KINDS = ("erf", "tanh")
+#: every activation the in-place recipe is applied to: the two GELU forms and SiLU
+ACT_KINDS = GELU_KINDS + ("silu",)
 DTYPES = ("f32", "bf16")
 
 
@@ -77,10 +82,14 @@ def round_to_dtype(a, dt: str) -> np.ndarray:
 # --------------------------------------------------------------------------------------
 def gelu_value(x, kind: str) -> np.ndarray:
     """GELU(x).  erf kind: x * Phi(x).  tanh kind: x * sigmoid(2u), which equals
-    0.5 x (1 + tanh u) with u = sqrt(2/pi) (x + 0.044715 x^3)."""
+    0.5 x (1 + tanh u) with u = sqrt(2/pi) (x + 0.044715 x^3).
+    silu kind (Sec. 5.1 applied to SiLU): x * sigmoid(x)."""
     x = np.asarray(x, dtype=np.float64)
     if kind == "erf":
         return x * (0.5 * erfc(-x / _SQRT2))
+    if kind == "silu":
+        with np.errstate(over="ignore"):
+            return x / (1.0 + np.exp(-x))
     if kind == "tanh":
         u = _SQRT_2_OVER_PI * (x + _TANH_CUBIC * x**3)
         with np.errstate(over="ignore"):
@@ -89,10 +98,16 @@ def gelu_value(x, kind: str) -> np.ndarray:
 
 
 def gelu_derivative(x, kind: str) -> np.ndarray:
-    """GELU'(x) in terms of the INPUT.  erf: Phi(x) + x phi(x)."""
+    """GELU'(x) in terms of the INPUT.  erf: Phi(x) + x phi(x).
+    silu: sigma(x) (1 + x (1 - sigma(x))), with 1 - sigma(x) taken as sigma(-x)."""
     x = np.asarray(x, dtype=np.float64)
     if kind == "erf":
         return 0.5 * erfc(-x / _SQRT2) + x * np.exp(-0.5 * x * x) * _INV_SQRT_2PI
+    if kind == "silu":
+        with np.errstate(over="ignore"):
+            sg = 1.0 / (1.0 + np.exp(-x))
+            sn = 1.0 / (1.0 + np.exp(x))
+        return sg * (1.0 + x * sn)
     if kind == "tanh":
         u = _SQRT_2_OVER_PI * (x + _TANH_CUBIC * x**3)
         du = _SQRT_2_OVER_PI * (1.0 + 3.0 * _TANH_CUBIC * x * x)
@@ -103,8 +118,10 @@ def gelu_derivative(x, kind: str) -> np.ndarray:
 
 
 def _solve_minimum(kind: str) -> float:
-    """Location of GELU's single minimum: the root of GELU' in [-1, -0.5] (bisection)."""
-    lo, hi = -1.0, -0.5  # GELU'(-1) < 0 < GELU'(-0.5) for both kinds
+    """Location of the activation's single minimum: the root of its derivative in
+    [-1, -0.5] (GELU) or [-2, -1] (SiLU), by bisection."""
+    # GELU'(-1) < 0 < GELU'(-0.5) for both GELU kinds; SiLU'(-2) < 0 < SiLU'(-1)
+    lo, hi = (-2.0, -1.0) if kind == "silu" else (-1.0, -0.5)
     for _ in range(200):
         mid = 0.5 * (lo + hi)
         if float(gelu_derivative(np.float64(mid), kind)) < 0.0:
@@ -115,11 +132,11 @@ def _solve_minimum(kind: str) -> float:
 
 
 #: x* (float64) where GELU has its minimum, per kind (Sec. 3.1 prints -0.75179 for erf)
-GELU_XSTAR = {k: _solve_minimum(k) for k in GELU_KINDS}
+GELU_XSTAR = {k: _solve_minimum(k) for k in ACT_KINDS}
 #: y* = GELU(x*)
-GELU_YSTAR = {k: float(gelu_value(np.float64(GELU_XSTAR[k]), k)) for k in GELU_KINDS}
+GELU_YSTAR = {k: float(gelu_value(np.float64(GELU_XSTAR[k]), k)) for k in ACT_KINDS}
 #: the branch point as compared by the forward pass: x* rounded to binary32
-GELU_XSTAR_F32 = {k: float(np.float32(GELU_XSTAR[k])) for k in GELU_KINDS}
+GELU_XSTAR_F32 = {k: float(np.float32(GELU_XSTAR[k])) for k in ACT_KINDS}
 
 
 def gelu_fwd(x, kind: str, dt: str):
@@ -145,8 +162,10 @@ def gelu_inverse(y, m, kind: str) -> np.ndarray:
     m = np.asarray(m, dtype=bool)
     xs = GELU_XSTAR[kind]
     # right branch: x - GELU(x) = x Phi(-x) <= |y*| < 1 for x > 0, and x in [x*, 0] for y < 0
+    # (SiLU: x - SiLU(x) = x sigma(-x) <= |y*| < 1 likewise).  Left branch: GELU(-64) and
+    # SiLU(-128) lie below the smallest binary32 magnitude.
     finite_y = np.where(np.isfinite(y), y, 0.0)
-    lo = np.where(m, xs, -64.0)
+    lo = np.where(m, xs, -128.0 if kind == "silu" else -64.0)
     hi = np.where(m, np.maximum(finite_y, 0.0) + 1.0, xs)
     for _ in range(200):
         mid = 0.5 * (lo + hi)

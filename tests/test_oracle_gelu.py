@@ -1,4 +1,5 @@
-"""Pins for the oracle's In-place GELU (Sec. 3.1; App. E.1 eq. 1-2; App. F.1)."""
+"""Pins for the oracle's In-place GELU (Sec. 3.1; App. E.1 eq. 1-2; App. F.1) and for the same
+recipe applied to SiLU (Sec. 5.1)."""
 import json
 import os
 
@@ -9,11 +10,26 @@ import torch
 from oracle import tempo_oracle as O
 
 GOLD = json.load(open(os.path.join(os.path.dirname(__file__), "golden", "paper_values.json")))
-KINDS = ["erf", "tanh"]
+KINDS = ["erf", "tanh", "silu"]
 
 
 def _torch_gelu(x, kind):
+    if kind == "silu":
+        return torch.nn.functional.silu(x)
     return torch.nn.functional.gelu(x, approximate="none" if kind == "erf" else "tanh")
+
+
+def test_silu_minimum_in_closed_form():
+    # SiLU'(x) = sigma(x) (1 + x sigma(-x)) = 0  <=>  x = -(1 + W(1/e)), and then y = -W(1/e)
+    from scipy.special import lambertw
+    w = float(lambertw(1.0 / np.e).real)
+    assert O.GELU_XSTAR["silu"] == pytest.approx(-(1.0 + w), abs=1e-14)
+    assert O.GELU_YSTAR["silu"] == pytest.approx(-w, abs=1e-15)
+    # extremes of SiLU': SiLU'' = sigma(x) sigma(-x) (2 + x (1 - 2 sigma(x))) vanishes at +-2.3994
+    x = np.linspace(-20, 20, 400001)
+    d = O.gelu_derivative(x, "silu")
+    assert d.max() == pytest.approx(1.0998393, abs=1e-6) and d.min() == pytest.approx(-0.0998393, abs=1e-6)
+    assert abs(x[np.argmax(d)] - 2.3994) < 1e-3 and abs(x[np.argmin(d)] + 2.3994) < 1e-3
 
 
 def test_minimum_location_matches_paper():
