@@ -59,6 +59,9 @@ def algorithmic_bytes(cfg):
         "attn_bwd": n_a * 4 * e + n_a / 8,
         # variant outside the step: backward that draws the keep bits again, no mask read
         "attn_bwd_regen": n_a * 4 * e,
+        # the activation kernels on SiLU tables (same traffic as GELU)
+        "silu_fwd": n_g * 2 * e + n_g / 8,
+        "silu_bwd": n_g * 3 * e + n_g / 8,
     }
 
 
@@ -161,7 +164,12 @@ def main():
         "layernorm_fwd": (k_ln_fwd, ln_b), "layernorm_bwd": (k_ln_bwd, ln_b),
         "attn_fwd": (k_attn_fwd, attn_b), "attn_bwd": (k_attn_bwd, attn_b),
     }
-    variants = {"attn_bwd_regen": (k_attn_bwd_regen, attn_b)}   # timed, not part of the step
+    def k_silu_fwd(s): B.tempo_silu_fwd(s["x"], s["y"], s["m"])
+    def k_silu_bwd(s): B.tempo_silu_bwd(s["dy"], s["y"], s["m"], s["dx"])
+
+    # timed, not part of the step
+    variants = {"attn_bwd_regen": (k_attn_bwd_regen, attn_b),
+                "silu_fwd": (k_silu_fwd, gelu_b), "silu_bwd": (k_silu_bwd, gelu_b)}
 
     # every set gets a valid forward state once (backward kernels read y / P / masks)
     for s in gelu_b.sets: k_gelu_fwd(s)

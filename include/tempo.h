@@ -101,6 +101,20 @@ TEMPO_API tempo_status tempo_gelu_bwd(const void* dy, const void* y, const uint3
                             int64_t n, tempo_dtype dt, tempo_gelu_kind kind, void* hip_stream);
 
 /*
+ * In-place SiLU: the in-place recipe for elementwise layers on another activation with a
+ * single minimum                                            [Sec. 5.1 (extending In-place GELU)]
+ *   SiLU(x) = x sigmoid(x) has its only minimum at x* = -(1 + W(1/e)) = -1.27846...,
+ *   y* = -0.27846...; on each side of x* it is one-to-one, so the steps of Sec. 5.1 apply as
+ *   for GELU: forward folds the side indicator m = [x >= x*] (x* rounded to float32) into the
+ *   kernel, backward evaluates dx = dy SiLU'(SiLU*^-1(y, m)) from the stored output.
+ *   Arguments, layouts, aliasing and edge-case readings as tempo_gelu_fwd / tempo_gelu_bwd.
+ */
+TEMPO_API tempo_status tempo_silu_fwd(const void* x, void* y, uint32_t* mask, int64_t n,
+                            tempo_dtype dt, void* hip_stream);
+TEMPO_API tempo_status tempo_silu_bwd(const void* dy, const void* y, const uint32_t* mask, void* dx,
+                            int64_t n, tempo_dtype dt, void* hip_stream);
+
+/*
  * In-place LayerNorm forward                                              [App. D.2; Sec. 3.2]
  *   mu_i = mean_j x_ij, sigma_i^2 = mean_j (x_ij - mu_i)^2 (biased),
  *   rstd_i = 1/sqrt(sigma_i^2 + eps), y_ij = gamma_j (x_ij - mu_i) rstd_i + beta_j.

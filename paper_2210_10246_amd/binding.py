@@ -32,6 +32,8 @@ _SIGNATURES = {
     "tempo_copy": (_int, [_vp, _vp, _i64, _int, _vp]),
     "tempo_gelu_fwd": (_int, [_vp, _vp, _vp, _i64, _int, _int, _vp]),
     "tempo_gelu_bwd": (_int, [_vp, _vp, _vp, _vp, _i64, _int, _int, _vp]),
+    "tempo_silu_fwd": (_int, [_vp, _vp, _vp, _i64, _int, _vp]),
+    "tempo_silu_bwd": (_int, [_vp, _vp, _vp, _vp, _i64, _int, _vp]),
     "tempo_layernorm_fwd": (_int, [_vp, _vp, _vp, _vp, _vp, _vp, _i64, _i64, _f32, _int, _vp]),
     "tempo_layernorm_bwd_workspace_bytes": (_sz, [_i64, _i64]),
     "tempo_layernorm_bwd": (_int, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _i64, _i64,
@@ -123,6 +125,18 @@ def tempo_gelu_bwd(dy, y, mask, dx, kind="erf", stream=None):
     """dx = dy * GELU'(GELU*^-1(y, mask)); dx may be dy."""
     _check(load().tempo_gelu_bwd(_ptr(dy), _ptr(y), _ptr(mask), _ptr(dx), y.numel(), _DT[y.dtype],
                                  _KIND[kind], _stream(stream)), "tempo_gelu_bwd")
+
+
+def tempo_silu_fwd(x, y, mask, stream=None):
+    """(y, mask) = SiLU*(x); y may be x."""
+    _check(load().tempo_silu_fwd(_ptr(x), _ptr(y), _ptr(mask), x.numel(), _DT[x.dtype],
+                                 _stream(stream)), "tempo_silu_fwd")
+
+
+def tempo_silu_bwd(dy, y, mask, dx, stream=None):
+    """dx = dy * SiLU'(SiLU*^-1(y, mask)); dx may be dy."""
+    _check(load().tempo_silu_bwd(_ptr(dy), _ptr(y), _ptr(mask), _ptr(dx), y.numel(), _DT[y.dtype],
+                                 _stream(stream)), "tempo_silu_bwd")
 
 
 def tempo_layernorm_fwd(x, gamma, beta, y, rstd, mean=None, eps=1e-5, stream=None):

@@ -117,6 +117,25 @@ tempo_status tempo_gelu_bwd(const void* dy, const void* y, const uint32_t* mask,
   return launch_gelu_bwd(dy, y, mask, dx, n, dt, kind, static_cast<hipStream_t>(hip_stream));
 }
 
+tempo_status tempo_silu_fwd(const void* x, void* y, uint32_t* mask, int64_t n, tempo_dtype dt,
+                            void* hip_stream) {
+  if (n < 0 || !dtype_ok(dt)) return TEMPO_ERR_INVALID_ARG;
+  if (n == 0) return TEMPO_OK;
+  if (!x || !y || !mask) return TEMPO_ERR_INVALID_ARG;
+  if (!aligned16(x) || !aligned16(y) || !aligned16(mask)) return TEMPO_ERR_UNSUPPORTED;
+  return launch_gelu_fwd(x, y, mask, n, dt, kActSilu, static_cast<hipStream_t>(hip_stream));
+}
+
+tempo_status tempo_silu_bwd(const void* dy, const void* y, const uint32_t* mask, void* dx,
+                            int64_t n, tempo_dtype dt, void* hip_stream) {
+  if (n < 0 || !dtype_ok(dt)) return TEMPO_ERR_INVALID_ARG;
+  if (n == 0) return TEMPO_OK;
+  if (!dy || !y || !mask || !dx) return TEMPO_ERR_INVALID_ARG;
+  if (!aligned16(dy) || !aligned16(y) || !aligned16(mask) || !aligned16(dx))
+    return TEMPO_ERR_UNSUPPORTED;
+  return launch_gelu_bwd(dy, y, mask, dx, n, dt, kActSilu, static_cast<hipStream_t>(hip_stream));
+}
+
 tempo_status tempo_layernorm_fwd(const void* x, const float* gamma, const float* beta, void* y,
                                  float* rstd, float* mean, int64_t N, int64_t M, float eps,
                                  tempo_dtype dt, void* hip_stream) {

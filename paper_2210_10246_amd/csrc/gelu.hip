@@ -1,11 +1,16 @@
 // In-place GELU for gfx950: forward writes y and a 1-bit "side of the minimum" mask, backward
 // evaluates GELU'(GELU*^-1(y, m)) from the stored output (Sec. 3.1; App. E.1 eq. 1-2; App. F.1).
+// The same kernels serve SiLU, x * sigmoid(x), which also has a single minimum: the general
+// recipe for in-place elementwise layers (Sec. 5.1) with another table set.  KIND is
+// TEMPO_GELU_ERF, TEMPO_GELU_TANH or kActSilu.
 //
 // Both kernels are streaming: every lane owns 16-byte pieces (8 bf16 or 4 f32 elements); the
 // mask bits of a piece are merged over the 4 (bf16) or 8 (f32) adjacent lanes that share a
 // word, so the mask is written and read as whole 32-bit words.  float32 evaluates piecewise
 // cubics whose coefficient rows live in LDS (one ds_read_b128 per element); bfloat16 looks the
 // function value up per bit pattern.
+#include <type_traits>
+
 #include "tempo_device.h"
 #include "tempo_host.h"
 
@@ -19,20 +24,27 @@ constexpr int kThreads = 256;
 
 template <int KIND>
 struct GeluConst;
-template <>
-struct GeluConst<TEMPO_GELU_ERF> {
-  static constexpr uint32_t xstar = TEMPO_GELU_ERF_XSTAR_F32;
-  static constexpr uint32_t ys_hi = TEMPO_GELU_ERF_YSTAR_HI;
-  static constexpr uint32_t ys_lo = TEMPO_GELU_ERF_YSTAR_LO;
-  __device__ static const uint32_t (*bwd_table())[4] { return tempo_gelu_bwd_table_erf; }
-};
-template <>
-struct GeluConst<TEMPO_GELU_TANH> {
-  static constexpr uint32_t xstar = TEMPO_GELU_TANH_XSTAR_F32;
-  static constexpr uint32_t ys_hi = TEMPO_GELU_TANH_YSTAR_HI;
-  static constexpr uint32_t ys_lo = TEMPO_GELU_TANH_YSTAR_LO;
-  __device__ static const uint32_t (*bwd_table())[4] { return tempo_gelu_bwd_table_tanh; }
-};
+// Per activation: the minimum (x* as compared in float32, y* split hi + lo), the number of
+// right-branch and left-near pieces of the backward table, the rows of that table, and how many
+// bf16 patterns lower the left branch's lookup window starts.
+#define TEMPO_ACT_CONST(KIND, UPPER, lower)                                                  \
+  template <>                                                                                \
+  struct GeluConst<KIND> {                                                                   \
+    static constexpr uint32_t xstar = TEMPO_GELU_##UPPER##_XSTAR_F32;                        \
+    static constexpr uint32_t ys_hi = TEMPO_GELU_##UPPER##_YSTAR_HI;                         \
+    static constexpr uint32_t ys_lo = TEMPO_GELU_##UPPER##_YSTAR_LO;                         \
+    static constexpr int NR = TEMPO_GELU_##UPPER##_NR;                                       \
+    static constexpr int NL = TEMPO_GELU_##UPPER##_NL;                                       \
+    static constexpr int kBwdRows = TEMPO_GELU_##UPPER##_BWD_ROWS;                           \
+    static constexpr int kLutLeftShift = TEMPO_GELU_##UPPER##_LUT_LEFT_SHIFT;                \
+    __device__ static const uint32_t (*bwd_table())[4] { return tempo_gelu_bwd_table_##lower; } \
+    __device__ static const uint32_t* lut_fwd() { return tempo_gelu_lut_fwd_##lower; }       \
+    __device__ static const uint32_t* lut_bwd() { return tempo_gelu_lut_bwd_##lower; }       \
+  };
+TEMPO_ACT_CONST(TEMPO_GELU_ERF, ERF, erf)
+TEMPO_ACT_CONST(TEMPO_GELU_TANH, TANH, tanh)
+TEMPO_ACT_CONST(kActSilu, SILU, silu)
+#undef TEMPO_ACT_CONST
 
 __device__ __forceinline__ float cubic(const f32x4 c, float z) {
   return fmaf(fmaf(fmaf(c.w, z, c.z), z, c.y), z, c.x);
@@ -62,6 +74,19 @@ __device__ __forceinline__ float gelu_tanh_value(float x) {
   return x * __builtin_amdgcn_rcpf(1.0f + e);
 }
 
+// SiLU(x) = x * sigmoid(x); exp overflows to +inf on the far left, which gives -0.
+__device__ __forceinline__ float silu_value(float x) {
+  const float e = __builtin_amdgcn_exp2f(-1.4426950408889634f * x);  // exp(-x)
+  return x * __builtin_amdgcn_rcpf(1.0f + e);
+}
+
+template <int KIND>
+__device__ __forceinline__ float act_value(float x, const f32x4* tab) {
+  if constexpr (KIND == TEMPO_GELU_ERF) return gelu_erf_value(x, tab);
+  else if constexpr (KIND == TEMPO_GELU_TANH) return gelu_tanh_value(x);
+  else return silu_value(x);
+}
+
 // d(y, m) = GELU'(GELU*^-1(y, m)).
 template <int KIND>
 __device__ __forceinline__ float gelu_composite(float y, bool right, const f32x4* tab) {
@@ -70,8 +95,9 @@ __device__ __forceinline__ float gelu_composite(float y, bool right, const f32x4
   const float t = fmaxf((y - ys_hi) - ys_lo, 0.0f);
   const float s = __builtin_amdgcn_sqrtf(t);
   const float c = right ? static_cast<float>(TEMPO_GELU_CR) : static_cast<float>(TEMPO_GELU_CL);
-  const float umax = right ? (TEMPO_GELU_NR - 0.00001f) : (TEMPO_GELU_NL - 0.00001f);
-  const int base = right ? 0 : TEMPO_GELU_NR;
+  constexpr int NR = GeluConst<KIND>::NR, NL = GeluConst<KIND>::NL;
+  const float umax = right ? (NR - 0.00001f) : (NL - 0.00001f);
+  const int base = right ? 0 : NR;
   const float u = fminf(s * c, umax);
   const float fl = floorf(u);
   const float z_s = u - fl;
@@ -87,7 +113,7 @@ __device__ __forceinline__ float gelu_composite(float y, bool right, const f32x4
   const float z_t = static_cast<float>(bits & ((1u << kRem) - 1u));
   const bool tail = !right && (ny < 0.0625f);
   static_assert(TEMPO_GELU_TAIL_TOP_EXP == -4, "tail threshold literal");
-  const int idx = tail ? static_cast<int>(it) + (TEMPO_GELU_NR + TEMPO_GELU_NL) : idx_s;
+  const int idx = tail ? static_cast<int>(it) + (NR + NL) : idx_s;
   const float z = tail ? z_t : z_s;
   float d = cubic(tab[idx], z);
   return (y != y) ? y : d;
@@ -140,7 +166,7 @@ __global__ __launch_bounds__(kThreads) void gelu_fwd_kernel(const float* x, floa
     for (int i = 0; i < 4; ++i) {
       const float xv = v[k][i];
       bits |= (xv >= xstar ? 1u : 0u) << i;
-      r[i] = (KIND == TEMPO_GELU_ERF) ? gelu_erf_value(xv, tab) : gelu_tanh_value(xv);
+      r[i] = act_value<KIND>(xv, tab);
     }
     // every lane of the wave takes part in the merge; absent pieces contribute zero bits
     const uint32_t word = merge_mask_word<4>(bits, threadIdx.x);
@@ -154,7 +180,7 @@ __global__ __launch_bounds__(kThreads) void gelu_bwd_kernel(const float* dy,  //
                                                             const float* __restrict__ y,
                                                             const uint32_t* __restrict__ mask,
                                                             float* dx, int64_t n) {
-  __shared__ f32x4 tab[TEMPO_GELU_BWD_ROWS];
+  __shared__ f32x4 tab[GeluConst<KIND>::kBwdRows];
   const int64_t q_base = static_cast<int64_t>(blockIdx.x) * (kThreads * K) + threadIdx.x;
   float g[K][4], o[K][4];
   uint32_t w[K];
@@ -169,7 +195,7 @@ __global__ __launch_bounds__(kThreads) void gelu_bwd_kernel(const float* dy,  //
       w[k] = __builtin_nontemporal_load(mask + (q >> 3));
     }
   }
-  load_table<TEMPO_GELU_BWD_ROWS>(tab, GeluConst<KIND>::bwd_table());
+  load_table<GeluConst<KIND>::kBwdRows>(tab, GeluConst<KIND>::bwd_table());
 #pragma unroll
   for (int k = 0; k < K; ++k) {
     const int64_t q = q_base + k * kThreads;
@@ -194,19 +220,6 @@ __global__ __launch_bounds__(kThreads) void gelu_bwd_kernel(const float* dy,  //
 // cubic path above costs ~40 VALU ops per element, more than a bf16 element's share of HBM
 // time).  Workgroups of 1024 lanes own contiguous tiles of 1024*K chunks.
 constexpr int kLutThreads = 1024;
-
-template <int KIND>
-struct GeluLut;
-template <>
-struct GeluLut<TEMPO_GELU_ERF> {
-  __device__ static const uint32_t* fwd() { return tempo_gelu_lut_fwd_erf; }
-  __device__ static const uint32_t* bwd() { return tempo_gelu_lut_bwd_erf; }
-};
-template <>
-struct GeluLut<TEMPO_GELU_TANH> {
-  __device__ static const uint32_t* fwd() { return tempo_gelu_lut_fwd_tanh; }
-  __device__ static const uint32_t* bwd() { return tempo_gelu_lut_bwd_tanh; }
-};
 
 template <int WORDS>
 __device__ __forceinline__ void stage_lut(uint32_t* lds, const uint32_t* src) {
@@ -240,10 +253,11 @@ __device__ __forceinline__ uint32_t lut_fwd_offsets(uint32_t w) {
 }
 
 // Same for the backward entries; mm holds the two mask bits at bit 0 and bit 16.  The left
-// branch (mask bit 0) looks LUT_LEFT_SHIFT patterns lower.  Index = m << 12 | sign << 11 | key.
+// branch (mask bit 0) looks SHIFT patterns lower.  Index = m << 12 | sign << 11 | key.
+template <int SHIFT>
 __device__ __forceinline__ uint32_t lut_bwd_offsets(uint32_t w, uint32_t mm) {
   constexpr short lo_r = TEMPO_GELU_LUT_LO;  // window of the right branch
-  const i16x2 shift = {TEMPO_GELU_LUT_LEFT_SHIFT, TEMPO_GELU_LUT_LEFT_SHIFT};
+  const i16x2 shift = {SHIFT, SHIFT};
   const i16x2 lo = {lo_r, lo_r};
   const i16x2 hi = {lo_r + TEMPO_GELU_LUT_N - 1, lo_r + TEMPO_GELU_LUT_N - 1};
   const i16x2 one = {1, 1};
@@ -276,6 +290,7 @@ __device__ __forceinline__ void gelu_fwd_lut_chunk(const u32x4 w, const uint32_t
   byte = acc >> 24;
 }
 
+template <int SHIFT>
 __device__ __forceinline__ u32x4 gelu_bwd_lut_chunk(const u32x4 wy, const u32x4 wd, uint32_t byte,
                                                     const uint32_t* lut) {
   const uint32_t iy[4] = {wy.x, wy.y, wy.z, wy.w};
@@ -284,7 +299,7 @@ __device__ __forceinline__ u32x4 gelu_bwd_lut_chunk(const u32x4 wy, const u32x4 
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
     const uint32_t mm = (((byte >> (2 * j)) & 3u) * 0x8001u) & 0x00010001u;
-    const uint32_t off = lut_bwd_offsets(iy[j], mm);
+    const uint32_t off = lut_bwd_offsets<SHIFT>(iy[j], mm);
     const float y0 = bf16_lo(iy[j]), y1 = bf16_hi(iy[j]);
     float d0 = as_f32(lds_word(lut, off & 0xFFFFu));
     float d1 = as_f32(lds_word(lut, off >> 16));
@@ -334,7 +349,7 @@ __global__ __launch_bounds__(kLutThreads) void gelu_fwd_lut_kernel(const bf16_t*
       else if (left > 0) w[k] = load_tail_bf16(x + q * 8, left, kAbsentX);
     }
   }
-  stage_lut<2 * TEMPO_GELU_LUT_N>(lut, GeluLut<KIND>::fwd());
+  stage_lut<2 * TEMPO_GELU_LUT_N>(lut, GeluConst<KIND>::lut_fwd());
 #pragma unroll
   for (int k = 0; k < K; ++k) {
     const int64_t q = q_base + k * kLutThreads;
@@ -390,12 +405,12 @@ __global__ __launch_bounds__(kLutThreads) void gelu_bwd_lut_kernel(const bf16_t*
       if (left > 0) mw[k] = mask[q >> 2];
     }
   }
-  stage_lut<4 * TEMPO_GELU_LUT_N>(lut, GeluLut<KIND>::bwd());
+  stage_lut<4 * TEMPO_GELU_LUT_N>(lut, GeluConst<KIND>::lut_bwd());
 #pragma unroll
   for (int k = 0; k < K; ++k) {
     const int64_t q = q_base + k * kLutThreads;
     const uint32_t byte = mw[k] >> (8 * static_cast<int>(q & 3));
-    const u32x4 r = gelu_bwd_lut_chunk(wy[k], wd[k], byte, lut);
+    const u32x4 r = gelu_bwd_lut_chunk<GeluConst<KIND>::kLutLeftShift>(wy[k], wd[k], byte, lut);
     if (full) {
       stg_stream(dx + q * 8, r);
     } else {
@@ -423,57 +438,56 @@ int pick_k(int tuned) { return tuned >= 4 ? 4 : (tuned >= 2 ? 2 : 1); }
 
 }  // namespace
 
-#define TEMPO_GELU_DISPATCH(KERNEL, ...)                                                     \
-  do {                                                                                       \
-    const int grid = tile_grid(n, k);                                                        \
-    if (kind == TEMPO_GELU_ERF) {                                                            \
-      if (k == 1) hipLaunchKernelGGL((KERNEL<TEMPO_GELU_ERF, 1>), dim3(grid), dim3(kThreads), 0, st, __VA_ARGS__);       \
-      else if (k == 2) hipLaunchKernelGGL((KERNEL<TEMPO_GELU_ERF, 2>), dim3(grid), dim3(kThreads), 0, st, __VA_ARGS__);  \
-      else hipLaunchKernelGGL((KERNEL<TEMPO_GELU_ERF, 4>), dim3(grid), dim3(kThreads), 0, st, __VA_ARGS__);              \
-    } else {                                                                                 \
-      if (k == 1) hipLaunchKernelGGL((KERNEL<TEMPO_GELU_TANH, 1>), dim3(grid), dim3(kThreads), 0, st, __VA_ARGS__);      \
-      else if (k == 2) hipLaunchKernelGGL((KERNEL<TEMPO_GELU_TANH, 2>), dim3(grid), dim3(kThreads), 0, st, __VA_ARGS__); \
-      else hipLaunchKernelGGL((KERNEL<TEMPO_GELU_TANH, 4>), dim3(grid), dim3(kThreads), 0, st, __VA_ARGS__);             \
-    }                                                                                        \
-  } while (0)
-
-#define TEMPO_LUT_DISPATCH(KERNEL, ...)                                                       \
-  do {                                                                                       \
-    const int grid = lut_grid(n, k);                                                         \
-    if (kind == TEMPO_GELU_ERF) {                                                            \
-      if (k == 1) hipLaunchKernelGGL((KERNEL<TEMPO_GELU_ERF, 1>), dim3(grid), dim3(kLutThreads), 0, st, __VA_ARGS__);       \
-      else if (k == 2) hipLaunchKernelGGL((KERNEL<TEMPO_GELU_ERF, 2>), dim3(grid), dim3(kLutThreads), 0, st, __VA_ARGS__);  \
-      else hipLaunchKernelGGL((KERNEL<TEMPO_GELU_ERF, 4>), dim3(grid), dim3(kLutThreads), 0, st, __VA_ARGS__);              \
-    } else {                                                                                 \
-      if (k == 1) hipLaunchKernelGGL((KERNEL<TEMPO_GELU_TANH, 1>), dim3(grid), dim3(kLutThreads), 0, st, __VA_ARGS__);      \
-      else if (k == 2) hipLaunchKernelGGL((KERNEL<TEMPO_GELU_TANH, 2>), dim3(grid), dim3(kLutThreads), 0, st, __VA_ARGS__); \
-      else hipLaunchKernelGGL((KERNEL<TEMPO_GELU_TANH, 4>), dim3(grid), dim3(kLutThreads), 0, st, __VA_ARGS__);             \
-    }                                                                                        \
-  } while (0)
+// Launch KERNEL<KIND, K> for the run-time (kind, k); THREADS lanes per workgroup.
+template <int KIND, typename F>
+static void with_k(int k, F&& f) {
+  if (k == 1) f(std::integral_constant<int, KIND>{}, std::integral_constant<int, 1>{});
+  else if (k == 2) f(std::integral_constant<int, KIND>{}, std::integral_constant<int, 2>{});
+  else f(std::integral_constant<int, KIND>{}, std::integral_constant<int, 4>{});
+}
+template <typename F>
+static void with_kind_k(int kind, int k, F&& f) {
+  if (kind == TEMPO_GELU_ERF) with_k<TEMPO_GELU_ERF>(k, f);
+  else if (kind == TEMPO_GELU_TANH) with_k<TEMPO_GELU_TANH>(k, f);
+  else with_k<kActSilu>(k, f);
+}
 
 tempo_status launch_gelu_fwd(const void* x, void* y, uint32_t* mask, int64_t n, tempo_dtype dt,
-                             tempo_gelu_kind kind, hipStream_t st) {
+                             int kind, hipStream_t st) {
   const int k = pick_k(tune_get(kTuneGeluFwdChunks));
   if (dt == TEMPO_BF16) {
-    TEMPO_LUT_DISPATCH(gelu_fwd_lut_kernel, static_cast<const bf16_t*>(x), static_cast<bf16_t*>(y),
-                       mask, n);
+    with_kind_k(kind, k, [&](auto kd, auto kk) {
+      hipLaunchKernelGGL((gelu_fwd_lut_kernel<decltype(kd)::value, decltype(kk)::value>),
+                         dim3(lut_grid(n, k)), dim3(kLutThreads), 0, st,
+                         static_cast<const bf16_t*>(x), static_cast<bf16_t*>(y), mask, n);
+    });
     return launch_status();
   }
-  TEMPO_GELU_DISPATCH(gelu_fwd_kernel, static_cast<const float*>(x), static_cast<float*>(y), mask,
-                      n);
+  with_kind_k(kind, k, [&](auto kd, auto kk) {
+    hipLaunchKernelGGL((gelu_fwd_kernel<decltype(kd)::value, decltype(kk)::value>),
+                       dim3(tile_grid(n, k)), dim3(kThreads), 0, st, static_cast<const float*>(x),
+                       static_cast<float*>(y), mask, n);
+  });
   return launch_status();
 }
 
 tempo_status launch_gelu_bwd(const void* dy, const void* y, const uint32_t* mask, void* dx,
-                             int64_t n, tempo_dtype dt, tempo_gelu_kind kind, hipStream_t st) {
+                             int64_t n, tempo_dtype dt, int kind, hipStream_t st) {
   const int k = pick_k(tune_get(kTuneGeluBwdChunks));
   if (dt == TEMPO_BF16) {
-    TEMPO_LUT_DISPATCH(gelu_bwd_lut_kernel, static_cast<const bf16_t*>(dy),
-                       static_cast<const bf16_t*>(y), mask, static_cast<bf16_t*>(dx), n);
+    with_kind_k(kind, k, [&](auto kd, auto kk) {
+      hipLaunchKernelGGL((gelu_bwd_lut_kernel<decltype(kd)::value, decltype(kk)::value>),
+                         dim3(lut_grid(n, k)), dim3(kLutThreads), 0, st,
+                         static_cast<const bf16_t*>(dy), static_cast<const bf16_t*>(y), mask,
+                         static_cast<bf16_t*>(dx), n);
+    });
     return launch_status();
   }
-  TEMPO_GELU_DISPATCH(gelu_bwd_kernel, static_cast<const float*>(dy),
-                      static_cast<const float*>(y), mask, static_cast<float*>(dx), n);
+  with_kind_k(kind, k, [&](auto kd, auto kk) {
+    hipLaunchKernelGGL((gelu_bwd_kernel<decltype(kd)::value, decltype(kk)::value>),
+                       dim3(tile_grid(n, k)), dim3(kThreads), 0, st, static_cast<const float*>(dy),
+                       static_cast<const float*>(y), mask, static_cast<float*>(dx), n);
+  });
   return launch_status();
 }
 

@@ -1,5 +1,7 @@
 #!/usr/bin/env python3
-"""Writes gelu_tables.inc: piecewise-cubic tables for the GELU kernels.
+"""Writes gelu_tables.inc: piecewise-cubic and per-pattern tables for the in-place activation
+kernels: GELU in its erf and tanh forms, and SiLU (the same recipe on another activation with
+a single minimum, Sec. 5.1).  "GELU" and G below stand for whichever of the three is meant.
 
     python paper_2210_10246_amd/csrc/gen_gelu_tables.py
 
@@ -48,9 +50,25 @@ from numpy.polynomial import polynomial as poly
 from scipy.special import erfc
 
 CR = 32          # right-branch pieces per unit s
-NR = 82          # right-branch pieces: s in [0, 82/32 = 2.5625)  (y up to 6.39)
 CL = 64          # left-branch pieces per unit s
-NL = 21          # left-near pieces: s in [0, 21/64), covers y in [y*, -2^-4]
+# Per activation:
+#   NR  right-branch pieces, s in [0, NR/32): up to where G' is 1 to ~1e-7 (GELU: y < 6.39,
+#       SiLU, whose derivative approaches 1 only like x e^-x: y < 17.8)
+#   NL  left-near pieces, s in [0, NL/64): covers y in [y*, -2^-4]
+#   right_top / left_span  how far the fit samples x to the right of / below the minimum
+#   bracket  an interval around the minimum on which G' changes sign once
+#   lut_left_shift  how many bf16 patterns lower the left branch's lookup window starts:
+#       GELU 6 octaves ([2^-18, 2^-2), y* = -0.17), SiLU 5 octaves ([2^-17, 2^-1), y* = -0.28)
+#   left_floor  lower end of the bisection bracket of the left branch
+GEOM = {
+    "erf": dict(NR=82, NL=21, right_top=9.0, left_span=14.5, bracket=(-1.0, -0.5),
+                lut_left_shift=0x300, left_floor=-64.0),
+    "tanh": dict(NR=82, NL=21, right_top=9.0, left_span=14.5, bracket=(-1.0, -0.5),
+                 lut_left_shift=0x300, left_floor=-64.0),
+    "silu": dict(NR=136, NL=30, right_top=19.0, left_span=30.0, bracket=(-2.0, -1.0),
+                 lut_left_shift=0x280, left_floor=-128.0),
+}
+KINDS = ("erf", "tanh", "silu")
 TAIL_TOP_EXP = -4          # tail is -y < 2^-4
 TAIL_OCTAVES = 24          # 2^-5 .. 2^-28
 TAIL_SUB_BITS = 2          # quarter octaves
@@ -66,6 +84,9 @@ K_TANH = math.sqrt(2.0 / math.pi)
 def g_val(x, kind):
     if kind == "erf":
         return x * 0.5 * erfc(-x / math.sqrt(2.0))
+    if kind == "silu":
+        with np.errstate(over="ignore"):
+            return x / (1.0 + np.exp(-x))
     u = K_TANH * (x + A_TANH * x**3)
     with np.errstate(over="ignore"):
         return x / (1.0 + np.exp(-2.0 * u))
@@ -74,6 +95,9 @@ def g_val(x, kind):
 def g_der(x, kind):
     if kind == "erf":
         return 0.5 * erfc(-x / math.sqrt(2.0)) + x * np.exp(-0.5 * x * x) / math.sqrt(2.0 * math.pi)
+    if kind == "silu":
+        with np.errstate(over="ignore"):
+            return (1.0 + x / (1.0 + np.exp(x))) / (1.0 + np.exp(-x))
     u = K_TANH * (x + A_TANH * x**3)
     with np.errstate(over="ignore"):
         sg = 1.0 / (1.0 + np.exp(-2.0 * u))
@@ -81,7 +105,7 @@ def g_der(x, kind):
 
 
 def minimum(kind):
-    lo, hi = -1.0, -0.5
+    lo, hi = GEOM[kind]["bracket"]
     for _ in range(200):
         mid = 0.5 * (lo + hi)
         if g_der(np.float64(mid), kind) < 0:
@@ -111,11 +135,13 @@ def fit_piece(z, d, deg=3):
 
 def bwd_table(kind):
     xs, ys = minimum(kind)
+    geo = GEOM[kind]
+    NR, NL = geo["NR"], geo["NL"]
     rows = np.zeros((NR + NL + NT, 4))
     errs = {}
     # ---- right branch: x from x* upward, dense in s
     n = 4_000_001
-    x = xs + np.linspace(0.0, 1.0, n) ** 2 * (9.0 - xs)
+    x = xs + np.linspace(0.0, 1.0, n) ** 2 * (geo["right_top"] - xs)
     y, d = g_val(x, kind), g_der(x, kind)
     s = np.sqrt(np.maximum(y - ys, 0.0))
     u = s * CR
@@ -126,7 +152,7 @@ def bwd_table(kind):
         worst = max(worst, e)
     errs["right"] = worst
     # ---- left branch: x from x* downward
-    x = xs - np.linspace(0.0, 1.0, n) ** 2 * 14.5
+    x = xs - np.linspace(0.0, 1.0, n) ** 2 * geo["left_span"]
     y, d = g_val(x, kind), g_der(x, kind)
     s = np.sqrt(np.maximum(y - ys, 0.0))
     u = s * CL
@@ -175,7 +201,6 @@ def fwd_table():
 
 LUT_LO = 0x3980            # bf16 pattern of 2^-12
 LUT_N = 2048               # patterns per (sign) sub-table: 16 octaves x 128
-LUT_LEFT_SHIFT = 0x300     # the left branch looks 6 octaves lower
 
 
 def bf16_value(pattern):
@@ -185,7 +210,7 @@ def bf16_value(pattern):
 def invert(y, right, kind, xs):
     """x with G(x) = y on one branch, bisection in float64."""
     y = np.asarray(y, dtype=np.float64)
-    lo = np.full(y.shape, xs if right else -64.0)
+    lo = np.full(y.shape, xs if right else GEOM[kind]["left_floor"])
     hi = np.maximum(y, 0.0) + 1.0 if right else np.full(y.shape, xs)
     for _ in range(200):
         mid = 0.5 * (lo + hi)
@@ -218,8 +243,8 @@ def lut_tables(kind):
     d = np.zeros(LUT_N)
     d[ok] = g_der(invert(y[ok], True, kind, xs), kind)
     bwd[1, 1] = d                                        # y <= y*: 0
-    # left branch, y < 0, key window 6 octaves lower
-    magl = bf16_value(LUT_LO - LUT_LEFT_SHIFT + k)
+    # left branch, y < 0, key window some octaves lower
+    magl = bf16_value(LUT_LO - GEOM[kind]["lut_left_shift"] + k)
     y = -magl
     ok = y > ys
     d = np.zeros(LUT_N)
@@ -257,20 +282,17 @@ def main():
         "#define TEMPO_TABLE_QUAL",
         "#endif",
         f"#define TEMPO_GELU_CR {CR}",
-        f"#define TEMPO_GELU_NR {NR}",
         f"#define TEMPO_GELU_CL {CL}",
-        f"#define TEMPO_GELU_NL {NL}",
         f"#define TEMPO_GELU_NT {NT}",
         f"#define TEMPO_GELU_TAIL_SUB_BITS {TAIL_SUB_BITS}",
         f"#define TEMPO_GELU_TAIL_TOP_EXP ({TAIL_TOP_EXP})",
-        f"#define TEMPO_GELU_BWD_ROWS {NR + NL + NT}",
         f"#define TEMPO_GELU_FWD_ROWS {NF}",
         f"#define TEMPO_GELU_FWD_PER_UNIT {FWD_PER_UNIT}",
         f"#define TEMPO_GELU_FWD_LO ({FWD_LO}f)",
         f"#define TEMPO_GELU_FWD_HI ({FWD_HI}f)",
     ]
     report = []
-    for kind in ("erf", "tanh"):
+    for kind in KINDS:
         xs, ys, rows, errs = bwd_table(kind)
         ys_hi = float(np.float32(ys))
         ys_lo = float(np.float32(ys - ys_hi))
@@ -280,15 +302,18 @@ def main():
             f"#define TEMPO_GELU_{K}_XSTAR_F32 {f32_hex(xs)}",
             f"#define TEMPO_GELU_{K}_YSTAR_HI {f32_hex(ys_hi)}",
             f"#define TEMPO_GELU_{K}_YSTAR_LO {f32_hex(ys_lo)}",
+            f"#define TEMPO_GELU_{K}_NR {GEOM[kind]['NR']}",
+            f"#define TEMPO_GELU_{K}_NL {GEOM[kind]['NL']}",
+            f"#define TEMPO_GELU_{K}_BWD_ROWS {rows.shape[0]}",
+            f"#define TEMPO_GELU_{K}_LUT_LEFT_SHIFT {GEOM[kind]['lut_left_shift']}",
         ]
         lines += emit_rows(f"tempo_gelu_bwd_table_{kind}", rows)
         report.append(f"{kind}: " + ", ".join(f"{k} {v:.2e}" for k, v in errs.items()))
     lines += [
         f"#define TEMPO_GELU_LUT_LO {LUT_LO}",
         f"#define TEMPO_GELU_LUT_N {LUT_N}",
-        f"#define TEMPO_GELU_LUT_LEFT_SHIFT {LUT_LEFT_SHIFT}",
     ]
-    for kind in ("erf", "tanh"):
+    for kind in KINDS:
         fwd, bwd = lut_tables(kind)
         lines += emit_flat(f"tempo_gelu_lut_fwd_{kind}", fwd)
         lines += emit_flat(f"tempo_gelu_lut_bwd_{kind}", bwd)

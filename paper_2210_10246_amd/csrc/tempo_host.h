@@ -31,10 +31,12 @@ inline tempo_status launch_status() {
   return hipGetLastError() == hipSuccess ? TEMPO_OK : TEMPO_ERR_LAUNCH;
 }
 
+// kind: TEMPO_GELU_ERF, TEMPO_GELU_TANH or kActSilu (the activation kernels serve all three).
+constexpr int kActSilu = 2;
 tempo_status launch_gelu_fwd(const void* x, void* y, uint32_t* mask, int64_t n, tempo_dtype dt,
-                             tempo_gelu_kind kind, hipStream_t st);
+                             int kind, hipStream_t st);
 tempo_status launch_gelu_bwd(const void* dy, const void* y, const uint32_t* mask, void* dx,
-                             int64_t n, tempo_dtype dt, tempo_gelu_kind kind, hipStream_t st);
+                             int64_t n, tempo_dtype dt, int kind, hipStream_t st);
 tempo_status launch_layernorm_fwd(const void* x, const float* gamma, const float* beta, void* y,
                                   float* rstd, float* mean, int64_t N, int64_t M, float eps,
                                   tempo_dtype dt, hipStream_t st);

@@ -2,6 +2,7 @@
 
 Only what is stashed for backward differs from the stock layers:
   InplaceGELU        keeps the output (which the next Linear keeps anyway) and a 1-bit mask
+  InplaceSiLU        the same for SiLU (Sec. 5.1)
   InplaceLayerNorm   keeps the output and one float per row
   TempoAttentionCore softmax -> dropout -> (. @ V) keeping the softmax output P and a 1-bit
                      mask; the dropout output is a transient in forward and is recomputed by
@@ -29,7 +30,10 @@ class _InplaceGELUFn(torch.autograd.Function):
         x = x.contiguous()
         y = torch.empty_like(x)
         mask = _words(x.numel(), x.device)
-        B.tempo_gelu_fwd(x, y, mask, kind)
+        if kind == "silu":
+            B.tempo_silu_fwd(x, y, mask)
+        else:
+            B.tempo_gelu_fwd(x, y, mask, kind)
         ctx.kind = kind
         ctx.save_for_backward(y, mask)
         return y
@@ -39,7 +43,10 @@ class _InplaceGELUFn(torch.autograd.Function):
         y, mask = ctx.saved_tensors
         dy = dy.contiguous()
         dx = torch.empty_like(dy)
-        B.tempo_gelu_bwd(dy, y, mask, dx, ctx.kind)
+        if ctx.kind == "silu":
+            B.tempo_silu_bwd(dy, y, mask, dx)
+        else:
+            B.tempo_gelu_bwd(dy, y, mask, dx, ctx.kind)
         return dx, None
 
 
@@ -52,6 +59,14 @@ class InplaceGELU(nn.Module):
 
     def forward(self, x):
         return _InplaceGELUFn.apply(x, self.kind)
+
+
+class InplaceSiLU(nn.Module):
+    """SiLU with the same stash as InplaceGELU: the in-place recipe for elementwise layers
+    (Sec. 5.1) on another activation with a single minimum."""
+
+    def forward(self, x):
+        return _InplaceGELUFn.apply(x, "silu")
 
 
 class _InplaceLayerNormFn(torch.autograd.Function):

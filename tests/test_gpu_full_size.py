@@ -69,6 +69,31 @@ def test_gelu_full_size(B, case):
     assert rel_err(got, ref) <= TOL[dt]
 
 
+@pytest.mark.parametrize("case", [CASES[0], CASES[4]])
+def test_silu_full_size(B, case):
+    """The same tensors through the SiLU entry points (Sec. 5.1)."""
+    cfg = _cfg(case)
+    dt = cfg.dtype
+    g = W.gelu_inputs(cfg)
+    x64 = W.as_f64(g["x"]).reshape(-1)
+    n = x64.size
+    xd, dyd = g["x"].cuda(), g["dy"].cuda()
+    yd = torch.empty_like(xd)
+    md = torch.empty(B.mask_words(n), dtype=torch.int32, device="cuda")
+    B.tempo_silu_fwd(xd, yd, md)
+    y_ref, m_ref = O.gelu_fwd(x64, "silu", dt)
+    assert np.array_equal(_words(md), O.pack_bits(m_ref)), "mask differs"
+    y_gpu = W.as_f64(yd).reshape(-1)
+    assert rel_err(y_gpu, y_ref) <= TOL[dt]
+    dxd = torch.empty_like(xd)
+    B.tempo_silu_bwd(dyd, yd, md, dxd)
+    rng = np.random.default_rng(50 + cfg.index)
+    idx = np.unique(np.concatenate([rng.integers(0, n, 200_000), np.arange(4096), np.arange(n - 4096, n)]))
+    dy64 = W.as_f64(g["dy"]).reshape(-1)
+    ref = O.gelu_bwd(dy64[idx], y_gpu[idx], m_ref[idx], "silu", dt)
+    assert rel_err(W.as_f64(dxd).reshape(-1)[idx], ref) <= TOL[dt]
+
+
 @pytest.mark.parametrize("case", CASES)
 def test_layernorm_full_size(B, case):
     cfg = _cfg(case)

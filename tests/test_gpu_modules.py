@@ -129,6 +129,24 @@ def test_attention_core_without_stored_mask(M):
     assert res[True][0] - res[False][0] == scores.numel() // 8
 
 
+def test_inplace_silu_module(M):
+    torch.manual_seed(4)
+    act = M.InplaceSiLU().cuda()
+    x = torch.randn(64, 1000, device="cuda", requires_grad=True) * 2
+    x.retain_grad()
+    dout = torch.randn(64, 1000, device="cuda")
+    stash, y = _stashed_bytes(lambda: act(x))
+    y.backward(dout)
+    xr = x.detach().clone().requires_grad_(True)
+    yr = F.silu(xr)
+    yr.backward(dout)
+    assert (y - yr).abs().max().item() <= 1e-5 * yr.abs().max().item()
+    # float32 y a few ulp above the minimum: d ~ sqrt(y - y*) amplifies its rounding
+    assert (x.grad - xr.grad).abs().max().item() <= 5e-3 * dout.abs().max().item()
+    assert ((x.grad - xr.grad) ** 2).mean().sqrt().item() <= 2e-6
+    assert stash == x.numel() * 4 + x.numel() // 8       # y and one bit per element
+
+
 def test_modules_in_bf16(M):
     torch.manual_seed(2)
     gelu = M.InplaceGELU().cuda()

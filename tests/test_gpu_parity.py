@@ -42,11 +42,26 @@ def stored(rng, shape, dt, scale=1.0):
     return O.round_to_dtype(rng.standard_normal(shape) * scale, dt)
 
 
-# ------------------------------------------------------------------ GELU
+# ------------------------------------------------------------------ GELU (and SiLU, Sec. 5.1)
 GELU_SIZES = [1, 7, 8, 31, 32, 33, 1000, 4099, 2 * 128 * 3072, 1_000_003]
+ACT_KINDS = ["erf", "tanh", "silu"]
 
 
-@pytest.mark.parametrize("kind", ["erf", "tanh"])
+def act_fwd(B, kind, x, y, mask):
+    if kind == "silu":
+        B.tempo_silu_fwd(x, y, mask)
+    else:
+        B.tempo_gelu_fwd(x, y, mask, kind)
+
+
+def act_bwd(B, kind, dy, y, mask, dx):
+    if kind == "silu":
+        B.tempo_silu_bwd(dy, y, mask, dx)
+    else:
+        B.tempo_gelu_bwd(dy, y, mask, dx, kind)
+
+
+@pytest.mark.parametrize("kind", ACT_KINDS)
 @pytest.mark.parametrize("dt", ["f32", "bf16"])
 @pytest.mark.parametrize("n", GELU_SIZES)
 def test_gelu_fwd(B, n, dt, kind):
@@ -55,31 +70,33 @@ def test_gelu_fwd(B, n, dt, kind):
     if n >= 1000:  # a few exact branch points, far tails and signed zeros
         xs32 = np.float32(O.GELU_XSTAR[kind])
         edge = [xs32, np.nextafter(xs32, np.float32(-9)), np.nextafter(xs32, np.float32(9)),
-                0.0, -0.0, 7.99, 8.0, 9.5, -7.99, -8.0, -9.5, 30.0, -30.0]
+                0.0, -0.0, 7.99, 8.0, 9.5, -7.99, -8.0, -9.5, 30.0, -30.0, 15.9, 16.0, 17.0,
+                -15.9, -16.0, -17.0, -60.0, -87.0, -90.0, -200.0, 200.0]
         x[: len(edge)] = O.round_to_dtype(np.array(edge, dtype=np.float64), dt)
     y_ref, m_ref = O.gelu_fwd(x, kind, dt)
     xd = dev(x, dt)
     yd = torch.full_like(xd, 7.0)
     md = torch.full((B.mask_words(n),), -1, dtype=torch.int32, device="cuda")
-    B.tempo_gelu_fwd(xd, yd, md, kind)
+    act_fwd(B, kind, xd, yd, md)
     torch.cuda.synchronize()
     assert np.array_equal(words(md), O.pack_bits(m_ref)), "mask differs"
     assert rel_err(host(yd), y_ref) <= TOL[dt]
     # in place: the input's storage need not survive
     md2 = torch.zeros_like(md)
-    B.tempo_gelu_fwd(xd, xd, md2, kind)
+    act_fwd(B, kind, xd, xd, md2)
     torch.cuda.synchronize()
     assert torch.equal(xd, yd) and torch.equal(md, md2)
 
 
-@pytest.mark.parametrize("kind", ["erf", "tanh"])
+@pytest.mark.parametrize("kind", ACT_KINDS)
 @pytest.mark.parametrize("dt", ["f32", "bf16"])
 @pytest.mark.parametrize("n", [1, 9, 33, 4099, 300_000])
 def test_gelu_bwd(B, n, dt, kind):
     rng = np.random.default_rng(100 + n)
     x = stored(rng, n, dt, 1.7)
     if n >= 4099:
-        x[:2000] = O.round_to_dtype(rng.uniform(-14.0, 8.0, 2000), dt)             # both tails
+        lo, hi = (-45.0, 22.0) if kind == "silu" else (-14.0, 8.0)
+        x[:2000] = O.round_to_dtype(rng.uniform(lo, hi, 2000), dt)                  # both tails
         x[2000:3000] = O.round_to_dtype(O.GELU_XSTAR[kind] + rng.normal(size=1000) * 1e-2, dt)
     y, m = O.gelu_fwd(x, kind, dt)
     dy = stored(rng, n, dt)
@@ -87,34 +104,37 @@ def test_gelu_bwd(B, n, dt, kind):
     dyd, yd = dev(dy, dt), dev(y, dt)
     md = torch.from_numpy(O.pack_bits(m).view(np.int32)).cuda()
     dxd = torch.empty_like(dyd)
-    B.tempo_gelu_bwd(dyd, yd, md, dxd, kind)
+    act_bwd(B, kind, dyd, yd, md, dxd)
     torch.cuda.synchronize()
     assert rel_err(host(dxd), ref) <= TOL[dt]
-    B.tempo_gelu_bwd(dyd, yd, md, dyd, kind)     # dx may alias dy
+    act_bwd(B, kind, dyd, yd, md, dyd)     # dx may alias dy
     torch.cuda.synchronize()
     assert torch.equal(dyd, dxd)
 
 
-@pytest.mark.parametrize("kind", ["erf", "tanh"])
+@pytest.mark.parametrize("kind", ACT_KINDS)
 def test_gelu_bwd_edge_values(B, kind):
     ys = O.GELU_YSTAR[kind]
     y = np.array([ys - 1e-3, ys, 0.0, -0.0, 0.0, np.inf, np.nan, 1e-30, -1e-30, -1e-45, 20.0, 6.5,
-                  -0.0625, -0.06249, -0.1, 1e-20], dtype=np.float64)
+                  -0.0625, -0.06249, -0.1, 1e-20, 17.5, 18.5, 40.0, 0.9 * ys, 0.9 * ys, 0.999 * ys,
+                  0.999 * ys, -1e-8, -1e-10], dtype=np.float64)
     y = O.round_to_dtype(y, "f32")
-    m = np.array([1, 1, 0, 0, 1, 1, 1, 0, 0, 0, 1, 1, 0, 0, 0, 1], dtype=bool)
+    m = np.array([1, 1, 0, 0, 1, 1, 1, 0, 0, 0, 1, 1, 0, 0, 0, 1, 1, 1, 1, 0, 1, 0, 1, 0, 0],
+                 dtype=bool)
     dy = np.ones_like(y)
     ref = O.gelu_bwd(dy, y, m, kind, "f32")
     dxd = torch.empty(y.size, dtype=torch.float32, device="cuda")
     md = torch.from_numpy(O.pack_bits(m).view(np.int32)).cuda()
-    B.tempo_gelu_bwd(dev(dy, "f32"), dev(y, "f32"), md, dxd, kind)
+    act_bwd(B, kind, dev(dy, "f32"), dev(y, "f32"), md, dxd)
     got = host(dxd)
     assert np.isnan(got[6]) and np.isnan(ref[6])
     ok = ~np.isnan(ref)
     np.testing.assert_allclose(got[ok], ref[ok], rtol=0, atol=5e-7)
 
 
+@pytest.mark.parametrize("kind", ["erf", "silu"])
 @pytest.mark.parametrize("dt", ["f32", "bf16"])
-def test_gelu_round_trip_against_input_based_gradient(B, dt):
+def test_gelu_round_trip_against_input_based_gradient(B, dt, kind):
     # fwd then bwd on the GPU vs dy * GELU'(x): the lossy part is only the storage of y
     rng = np.random.default_rng(7)
     n = 200_000
@@ -124,9 +144,9 @@ def test_gelu_round_trip_against_input_based_gradient(B, dt):
     yd = torch.empty_like(xd)
     md = torch.empty(B.mask_words(n), dtype=torch.int32, device="cuda")
     dxd = torch.empty_like(xd)
-    B.tempo_gelu_fwd(xd, yd, md, "erf")
-    B.tempo_gelu_bwd(dyd, yd, md, dxd, "erf")
-    ref = O.gelu_bwd_from_input(dy, x, "erf")
+    act_fwd(B, kind, xd, yd, md)
+    act_bwd(B, kind, dyd, yd, md, dxd)
+    ref = O.gelu_bwd_from_input(dy, x, kind)
     err = np.abs(host(dxd) - ref)
     # the square-root singularity at the minimum amplifies the rounding of y: |dd| ~ sqrt(ulp)
     assert err.max() <= (5e-3 if dt == "f32" else 0.15) * max(1.0, np.abs(dy).max())

@@ -55,6 +55,10 @@ def test_invalid_arguments_are_rejected_before_any_launch():
     assert lib.tempo_attn_softmax_dropout_bwd_regen(16, None, 16, None, 1, 1, 8, 8, 0.1, 0, 0, 0, None) == INVALID
     assert lib.tempo_attn_softmax_dropout_bwd_regen(16, 16, 24, None, 1, 1, 8, 8, 0.1, 0, 0, 0, None) == UNSUPPORTED
     assert lib.tempo_mask_bits_to_bytes(16, 16, -1, None) == INVALID
+    assert lib.tempo_silu_fwd(16, 16, 16, -1, 0, None) == INVALID
+    assert lib.tempo_silu_fwd(16, 16, 16, 8, 5, None) == INVALID
+    assert lib.tempo_silu_bwd(16, 16, None, 16, 8, 0, None) == INVALID
+    assert lib.tempo_silu_bwd(16, 24, 16, 16, 8, 0, None) == UNSUPPORTED
     assert lib.tempo_mask_bits_to_bytes(None, 16, 5, None) == INVALID
     assert lib.tempo_mask_bytes_to_bits(16, None, 5, None) == INVALID
     assert lib.tempo_mask_bytes_to_bits(17, 16, 5, None) == UNSUPPORTED
@@ -75,6 +79,8 @@ def test_zero_sizes_return_ok_without_pointers():
     assert lib.tempo_attn_softmax_dropout_bwd(None, None, None, None, None, 2, 12, 0, 128, 0.1, 0, None) == 0
     assert lib.tempo_attn_softmax_dropout_bwd_regen(None, None, None, None, 2, 0, 8, 128, 0.1, 1, 2, 0, None) == 0
     assert lib.tempo_mask_bits_to_bytes(None, None, 0, None) == 0
+    assert lib.tempo_silu_fwd(None, None, None, 0, 0, None) == 0
+    assert lib.tempo_silu_bwd(None, None, None, None, 0, 1, None) == 0
     assert lib.tempo_mask_bytes_to_bits(None, None, 0, None) == 0
     assert lib.tempo_layernorm_bwd_workspace_bytes(0, 8) == 0
 
