@@ -61,7 +61,8 @@ TEMPO_API int tempo_version(void);
  *   key 6, 7: rows a lane group of attn fwd / layernorm_fwd fetches at once (1 or 2);
  *   key 8, 9, 10, 11: attn fwd / attn bwd / layernorm_fwd / layernorm_bwd: 16-byte pieces per
  *   lane above which a row is spread over 2 or 4 waves instead of one (16 or more: never);
- *   key 3: rows each lane group of layernorm_bwd walks; keys 3 and 11 set its grid and the
+ *   key 3: rows each lane group of layernorm_bwd walks; key 12: workgroups per compute unit
+ *   beyond which its workgroups loop over the rows; keys 3, 11 and 12 set its grid and the
  *   size of its workspace, so query tempo_layernorm_bwd_workspace_bytes after changing them.
  * Results never depend on these except the summation order of dgamma/dbeta and of the softmax
  * denominator and the other row sums (keys 8-11).  value in

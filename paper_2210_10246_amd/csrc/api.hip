@@ -20,6 +20,7 @@ static std::atomic<int> g_tune[kTuneCount] = {
     {4},      // attention bwd: the same
     {4},      // layernorm fwd: the same
     {4},      // layernorm bwd: the same
+    {1},      // layernorm bwd: workgroups per CU beyond which they loop with prefetch
 };
 
 int tune_get(TuneKey k) { return g_tune[k].load(std::memory_order_relaxed); }

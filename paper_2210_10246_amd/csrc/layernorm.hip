@@ -641,10 +641,11 @@ static BwdPlan bwd_plan(int64_t N, const Shape& sh, tempo_dtype dt) {
   if (r > avail) r = avail;
   while (r > 1 && (r * regs_per_row > 64 || batches(r) < cus)) r >>= 1;
   BwdPlan p = {r, false, static_cast<int>(batches(r) > 4096 ? 4096 : batches(r))};
-  if (batches(r) > 2 * cus) {
+  const int per_cu = tune_get(kTuneLnBwdLoopBlocksPerCu);
+  if (batches(r) > static_cast<int64_t>(per_cu) * cus) {
     p.loop = true;
     p.r = r > 1 ? r / 2 : 1;
-    p.grid = 2 * cus;
+    p.grid = per_cu * cus;
   }
   if (p.grid < 1) p.grid = 1;
   return p;

@@ -22,7 +22,8 @@ enum TuneKey {
   kTuneAttnBwdMaxPieces = 9,    // the same for attn bwd
   kTuneLnFwdMaxPieces = 10,     // the same for layernorm_fwd
   kTuneLnBwdMaxPieces = 11,     // and layernorm_bwd
-  kTuneCount = 12
+  kTuneLnBwdLoopBlocksPerCu = 12,  // layernorm_bwd: workgroups per CU beyond which they loop
+  kTuneCount = 13
 };
 int tune_get(TuneKey k);
 int compute_units();
