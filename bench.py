@@ -28,14 +28,16 @@ METRIC = "fwd+bwd HBM GB/s (% of peak) per layer; activation bytes saved/token"
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
+    # defaults long enough for the clocks to settle: short runs read 3-4 % low
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=400)
     ap.add_argument("--config", type=int, default=1, help="workload configuration index (0-4)")
     ap.add_argument("--batch", type=int, default=None, help="batch override (config 4 sweep)")
     ap.add_argument("--dtype", choices=["f32", "bf16"], default=None)
     ap.add_argument("--seq", type=int, default=None, help="sequence length override (shape sweeps)")
     ap.add_argument("--hidden", type=int, default=None, help="hidden size override; heads = hidden/64")
-    ap.add_argument("--kernel-iters", type=int, default=60, help="launches per kernel timing loop")
+    ap.add_argument("--kernel-iters", type=int, default=60, help="launches per kernel timing burst")
+    ap.add_argument("--kernel-bursts", type=int, default=5, help="timed bursts per kernel")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true")
     ap.add_argument("--no-graph", action="store_true",
@@ -201,8 +203,8 @@ def main():
     use_graph = not args.no_graph
     ms_per_step = float("nan")
     if args.only is None:
-        for i in range(max(args.warmup, PHASES)):
-            step(i % PHASES)
+        for i in range(PHASES):
+            step(i)
         torch.cuda.synchronize()
         if use_graph:
             # one graph per step, and one holding PHASES consecutive steps: the timed loop
@@ -223,6 +225,7 @@ def main():
             def run_steps(k):
                 for i in range(k):
                     step(i % PHASES)
+        run_steps(args.warmup)   # the untimed warm-up steps, launched the same way as the timed ones
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         run_steps(args.steps)
@@ -244,14 +247,21 @@ def main():
                 for _ in range(args.kernel_iters):
                     fn(bufs.next())
             body = capture(burst).replay if use_graph else burst
-            body()
-            torch.cuda.synchronize()
+            # steady state first (clocks ramp over some milliseconds of load), then the average
+            # launch duration over kernel_bursts bursts of kernel_iters launches
+            t_warm = time.perf_counter()
+            while True:
+                body()
+                torch.cuda.synchronize()
+                if time.perf_counter() - t_warm > 0.03:
+                    break
             ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             ev0.record()
-            body()
+            for _ in range(args.kernel_bursts):
+                body()
             ev1.record()
             ev1.synchronize()
-            us = ev0.elapsed_time(ev1) * 1e3 / args.kernel_iters
+            us = ev0.elapsed_time(ev1) * 1e3 / (args.kernel_iters * args.kernel_bursts)
             gbs = algo[name] / us * 1e-3
             per_kernel[name] = {"us": round(us, 2), "GB/s": round(gbs, 1),
                                 "frac_of_peak": round(gbs / HBM_PEAK_GBS, 4),

@@ -48,7 +48,9 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
   w[0] = c0; w[1] = c1; w[2] = c2; w[3] = c3;
 }
 
-// Keep bits of the 8 elements of group g (bit i = element 8g + i).
+// Keep bits of the 8 elements of group g (bit i = element 8g + i).  A 16-bit draw r is kept iff
+// r < t16, i.e. iff r - t16 is negative: v_alignbit shifts that sign bit into the byte, last
+// element first.
 __device__ __forceinline__ uint32_t keep_byte(uint64_t g, const RngArgs& a) {
   if (a.t16 >= 65536u) return 0xFFu;
   uint32_t w[4];
@@ -56,11 +58,19 @@ __device__ __forceinline__ uint32_t keep_byte(uint64_t g, const RngArgs& a) {
                 a.seed_lo, a.seed_hi, w);
   uint32_t byte = 0;
 #pragma unroll
-  for (int i = 3; i >= 0; --i) {  // last element first: each step shifts one bit in
-    byte = (byte << 1) | ((w[i] >> 16) < a.t16 ? 1u : 0u);
-    byte = (byte << 1) | ((w[i] & 0xFFFFu) < a.t16 ? 1u : 0u);
+  for (int i = 3; i >= 0; --i) {
+    byte = __builtin_amdgcn_alignbit(byte, (w[i] >> 16) - a.t16, 31);      // byte << 1 | sign
+    byte = __builtin_amdgcn_alignbit(byte, (w[i] & 0xFFFFu) - a.t16, 31);
   }
   return byte;
+}
+
+// All ones if bit k of bits is set, else zero (one v_bfe_i32), and a float kept or zeroed by it.
+__device__ __forceinline__ uint32_t bit_mask(uint32_t bits, int k) {
+  return static_cast<uint32_t>(__builtin_amdgcn_sbfe(static_cast<int>(bits), k, 1));
+}
+__device__ __forceinline__ float keep_or_zero(float v, uint32_t bits, int k) {
+  return as_f32(as_u32(v) & bit_mask(bits, k));
 }
 
 
@@ -241,12 +251,16 @@ __global__ __launch_bounds__(kThreads) void attn_fwd_kernel(
         if (valid) {
           float p8[V], o8[V];
 #pragma unroll
-          for (int k = 0; k < V; ++k) {
-            p8[k] = Store<T>::round(v[c][k] * rinv);
-            o8[k] = ((bits[c] >> k) & 1u) ? p8[k] * scale : 0.0f;
+          for (int k = 0; k < V; ++k) p8[k] = v[c][k] * rinv;
+          // round P once, into the words that are stored; Out is computed from the stored P
+          const u32x4 pw = Store<T>::pack(p8);
+          Store<T>::unpack(pw, p8);
+          stg_stream(probs + row * Sk + pc * V, pw);
+          if (out) {
+#pragma unroll
+            for (int k = 0; k < V; ++k) o8[k] = keep_or_zero(p8[k] * scale, bits[c], k);
+            store_piece<T>(out + row * Sk + pc * V, o8);
           }
-          store_piece<T>(probs + row * Sk + pc * V, p8);
-          if (out) store_piece<T>(out + row * Sk + pc * V, o8);
         }
         store_keep_bits<T, WORDS>(keep_bits, piece0 + pc, t, valid ? bits[c] : 0u, valid,
                                   total_pieces);
@@ -317,7 +331,7 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_kernel(
         }
 #pragma unroll
         for (int k = 0; k < V; ++k) {
-          dp[c][k] = ((bits[r][c] >> k) & 1u) ? dp[c][k] * scale : 0.0f;
+          dp[c][k] = keep_or_zero(dp[c][k] * scale, bits[r][c], k);
           dot = fmaf(dp[c][k], pr[c][k], dot);
         }
       }
@@ -334,7 +348,7 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_kernel(
             float o8[V];
 #pragma unroll
             for (int k = 0; k < V; ++k)
-              o8[k] = ((bits[r][c] >> k) & 1u) ? pr[c][k] * scale : 0.0f;
+              o8[k] = keep_or_zero(pr[c][k] * scale, bits[r][c], k);
             store_piece<T>(out_re + row * Sk + pc * V, o8);
           }
         }
