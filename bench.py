@@ -38,6 +38,8 @@ def parse():
     ap.add_argument("--hidden", type=int, default=None, help="hidden size override; heads = hidden/64")
     ap.add_argument("--kernel-iters", type=int, default=60, help="launches per kernel timing burst")
     ap.add_argument("--kernel-bursts", type=int, default=5, help="timed bursts per kernel")
+    ap.add_argument("--kernel-warm-ms", type=float, default=30.0,
+                    help="untimed replays of a kernel's burst before it is timed")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true")
     ap.add_argument("--no-graph", action="store_true",
@@ -253,7 +255,7 @@ def main():
             while True:
                 body()
                 torch.cuda.synchronize()
-                if time.perf_counter() - t_warm > 0.03:
+                if time.perf_counter() - t_warm > args.kernel_warm_ms * 1e-3:
                     break
             ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             ev0.record()

@@ -9,7 +9,7 @@ namespace tempo {
 
 static std::atomic<int> g_tune[kTuneCount] = {
     {4},      // gelu fwd: chunks per lane
-    {2},      // gelu bwd: chunks per lane
+    {1},      // gelu bwd: chunks per lane
     {3},      // layernorm fwd: workgroups per CU (beyond that they loop with prefetch)
     {4},      // layernorm bwd: rows per lane group
     {65536},  // attention fwd: workgroups per CU (65536 = one row per lane group)
@@ -21,6 +21,8 @@ static std::atomic<int> g_tune[kTuneCount] = {
     {4},      // layernorm fwd: the same
     {4},      // layernorm bwd: the same
     {1},      // layernorm bwd: workgroups per CU beyond which they loop with prefetch
+    {65536},  // bf16 gelu/silu fwd: workgroups per CU beyond which they loop with prefetch
+    {1},      // bf16 gelu/silu bwd: the same
 };
 
 int tune_get(TuneKey k) { return g_tune[k].load(std::memory_order_relaxed); }
