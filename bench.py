@@ -269,23 +269,43 @@ def main():
                                 "frac_of_peak": round(gbs / HBM_PEAK_GBS, 4),
                                 "bytes": int(algo[name]), "buffer_sets": bufs.n}
 
-    # ---- what a plain 16-byte copy reaches on this GPU (read + write bytes per second)
-    copy_gbs = None
-    if not args.no_kernel_timing and args.only in (None, "copy"):
-        nb = 256 << 20
+    # ---- what a plain 16-byte copy reaches on this GPU (read + write bytes per second): at
+    # 256 MiB, and moving as many bytes as the slowest kernel of the step moves per launch
+    def time_copy(nb):
         srcs = [torch.empty(nb, dtype=torch.uint8, device=dev).fill_(i) for i in range(3)]
         dsts = [torch.empty(nb, dtype=torch.uint8, device=dev) for _ in range(3)]
-        for i in range(3):
-            B.tempo_copy(srcs[i], dsts[i])
+
+        def copies():
+            for i in range(30):
+                B.tempo_copy(srcs[i % 3], dsts[i % 3], blocks_per_cu=65536)   # one access per lane
+        copies()
         torch.cuda.synchronize()
+        body = capture(copies).replay if use_graph else copies
+        t_warm = time.perf_counter()
+        while True:
+            body()
+            torch.cuda.synchronize()
+            if time.perf_counter() - t_warm > args.kernel_warm_ms * 1e-3:
+                break
         ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         ev0.record()
-        for i in range(30):
-            B.tempo_copy(srcs[i % 3], dsts[i % 3])
+        body()
         ev1.record()
         ev1.synchronize()
-        copy_gbs = round(2 * nb * 30 / (ev0.elapsed_time(ev1) * 1e-3) * 1e-9, 1)
-        del srcs, dsts
+        us = ev0.elapsed_time(ev1) * 1e3 / 30
+        return us, 2 * nb / us * 1e-3
+
+    copy_gbs = None
+    copy_same = None
+    if not args.no_kernel_timing and args.only in (None, "copy"):
+        copy_gbs = round(time_copy(256 << 20)[1], 1)
+        in_step = {k: v for k, v in per_kernel.items() if k in kernels}
+        if in_step:
+            dom = max(in_step, key=lambda k: in_step[k]["us"])
+            nb = int(in_step[dom]["bytes"] // 2) // 16 * 16
+            us, gbs = time_copy(nb)
+            copy_same = {"as_many_bytes_as": dom, "bytes": 2 * nb, "us": round(us, 2),
+                         "GB/s": round(gbs, 1)}
 
     value = step_bytes / (ms_per_step * 1e-3) * 1e-9 if ms_per_step == ms_per_step else None
     roofline = None
@@ -317,6 +337,7 @@ def main():
                    "algorithmic_bytes_per_step": int(step_bytes)},
         "frac_of_hbm_peak": None if value is None else round(value / HBM_PEAK_GBS, 4),
         "copy_kernel_GB/s": copy_gbs,
+        "copy_kernel_same_bytes": copy_same,
         "roofline": roofline,
         "cpu_baseline": cpu,
         "kernels": per_kernel,

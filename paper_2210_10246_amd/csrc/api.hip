@@ -9,7 +9,7 @@ namespace tempo {
 
 static std::atomic<int> g_tune[kTuneCount] = {
     {4},      // gelu fwd: chunks per lane
-    {1},      // gelu bwd: chunks per lane
+    {2},      // gelu bwd: chunks per lane
     {3},      // layernorm fwd: workgroups per CU (beyond that they loop with prefetch)
     {4},      // layernorm bwd: rows per lane group
     {65536},  // attention fwd: workgroups per CU (65536 = one row per lane group)
@@ -21,8 +21,6 @@ static std::atomic<int> g_tune[kTuneCount] = {
     {4},      // layernorm fwd: the same
     {4},      // layernorm bwd: the same
     {1},      // layernorm bwd: workgroups per CU beyond which they loop with prefetch
-    {65536},  // bf16 gelu/silu fwd: workgroups per CU beyond which they loop with prefetch
-    {1},      // bf16 gelu/silu bwd: the same
 };
 
 int tune_get(TuneKey k) { return g_tune[k].load(std::memory_order_relaxed); }
@@ -53,7 +51,7 @@ __global__ __launch_bounds__(256) void copy_kernel(const u32x4* __restrict__ src
                                                    u32x4* __restrict__ dst, int64_t n16) {
   const int64_t stride = static_cast<int64_t>(gridDim.x) * 256;
   for (int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x; i < n16; i += stride)
-    dst[i] = src[i];
+    __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
 }
 
 }  // namespace tempo

@@ -65,14 +65,41 @@ __device__ __forceinline__ uint32_t keep_byte(uint64_t g, const RngArgs& a) {
   return byte;
 }
 
-// All ones if bit k of bits is set, else zero (one v_bfe_i32), and a float kept or zeroed by it.
-__device__ __forceinline__ uint32_t bit_mask(uint32_t bits, int k) {
-  return static_cast<uint32_t>(__builtin_amdgcn_sbfe(static_cast<int>(bits), k, 1));
-}
-__device__ __forceinline__ float keep_or_zero(float v, uint32_t bits, int k) {
-  return as_f32(as_u32(v) & bit_mask(bits, k));
+// All ones if bit K of bits is set, else zero.  Written as the instruction itself: spelled in
+// C++ the compiler turns the following AND into test + compare + select, three operations per
+// element where two suffice (these kernels run close to the vector-ALU limit).
+template <int K>
+__device__ __forceinline__ uint32_t bit_mask(uint32_t bits) {
+  uint32_t m;
+  asm("v_bfe_i32 %0, %1, %2, 1" : "=v"(m) : "v"(bits), "n"(K));
+  return m;
 }
 
+// Zero the dropped elements of a packed piece: keep bit i belongs to element i of the piece.
+// bfloat16 words hold two elements: their two masks are merged byte-wise (v_perm_b32).
+template <typename T>
+__device__ __forceinline__ u32x4 apply_keep(u32x4 w, uint32_t bits) {
+  if constexpr (Store<T>::kVec == 4) {
+    w.x &= bit_mask<0>(bits);
+    w.y &= bit_mask<1>(bits);
+    w.z &= bit_mask<2>(bits);
+    w.w &= bit_mask<3>(bits);
+  } else {
+    constexpr uint32_t kLoHalves = 0x05040100u;  // bytes 0,1 of the second source, then of the first
+    w.x &= __builtin_amdgcn_perm(bit_mask<1>(bits), bit_mask<0>(bits), kLoHalves);
+    w.y &= __builtin_amdgcn_perm(bit_mask<3>(bits), bit_mask<2>(bits), kLoHalves);
+    w.z &= __builtin_amdgcn_perm(bit_mask<5>(bits), bit_mask<4>(bits), kLoHalves);
+    w.w &= __builtin_amdgcn_perm(bit_mask<7>(bits), bit_mask<6>(bits), kLoHalves);
+  }
+  return w;
+}
+
+
+// Element offset of the start of a row: rows are counted in 32 bits on the register-resident
+// paths (the host checks), so the product is one 32x32->64 multiply instead of a 64x64 one.
+__device__ __forceinline__ int64_t row_offset(uint32_t row, int Sk) {
+  return static_cast<int64_t>(static_cast<uint64_t>(row) * static_cast<uint32_t>(Sk));
+}
 
 // Number of leading key columns of query row i that take part in the softmax.
 __device__ __forceinline__ int row_limit(int i, int key_limit, int causal, int Sq, int Sk) {
@@ -192,7 +219,7 @@ __global__ __launch_bounds__(kThreads) void attn_fwd_kernel(
     for (int r = 0; r < R; ++r) {
       const int i = i0 + r * kGroups;
       limit[r] = (i < Sq) ? row_limit(i, key_limit, causal, Sq, Sk) : -1;
-      const T* sr = scores + (static_cast<int64_t>(slice) * Sq + i) * Sk;
+      const T* sr = scores + row_offset(static_cast<uint32_t>(slice) * Sq + i, Sk);
 #pragma unroll
       for (int c = 0; c < CH; ++c) {
         const int col0 = (c * LANES + t) * V;
@@ -205,7 +232,7 @@ __global__ __launch_bounds__(kThreads) void attn_fwd_kernel(
       // stores) because the reductions below hold workgroup barriers
       const bool live = limit[r] >= 0;
       if (LANES <= kWave && !live) continue;
-      const int64_t row = static_cast<int64_t>(slice) * Sq + i0 + r * kGroups;
+      const int64_t row0 = row_offset(static_cast<uint32_t>(slice) * Sq + i0 + r * kGroups, Sk);
       float v[CH][V];
       float mx = -INFINITY;
 #pragma unroll
@@ -241,7 +268,7 @@ __global__ __launch_bounds__(kThreads) void attn_fwd_kernel(
       }
       sum = row_reduce<LANES, false>(sum, red[1]);
       const float rinv = (sum > 0.0f) ? __builtin_amdgcn_rcpf(sum) : 0.0f;
-      const int64_t piece0 = row * pieces;
+      const int64_t piece0 = row0 / V;  // Sk is a multiple of the piece length here
       uint32_t bits[CH];
       lane_keep_bits<T, LANES, CH>(piece0, t, rng, bits);
 #pragma unroll
@@ -255,11 +282,11 @@ __global__ __launch_bounds__(kThreads) void attn_fwd_kernel(
           // round P once, into the words that are stored; Out is computed from the stored P
           const u32x4 pw = Store<T>::pack(p8);
           Store<T>::unpack(pw, p8);
-          stg_stream(probs + row * Sk + pc * V, pw);
+          stg_stream(probs + row0 + pc * V, pw);
           if (out) {
 #pragma unroll
-            for (int k = 0; k < V; ++k) o8[k] = keep_or_zero(p8[k] * scale, bits[c], k);
-            store_piece<T>(out + row * Sk + pc * V, o8);
+            for (int k = 0; k < V; ++k) o8[k] = p8[k] * scale;
+            stg_stream(out + row0 + pc * V, apply_keep<T>(Store<T>::pack(o8), bits[c]));
           }
         }
         store_keep_bits<T, WORDS>(keep_bits, piece0 + pc, t, valid ? bits[c] : 0u, valid,
@@ -277,7 +304,7 @@ enum MaskSource { kMaskWords, kMaskBytes, kMaskRegen };
 template <typename T, int LANES, int CH, int R, MaskSource MASK>
 __global__ __launch_bounds__(kThreads) void attn_bwd_kernel(
     const T* dout, const T* __restrict__ probs, const uint32_t* __restrict__ keep_bits,
-    T* dscores, T* __restrict__ out_re, int64_t rows, int Sk, float scale, RngArgs rng) {
+    T* dscores, T* __restrict__ out_re, uint32_t rows, int Sk, float scale, RngArgs rng) {
   constexpr int kGroups = kThreads / LANES;
   constexpr int V = Store<T>::kVec;
   const int g = threadIdx.x / LANES;
@@ -298,17 +325,19 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_kernel(
         const int pc = c * LANES + t;
         bits[r][c] = 0;
         if (row < rows && pc < pieces) {
-          rdo[r][c].load(dout + row * Sk + pc * V);
-          rp[r][c].load(probs + row * Sk + pc * V);
+          const int64_t row0 = row_offset(static_cast<uint32_t>(row), Sk);
+          rdo[r][c].load(dout + row0 + pc * V);
+          rp[r][c].load(probs + row0 + pc * V);
           if constexpr (MASK != kMaskRegen)
-            bits[r][c] = load_keep_bits<T, MASK == kMaskWords>(keep_bits, row * pieces + pc);
+            bits[r][c] = load_keep_bits<T, MASK == kMaskWords>(keep_bits, row0 / V + pc);
         }
       }
     }
     if constexpr (MASK == kMaskRegen) {  // every lane takes part: lane pairs share draws
 #pragma unroll
       for (int r = 0; r < R; ++r)
-        lane_keep_bits<T, LANES, CH>((base + r * kGroups + g) * pieces, t, rng, bits[r]);
+        lane_keep_bits<T, LANES, CH>(
+            row_offset(static_cast<uint32_t>(base + r * kGroups + g), Sk) / V, t, rng, bits[r]);
     }
 #pragma unroll
     for (int r = 0; r < R; ++r) {
@@ -317,13 +346,14 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_kernel(
       // holds a workgroup barrier) with zeros and stores nothing
       const bool live = row < rows;
       if (LANES <= kWave && !live) continue;
+      const int64_t row0 = row_offset(static_cast<uint32_t>(row), Sk);
       float dp[CH][V], pr[CH][V];
       float dot = 0.0f;
 #pragma unroll
       for (int c = 0; c < CH; ++c) {
         const int pc = c * LANES + t;
         if (live && pc < pieces) {
-          rdo[r][c].unpack(dp[c]);
+          Store<T>::unpack(apply_keep<T>(rdo[r][c].a, bits[r][c]), dp[c]);  // dropped: dP = 0
           rp[r][c].unpack(pr[c]);
         } else {
 #pragma unroll
@@ -331,7 +361,7 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_kernel(
         }
 #pragma unroll
         for (int k = 0; k < V; ++k) {
-          dp[c][k] = keep_or_zero(dp[c][k] * scale, bits[r][c], k);
+          dp[c][k] *= scale;
           dot = fmaf(dp[c][k], pr[c][k], dot);
         }
       }
@@ -343,13 +373,13 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_kernel(
           float ds[V];
 #pragma unroll
           for (int k = 0; k < V; ++k) ds[k] = pr[c][k] * (dp[c][k] - dot);
-          store_piece<T>(dscores + row * Sk + pc * V, ds);
+          store_piece<T>(dscores + row0 + pc * V, ds);
           if (out_re) {
             float o8[V];
 #pragma unroll
-            for (int k = 0; k < V; ++k)
-              o8[k] = keep_or_zero(pr[c][k] * scale, bits[r][c], k);
-            store_piece<T>(out_re + row * Sk + pc * V, o8);
+            for (int k = 0; k < V; ++k) o8[k] = pr[c][k] * scale;
+            stg_stream(out_re + row0 + pc * V,
+                       apply_keep<T>(Store<T>::pack(o8), bits[r][c]));
           }
         }
       }
@@ -554,7 +584,8 @@ static void attn_bwd_go(MaskSource mask, int grid, hipStream_t st, const void* d
     hipLaunchKernelGGL((attn_bwd_kernel<T, L, C, 1, decltype(m)::value>), dim3(grid),
                        dim3(kThreads), 0, st, static_cast<const T*>(dout),
                        static_cast<const T*>(probs), keep_bits, static_cast<T*>(dscores),
-                       static_cast<T*>(out_re), rows, static_cast<int>(Sk), scale, rng);
+                       static_cast<T*>(out_re), static_cast<uint32_t>(rows), static_cast<int>(Sk),
+                       scale, rng);
   };
   using std::integral_constant;
   if (mask == kMaskWords) return go(integral_constant<MaskSource, kMaskWords>{});
@@ -586,7 +617,7 @@ tempo_status launch_attn_fwd(const void* scores, const int32_t* key_len, int cau
   const int vec = dt == TEMPO_F32 ? 4 : 8;
   Shape sh = pick_wide_shape(static_cast<int>(Sk / vec), 32 / vec,
                             tune_get(kTuneAttnFwdMaxPieces));
-  if (Sk % 8 == 0 && sh.ch != 0 && B * A <= INT32_MAX) {
+  if (Sk % 8 == 0 && sh.ch != 0 && rows <= UINT32_MAX) {  // rows counted in 32 bits
     const int slices = static_cast<int>(B * A);
     const int rr = sh.lanes > kWave ? 1 : attn_rows(sh.ch, tune_get(kTuneAttnFwdRows));
     const int rows_per_set = (kThreads / sh.lanes) * rr;
@@ -641,7 +672,7 @@ static tempo_status attn_bwd_any(const void* dout, const void* probs, const uint
   const int vec = dt == TEMPO_F32 ? 4 : 8;
   Shape sh = pick_wide_shape(static_cast<int>(Sk / vec), 32 / vec,
                             tune_get(kTuneAttnBwdMaxPieces));
-  if (Sk % 8 == 0 && sh.ch != 0) {
+  if (Sk % 8 == 0 && sh.ch != 0 && rows <= UINT32_MAX) {  // rows counted in 32 bits
     const int grid = row_grid(rows, sh.lanes, bpc);
     const MaskSource mask = regen ? kMaskRegen : (Sk % 32 == 0 ? kMaskWords : kMaskBytes);
 #define TEMPO_LAUNCH(L, C)                                                                   \

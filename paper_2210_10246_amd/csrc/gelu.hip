@@ -327,14 +327,16 @@ __device__ __forceinline__ void store_tail_bf16(bf16_t* p, int64_t left, const u
 
 constexpr uint32_t kAbsentX = 0xF149F149u;  // two bf16 of about -2.5e30: mask bit 0
 
-// One tile = kLutThreads*K pieces; piece k of lane t of tile b is b*kLutThreads*K + k*kLutThreads + t.
-// A tile that lies wholly inside the tensor takes straight-line 16-byte accesses; the last,
-// partial one goes element by element where needed.
-template <int K>
-__device__ __forceinline__ void fwd_tile_load(const bf16_t* x, int64_t n, int64_t tile,
-                                              u32x4 (&w)[K]) {
-  const int64_t q_base = tile * (kLutThreads * K) + threadIdx.x;
-  if ((tile + 1) * (kLutThreads * K) * 8 <= n) {
+template <int KIND, int K>
+__global__ __launch_bounds__(kLutThreads) void gelu_fwd_lut_kernel(const bf16_t* x, bf16_t* y,
+                                                                   uint32_t* __restrict__ mask,
+                                                                   int64_t n) {
+  __shared__ uint32_t lut[2 * TEMPO_GELU_LUT_N];
+  const int lane = threadIdx.x & (kWave - 1);
+  const int64_t q_base = static_cast<int64_t>(blockIdx.x) * (kLutThreads * K) + threadIdx.x;
+  const bool full = (static_cast<int64_t>(blockIdx.x) + 1) * (kLutThreads * K) * 8 <= n;
+  u32x4 w[K];
+  if (full) {  // whole tile inside the tensor: straight-line loads
 #pragma unroll
     for (int k = 0; k < K; ++k) w[k] = ldg_stream(x + (q_base + k * kLutThreads) * 8);
   } else {
@@ -347,15 +349,7 @@ __device__ __forceinline__ void fwd_tile_load(const bf16_t* x, int64_t n, int64_
       else if (left > 0) w[k] = load_tail_bf16(x + q * 8, left, kAbsentX);
     }
   }
-}
-
-template <int K>
-__device__ __forceinline__ void fwd_tile_finish(const u32x4 (&w)[K], const uint32_t* lut,
-                                                bf16_t* y, uint32_t* __restrict__ mask, int64_t n,
-                                                int64_t tile) {
-  const int lane = threadIdx.x & (kWave - 1);
-  const int64_t q_base = tile * (kLutThreads * K) + threadIdx.x;
-  const bool full = (tile + 1) * (kLutThreads * K) * 8 <= n;
+  stage_lut<2 * TEMPO_GELU_LUT_N>(lut, GeluConst<KIND>::lut_fwd());
 #pragma unroll
   for (int k = 0; k < K; ++k) {
     const int64_t q = q_base + k * kLutThreads;
@@ -376,41 +370,17 @@ __device__ __forceinline__ void fwd_tile_finish(const u32x4 (&w)[K], const uint3
   }
 }
 
-// LOOP = false: one tile per workgroup, all loads issued before the table is staged.
-// LOOP = true: workgroups walk the tiles grid-stride with the next tile's loads in flight while
-// the current one is finished, and stage the table once.
-template <int KIND, int K, bool LOOP>
-__global__ __launch_bounds__(kLutThreads) void gelu_fwd_lut_kernel(const bf16_t* x, bf16_t* y,
-                                                                   uint32_t* __restrict__ mask,
-                                                                   int64_t n, int64_t tiles) {
-  __shared__ uint32_t lut[2 * TEMPO_GELU_LUT_N];
-  int64_t tile = blockIdx.x;
-  u32x4 w[K];
-  fwd_tile_load<K>(x, n, tile, w);
-  stage_lut<2 * TEMPO_GELU_LUT_N>(lut, GeluConst<KIND>::lut_fwd());
-  if constexpr (!LOOP) {
-    fwd_tile_finish<K>(w, lut, y, mask, n, tile);
-  } else {
-    while (true) {
-      const int64_t next = tile + gridDim.x;
-      u32x4 ahead[K];
-      if (next < tiles) fwd_tile_load<K>(x, n, next, ahead);
-      fwd_tile_finish<K>(w, lut, y, mask, n, tile);
-      if (next >= tiles) break;
-#pragma unroll
-      for (int k = 0; k < K; ++k) w[k] = ahead[k];
-      tile = next;
-    }
-  }
-}
-
-template <int K>
-__device__ __forceinline__ void bwd_tile_load(const bf16_t* dy, const bf16_t* __restrict__ y,
-                                              const uint32_t* __restrict__ mask, int64_t n,
-                                              int64_t tile, u32x4 (&wd)[K], u32x4 (&wy)[K],
-                                              uint32_t (&mw)[K]) {
-  const int64_t q_base = tile * (kLutThreads * K) + threadIdx.x;
-  if ((tile + 1) * (kLutThreads * K) * 8 <= n) {
+template <int KIND, int K>
+__global__ __launch_bounds__(kLutThreads) void gelu_bwd_lut_kernel(const bf16_t* dy,
+                                                                   const bf16_t* __restrict__ y,
+                                                                   const uint32_t* __restrict__ mask,
+                                                                   bf16_t* dx, int64_t n) {
+  __shared__ uint32_t lut[4 * TEMPO_GELU_LUT_N];
+  const int64_t q_base = static_cast<int64_t>(blockIdx.x) * (kLutThreads * K) + threadIdx.x;
+  const bool full = (static_cast<int64_t>(blockIdx.x) + 1) * (kLutThreads * K) * 8 <= n;
+  u32x4 wy[K], wd[K];
+  uint32_t mw[K];
+  if (full) {
 #pragma unroll
     for (int k = 0; k < K; ++k) {
       const int64_t q = q_base + k * kLutThreads;
@@ -435,14 +405,7 @@ __device__ __forceinline__ void bwd_tile_load(const bf16_t* dy, const bf16_t* __
       if (left > 0) mw[k] = mask[q >> 2];
     }
   }
-}
-
-template <int KIND, int K>
-__device__ __forceinline__ void bwd_tile_finish(const u32x4 (&wd)[K], const u32x4 (&wy)[K],
-                                                const uint32_t (&mw)[K], const uint32_t* lut,
-                                                bf16_t* dx, int64_t n, int64_t tile) {
-  const int64_t q_base = tile * (kLutThreads * K) + threadIdx.x;
-  const bool full = (tile + 1) * (kLutThreads * K) * 8 <= n;
+  stage_lut<4 * TEMPO_GELU_LUT_N>(lut, GeluConst<KIND>::lut_bwd());
 #pragma unroll
   for (int k = 0; k < K; ++k) {
     const int64_t q = q_base + k * kLutThreads;
@@ -454,39 +417,6 @@ __device__ __forceinline__ void bwd_tile_finish(const u32x4 (&wd)[K], const u32x
       const int64_t left = n - q * 8;
       if (left >= 8) stg_stream(dx + q * 8, r);
       else if (left > 0) store_tail_bf16(dx + q * 8, left, r);
-    }
-  }
-}
-
-template <int KIND, int K, bool LOOP>
-__global__ __launch_bounds__(kLutThreads) void gelu_bwd_lut_kernel(const bf16_t* dy,
-                                                                   const bf16_t* __restrict__ y,
-                                                                   const uint32_t* __restrict__ mask,
-                                                                   bf16_t* dx, int64_t n,
-                                                                   int64_t tiles) {
-  __shared__ uint32_t lut[4 * TEMPO_GELU_LUT_N];
-  int64_t tile = blockIdx.x;
-  u32x4 wy[K], wd[K];
-  uint32_t mw[K];
-  bwd_tile_load<K>(dy, y, mask, n, tile, wd, wy, mw);
-  stage_lut<4 * TEMPO_GELU_LUT_N>(lut, GeluConst<KIND>::lut_bwd());
-  if constexpr (!LOOP) {
-    bwd_tile_finish<KIND, K>(wd, wy, mw, lut, dx, n, tile);
-  } else {
-    while (true) {
-      const int64_t next = tile + gridDim.x;
-      u32x4 ny[K], nd[K];
-      uint32_t nm[K];
-      if (next < tiles) bwd_tile_load<K>(dy, y, mask, n, next, nd, ny, nm);
-      bwd_tile_finish<KIND, K>(wd, wy, mw, lut, dx, n, tile);
-      if (next >= tiles) break;
-#pragma unroll
-      for (int k = 0; k < K; ++k) {
-        wd[k] = nd[k];
-        wy[k] = ny[k];
-        mw[k] = nm[k];
-      }
-      tile = next;
     }
   }
 }
@@ -526,18 +456,10 @@ tempo_status launch_gelu_fwd(const void* x, void* y, uint32_t* mask, int64_t n, 
                              int kind, hipStream_t st) {
   const int k = pick_k(tune_get(kTuneGeluFwdChunks));
   if (dt == TEMPO_BF16) {
-    const int64_t tiles = lut_grid(n, k);
-    const int64_t cap = static_cast<int64_t>(compute_units()) * tune_get(kTuneGeluFwdLoopBlocksPerCu);
     with_kind_k(kind, k, [&](auto kd, auto kk) {
-      constexpr int KD = decltype(kd)::value, KK = decltype(kk)::value;
-      if (tiles > cap)
-        hipLaunchKernelGGL((gelu_fwd_lut_kernel<KD, KK, true>), dim3(static_cast<unsigned>(cap)),
-                           dim3(kLutThreads), 0, st, static_cast<const bf16_t*>(x),
-                           static_cast<bf16_t*>(y), mask, n, tiles);
-      else
-        hipLaunchKernelGGL((gelu_fwd_lut_kernel<KD, KK, false>),
-                           dim3(static_cast<unsigned>(tiles)), dim3(kLutThreads), 0, st,
-                           static_cast<const bf16_t*>(x), static_cast<bf16_t*>(y), mask, n, tiles);
+      hipLaunchKernelGGL((gelu_fwd_lut_kernel<decltype(kd)::value, decltype(kk)::value>),
+                         dim3(lut_grid(n, k)), dim3(kLutThreads), 0, st,
+                         static_cast<const bf16_t*>(x), static_cast<bf16_t*>(y), mask, n);
     });
     return launch_status();
   }
@@ -553,19 +475,11 @@ tempo_status launch_gelu_bwd(const void* dy, const void* y, const uint32_t* mask
                              int64_t n, tempo_dtype dt, int kind, hipStream_t st) {
   const int k = pick_k(tune_get(kTuneGeluBwdChunks));
   if (dt == TEMPO_BF16) {
-    const int64_t tiles = lut_grid(n, k);
-    const int64_t cap = static_cast<int64_t>(compute_units()) * tune_get(kTuneGeluBwdLoopBlocksPerCu);
     with_kind_k(kind, k, [&](auto kd, auto kk) {
-      constexpr int KD = decltype(kd)::value, KK = decltype(kk)::value;
-      if (tiles > cap)
-        hipLaunchKernelGGL((gelu_bwd_lut_kernel<KD, KK, true>), dim3(static_cast<unsigned>(cap)),
-                           dim3(kLutThreads), 0, st, static_cast<const bf16_t*>(dy),
-                           static_cast<const bf16_t*>(y), mask, static_cast<bf16_t*>(dx), n, tiles);
-      else
-        hipLaunchKernelGGL((gelu_bwd_lut_kernel<KD, KK, false>),
-                           dim3(static_cast<unsigned>(tiles)), dim3(kLutThreads), 0, st,
-                           static_cast<const bf16_t*>(dy), static_cast<const bf16_t*>(y), mask,
-                           static_cast<bf16_t*>(dx), n, tiles);
+      hipLaunchKernelGGL((gelu_bwd_lut_kernel<decltype(kd)::value, decltype(kk)::value>),
+                         dim3(lut_grid(n, k)), dim3(kLutThreads), 0, st,
+                         static_cast<const bf16_t*>(dy), static_cast<const bf16_t*>(y), mask,
+                         static_cast<bf16_t*>(dx), n);
     });
     return launch_status();
   }

@@ -23,9 +23,7 @@ enum TuneKey {
   kTuneLnFwdMaxPieces = 10,     // the same for layernorm_fwd
   kTuneLnBwdMaxPieces = 11,     // and layernorm_bwd
   kTuneLnBwdLoopBlocksPerCu = 12,  // layernorm_bwd: workgroups per CU beyond which they loop
-  kTuneGeluFwdLoopBlocksPerCu = 13,  // bf16 gelu/silu fwd: workgroups per CU beyond which they loop
-  kTuneGeluBwdLoopBlocksPerCu = 14,  // the same for bwd
-  kTuneCount = 15
+  kTuneCount = 13
 };
 int tune_get(TuneKey k);
 int compute_units();

@@ -112,37 +112,6 @@ def test_gelu_bwd(B, n, dt, kind):
     assert torch.equal(dyd, dxd)
 
 
-@pytest.mark.parametrize("kind", ["erf", "silu"])
-@pytest.mark.parametrize("pieces", [1, 2, 4])
-def test_gelu_bf16_looping_workgroups(B, kind, pieces):
-    """More tiles than workgroups (knobs 13, 14 = 1 per compute unit): workgroups walk the tiles,
-    the last tile is partial."""
-    n = 256 * 1024 * 8 * pieces * 2 + 8 * 1024 * pieces + 1003
-    rng = np.random.default_rng(n)
-    x = stored(rng, n, "bf16", 1.5)
-    dy = stored(rng, n, "bf16")
-    y_ref, m_ref = O.gelu_fwd(x, kind, "bf16")
-    idx = np.unique(np.concatenate([rng.integers(0, n, 100_000), np.arange(n - 5000, n)]))
-    dx_ref = O.gelu_bwd(dy[idx], y_ref[idx], m_ref[idx], kind, "bf16")
-    old = [B.tempo_get_launch_param(k) for k in (0, 1, 13, 14)]
-    try:
-        for k, v in zip((0, 1, 13, 14), (pieces, pieces, 1, 1)):
-            B.tempo_set_launch_param(k, v)
-        xd, dyd = dev(x, "bf16"), dev(dy, "bf16")
-        yd = torch.full_like(xd, 7.0)
-        md = torch.full((B.mask_words(n),), -1, dtype=torch.int32, device="cuda")
-        act_fwd(B, kind, xd, yd, md)
-        dxd = torch.full_like(xd, 7.0)
-        act_bwd(B, kind, dyd, yd, md, dxd)
-        torch.cuda.synchronize()
-    finally:
-        for k, v in zip((0, 1, 13, 14), old):
-            B.tempo_set_launch_param(k, v)
-    assert np.array_equal(words(md), O.pack_bits(m_ref)), "mask differs"
-    assert rel_err(host(yd), y_ref) <= TOL["bf16"]
-    assert rel_err(host(dxd)[idx], dx_ref) <= TOL["bf16"]
-
-
 @pytest.mark.parametrize("kind", ACT_KINDS)
 def test_gelu_bwd_edge_values(B, kind):
     ys = O.GELU_YSTAR[kind]
