@@ -218,15 +218,17 @@ __global__ __launch_bounds__(kThreads) void gelu_bwd_kernel(const float* dy,  //
 // 16 KiB forward, 32 KiB backward.  Per element this leaves a handful of integer ops, one
 // ds_read_b32 and one multiply, which keeps the vector ALU far below the memory time (the
 // cubic path above costs ~40 VALU ops per element, more than a bf16 element's share of HBM
-// time).  Workgroups of 1024 lanes own contiguous tiles of 1024*K chunks.
-constexpr int kLutThreads = 1024;
+// time).  Workgroups of 1024 lanes own contiguous tiles of K pieces
+// per lane.
+constexpr int kLutFwdThreads = 1024;  // 512 is 2-3 % faster on 140+ MB tensors but 20 % slower on 70 MB
+constexpr int kLutBwdThreads = 1024;  // 512 is 2-5 % slower
 
-template <int WORDS>
+template <int WORDS, int THREADS>
 __device__ __forceinline__ void stage_lut(uint32_t* lds, const uint32_t* src) {
-  static_assert(WORDS % (4 * kLutThreads) == 0, "whole 16-byte pieces per lane");
+  static_assert(WORDS % (4 * THREADS) == 0, "whole 16-byte pieces per lane");
 #pragma unroll
-  for (int i = 0; i < WORDS / (4 * kLutThreads); ++i) {
-    const int j = (i * kLutThreads + threadIdx.x) * 4;
+  for (int i = 0; i < WORDS / (4 * THREADS); ++i) {
+    const int j = (i * THREADS + threadIdx.x) * 4;
     *reinterpret_cast<u32x4*>(lds + j) = *reinterpret_cast<const u32x4*>(src + j);
   }
   __syncthreads();
@@ -328,31 +330,31 @@ __device__ __forceinline__ void store_tail_bf16(bf16_t* p, int64_t left, const u
 constexpr uint32_t kAbsentX = 0xF149F149u;  // two bf16 of about -2.5e30: mask bit 0
 
 template <int KIND, int K>
-__global__ __launch_bounds__(kLutThreads) void gelu_fwd_lut_kernel(const bf16_t* x, bf16_t* y,
+__global__ __launch_bounds__(kLutFwdThreads) void gelu_fwd_lut_kernel(const bf16_t* x, bf16_t* y,
                                                                    uint32_t* __restrict__ mask,
                                                                    int64_t n) {
   __shared__ uint32_t lut[2 * TEMPO_GELU_LUT_N];
   const int lane = threadIdx.x & (kWave - 1);
-  const int64_t q_base = static_cast<int64_t>(blockIdx.x) * (kLutThreads * K) + threadIdx.x;
-  const bool full = (static_cast<int64_t>(blockIdx.x) + 1) * (kLutThreads * K) * 8 <= n;
+  const int64_t q_base = static_cast<int64_t>(blockIdx.x) * (kLutFwdThreads * K) + threadIdx.x;
+  const bool full = (static_cast<int64_t>(blockIdx.x) + 1) * (kLutFwdThreads * K) * 8 <= n;
   u32x4 w[K];
   if (full) {  // whole tile inside the tensor: straight-line loads
 #pragma unroll
-    for (int k = 0; k < K; ++k) w[k] = ldg_stream(x + (q_base + k * kLutThreads) * 8);
+    for (int k = 0; k < K; ++k) w[k] = ldg_stream(x + (q_base + k * kLutFwdThreads) * 8);
   } else {
 #pragma unroll
     for (int k = 0; k < K; ++k) {
-      const int64_t q = q_base + k * kLutThreads;
+      const int64_t q = q_base + k * kLutFwdThreads;
       const int64_t left = n - q * 8;
       w[k] = u32x4{kAbsentX, kAbsentX, kAbsentX, kAbsentX};
       if (left >= 8) w[k] = ldg_stream(x + q * 8);
       else if (left > 0) w[k] = load_tail_bf16(x + q * 8, left, kAbsentX);
     }
   }
-  stage_lut<2 * TEMPO_GELU_LUT_N>(lut, GeluConst<KIND>::lut_fwd());
+  stage_lut<2 * TEMPO_GELU_LUT_N, kLutFwdThreads>(lut, GeluConst<KIND>::lut_fwd());
 #pragma unroll
   for (int k = 0; k < K; ++k) {
-    const int64_t q = q_base + k * kLutThreads;
+    const int64_t q = q_base + k * kLutFwdThreads;
     u32x4 yw;
     uint32_t byte;
     gelu_fwd_lut_chunk(w[k], lut, yw, byte);
@@ -371,19 +373,19 @@ __global__ __launch_bounds__(kLutThreads) void gelu_fwd_lut_kernel(const bf16_t*
 }
 
 template <int KIND, int K>
-__global__ __launch_bounds__(kLutThreads) void gelu_bwd_lut_kernel(const bf16_t* dy,
+__global__ __launch_bounds__(kLutBwdThreads) void gelu_bwd_lut_kernel(const bf16_t* dy,
                                                                    const bf16_t* __restrict__ y,
                                                                    const uint32_t* __restrict__ mask,
                                                                    bf16_t* dx, int64_t n) {
   __shared__ uint32_t lut[4 * TEMPO_GELU_LUT_N];
-  const int64_t q_base = static_cast<int64_t>(blockIdx.x) * (kLutThreads * K) + threadIdx.x;
-  const bool full = (static_cast<int64_t>(blockIdx.x) + 1) * (kLutThreads * K) * 8 <= n;
+  const int64_t q_base = static_cast<int64_t>(blockIdx.x) * (kLutBwdThreads * K) + threadIdx.x;
+  const bool full = (static_cast<int64_t>(blockIdx.x) + 1) * (kLutBwdThreads * K) * 8 <= n;
   u32x4 wy[K], wd[K];
   uint32_t mw[K];
   if (full) {
 #pragma unroll
     for (int k = 0; k < K; ++k) {
-      const int64_t q = q_base + k * kLutThreads;
+      const int64_t q = q_base + k * kLutBwdThreads;
       wd[k] = ldg_stream(dy + q * 8);
       wy[k] = ldg_stream(y + q * 8);
       mw[k] = __builtin_nontemporal_load(mask + (q >> 2));
@@ -391,7 +393,7 @@ __global__ __launch_bounds__(kLutThreads) void gelu_bwd_lut_kernel(const bf16_t*
   } else {
 #pragma unroll
     for (int k = 0; k < K; ++k) {
-      const int64_t q = q_base + k * kLutThreads;
+      const int64_t q = q_base + k * kLutBwdThreads;
       const int64_t left = n - q * 8;
       wy[k] = wd[k] = u32x4{0u, 0u, 0u, 0u};
       mw[k] = 0;
@@ -405,10 +407,10 @@ __global__ __launch_bounds__(kLutThreads) void gelu_bwd_lut_kernel(const bf16_t*
       if (left > 0) mw[k] = mask[q >> 2];
     }
   }
-  stage_lut<4 * TEMPO_GELU_LUT_N>(lut, GeluConst<KIND>::lut_bwd());
+  stage_lut<4 * TEMPO_GELU_LUT_N, kLutBwdThreads>(lut, GeluConst<KIND>::lut_bwd());
 #pragma unroll
   for (int k = 0; k < K; ++k) {
-    const int64_t q = q_base + k * kLutThreads;
+    const int64_t q = q_base + k * kLutBwdThreads;
     const uint32_t byte = mw[k] >> (8 * static_cast<int>(q & 3));
     const u32x4 r = gelu_bwd_lut_chunk<GeluConst<KIND>::kLutLeftShift>(wy[k], wd[k], byte, lut);
     if (full) {
@@ -421,9 +423,9 @@ __global__ __launch_bounds__(kLutThreads) void gelu_bwd_lut_kernel(const bf16_t*
   }
 }
 
-int lut_grid(int64_t n, int k) {
+int lut_grid(int64_t n, int k, int threads) {
   const int64_t n_chunks = (n + 7) / 8;
-  const int64_t per_block = static_cast<int64_t>(kLutThreads) * k;
+  const int64_t per_block = static_cast<int64_t>(threads) * k;
   return static_cast<int>((n_chunks + per_block - 1) / per_block);
 }
 
@@ -458,7 +460,7 @@ tempo_status launch_gelu_fwd(const void* x, void* y, uint32_t* mask, int64_t n, 
   if (dt == TEMPO_BF16) {
     with_kind_k(kind, k, [&](auto kd, auto kk) {
       hipLaunchKernelGGL((gelu_fwd_lut_kernel<decltype(kd)::value, decltype(kk)::value>),
-                         dim3(lut_grid(n, k)), dim3(kLutThreads), 0, st,
+                         dim3(lut_grid(n, k, kLutFwdThreads)), dim3(kLutFwdThreads), 0, st,
                          static_cast<const bf16_t*>(x), static_cast<bf16_t*>(y), mask, n);
     });
     return launch_status();
@@ -477,7 +479,7 @@ tempo_status launch_gelu_bwd(const void* dy, const void* y, const uint32_t* mask
   if (dt == TEMPO_BF16) {
     with_kind_k(kind, k, [&](auto kd, auto kk) {
       hipLaunchKernelGGL((gelu_bwd_lut_kernel<decltype(kd)::value, decltype(kk)::value>),
-                         dim3(lut_grid(n, k)), dim3(kLutThreads), 0, st,
+                         dim3(lut_grid(n, k, kLutBwdThreads)), dim3(kLutBwdThreads), 0, st,
                          static_cast<const bf16_t*>(dy), static_cast<const bf16_t*>(y), mask,
                          static_cast<bf16_t*>(dx), n);
     });
