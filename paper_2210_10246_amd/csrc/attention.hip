@@ -223,6 +223,7 @@ __global__ __launch_bounds__(kThreads) void attn_fwd_kernel(
 #pragma unroll
       for (int c = 0; c < CH; ++c) {
         const int col0 = (c * LANES + t) * V;
+        if constexpr (CH == 1) raw[r][c].a = Store<T>::neg_inf_piece();  // see below
         if (col0 < limit[r]) raw[r][c].load(sr + col0);
       }
     }
@@ -235,12 +236,17 @@ __global__ __launch_bounds__(kThreads) void attn_fwd_kernel(
       const int64_t row0 = row_offset(static_cast<uint32_t>(slice) * Sq + i0 + r * kGroups, Sk);
       float v[CH][V];
       float mx = -INFINITY;
+      // One piece per lane: the lanes of a masked piece cannot save time by idling (their wave
+      // runs on for the others), so a piece that was not loaded holds -inf and goes through the
+      // same straight-line code, which gives 0 for it.  Several pieces per lane: a masked piece
+      // is skipped, which for a causal mask spares whole waves half of their work.
+      constexpr bool kSkip = CH > 1;
 #pragma unroll
       for (int c = 0; c < CH; ++c) {
         const int col0 = (c * LANES + t) * V;
-        if (col0 < limit[r]) {
+        if (!kSkip || col0 < limit[r]) {
           raw[r][c].unpack(v[c]);
-          if (col0 + V > limit[r]) {  // the piece the limit falls into
+          if (col0 < limit[r] && col0 + V > limit[r]) {  // the piece the limit falls into
 #pragma unroll
             for (int k = 0; k < V; ++k) v[c][k] = (col0 + k < limit[r]) ? v[c][k] : -INFINITY;
           }
@@ -254,7 +260,7 @@ __global__ __launch_bounds__(kThreads) void attn_fwd_kernel(
 #pragma unroll
       for (int c = 0; c < CH; ++c) {
         const int col0 = (c * LANES + t) * V;
-        if (col0 < limit[r]) {
+        if (!kSkip || col0 < limit[r]) {
 #pragma unroll
           for (int k = 0; k < V; ++k) {
             const float e = __builtin_amdgcn_exp2f(fmaf(v[c][k], kLog2e, -shift));

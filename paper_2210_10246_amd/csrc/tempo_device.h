@@ -57,6 +57,9 @@ struct Store<float> {
   __device__ static __forceinline__ u32x4 pack(const float (&v)[4]) {
     return u32x4{as_u32(v[0]), as_u32(v[1]), as_u32(v[2]), as_u32(v[3])};
   }
+  __device__ static __forceinline__ u32x4 neg_inf_piece() {
+    return u32x4{0xFF800000u, 0xFF800000u, 0xFF800000u, 0xFF800000u};
+  }
 };
 
 template <>
@@ -78,6 +81,9 @@ struct Store<bf16_t> {
   __device__ static __forceinline__ u32x4 pack(const float (&v)[8]) {
     return u32x4{pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3]), pack_bf16(v[4], v[5]),
                  pack_bf16(v[6], v[7])};
+  }
+  __device__ static __forceinline__ u32x4 neg_inf_piece() {
+    return u32x4{0xFF80FF80u, 0xFF80FF80u, 0xFF80FF80u, 0xFF80FF80u};
   }
 };
 
