@@ -48,8 +48,20 @@ def parse():
     return ap.parse_args()
 
 
-def algorithmic_bytes(cfg):
-    """Bytes each kernel must move per launch (reads of inputs + writes of outputs)."""
+def unmasked_fraction(cfg, key_len=None):
+    """Share of the score entries the attention forward has to read: masked entries (padding
+    beyond key_len[b], or above the causal diagonal) are never needed."""
+    if cfg.mask == "causal":
+        return (cfg.seq + 1) / (2 * cfg.seq)
+    if cfg.mask == "padding" and key_len is not None:
+        return float(sum(min(max(int(k), 0), cfg.seq) for k in key_len)) / (len(key_len) * cfg.seq)
+    return 1.0
+
+
+def algorithmic_bytes(cfg, key_len=None):
+    """Bytes each kernel must move per launch (reads of inputs + writes of outputs).  The
+    attention forward counts only the unmasked score reads (all writes: dense consumers expect
+    the zeros); "attn_fwd_dense" is the same with every score counted as read."""
     e = cfg.elem_bytes
     n_g = cfg.tokens * cfg.ffn
     N, M = cfg.tokens, cfg.hidden
@@ -59,7 +71,8 @@ def algorithmic_bytes(cfg):
         "gelu_bwd": n_g * 3 * e + n_g / 8,
         "layernorm_fwd": N * M * 2 * e + 4 * N + 8 * M,
         "layernorm_bwd": N * M * 3 * e + 4 * N + 16 * M,
-        "attn_fwd": n_a * 3 * e + n_a / 8,
+        "attn_fwd": n_a * (2 + unmasked_fraction(cfg, key_len)) * e + n_a / 8,
+        "attn_fwd_dense": n_a * 3 * e + n_a / 8,
         "attn_bwd": n_a * 4 * e + n_a / 8,
         # variant outside the step: backward that draws the keep bits again, no mask read
         "attn_bwd_regen": n_a * 4 * e,
@@ -119,12 +132,11 @@ def main():
     N, M = cfg.tokens, cfg.hidden
     shape_a = (cfg.batch, cfg.heads, cfg.seq, cfg.seq)
     n_g, n_a = N * cfg.ffn, int(np.prod(shape_a))
-    algo = algorithmic_bytes(cfg)
-
     # ---- seeded inputs, generated once on the host and copied into every rotating set
     g_in = W.gelu_inputs(cfg)
     l_in = W.layernorm_inputs(cfg)
     a_in = W.attention_inputs(cfg)
+    algo = algorithmic_bytes(cfg, None if a_in["key_len"] is None else a_in["key_len"].tolist())
     key_len = None if a_in["key_len"] is None else a_in["key_len"].to(dev)
     gamma, beta = l_in["gamma"].to(dev), l_in["beta"].to(dev)
     gx0, gdy0 = g_in["x"].to(dev), g_in["dy"].to(dev)
@@ -268,6 +280,9 @@ def main():
             per_kernel[name] = {"us": round(us, 2), "GB/s": round(gbs, 1),
                                 "frac_of_peak": round(gbs / HBM_PEAK_GBS, 4),
                                 "bytes": int(algo[name]), "buffer_sets": bufs.n}
+            if name + "_dense" in algo:   # every input element counted as read
+                per_kernel[name]["dense_bytes"] = int(algo[name + "_dense"])
+                per_kernel[name]["dense_GB/s"] = round(algo[name + "_dense"] / us * 1e-3, 1)
 
     # ---- what a plain 16-byte copy reaches on this GPU (read + write bytes per second): at
     # 256 MiB, and moving as many bytes as the slowest kernel of the step moves per launch
@@ -307,6 +322,10 @@ def main():
             copy_same = {"as_many_bytes_as": dom, "bytes": 2 * nb, "us": round(us, 2),
                          "GB/s": round(gbs, 1)}
 
+    if copy_gbs:
+        for v in per_kernel.values():
+            v["frac_of_copy_kernel"] = round(v["GB/s"] / copy_gbs, 4)
+
     value = step_bytes / (ms_per_step * 1e-3) * 1e-9 if ms_per_step == ms_per_step else None
     roofline = None
     if per_kernel:
@@ -323,6 +342,19 @@ def main():
         cpu = cpu_baseline(cfg, algo)
 
     saved = activation_bytes_saved(cfg)
+    # the same from the buffers this run actually used: what a standard layer keeps for backward
+    # (its input, and for attention scores, P, Out and a byte mask) against what these kernels
+    # keep (mask bits, rstd, P and mask bits); the outputs y are kept by both
+    nbytes = lambda t: t.numel() * t.element_size()
+    g0, l0, a0 = gelu_b.sets[0], ln_b.sets[0], attn_b.sets[0]
+    measured = {
+        "gelu": (nbytes(g0["x"]) - nbytes(g0["m"])) // N,
+        "layernorm": 2 * (nbytes(l0["x"]) + nbytes(l0["rstd"])) // N,   # x and mean, twice
+        "attention": (nbytes(a0["s"]) + nbytes(a0["out"]) + n_a - nbytes(a0["k"])) // N,
+    }
+    device = {"name": torch.cuda.get_device_name(0),
+              "compute_units": torch.cuda.get_device_properties(0).multi_processor_count,
+              "clocks": device_clocks()}
     line = {
         "metric": METRIC, "value": None if value is None else round(value, 1), "unit": "GB/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -336,14 +368,32 @@ def main():
                    "launch": "eager" if args.no_graph else "HIP graph replay (one graph per buffer phase)",
                    "algorithmic_bytes_per_step": int(step_bytes)},
         "frac_of_hbm_peak": None if value is None else round(value / HBM_PEAK_GBS, 4),
+        # the same step with every score of the attention forward counted as read
+        "value_dense_count": None if value is None else round(
+            (step_bytes - algo["attn_fwd"] + algo["attn_fwd_dense"]) / (ms_per_step * 1e-3) * 1e-9, 1),
         "copy_kernel_GB/s": copy_gbs,
         "copy_kernel_same_bytes": copy_same,
         "roofline": roofline,
         "cpu_baseline": cpu,
         "kernels": per_kernel,
-        "activation_bytes_saved_per_token": {**saved, "total": sum(saved.values())},
+        "activation_bytes_saved_per_token": {**saved, "total": sum(saved.values()),
+                                             "from_buffers": measured},
+        "device": device,
     }
     print(json.dumps(line))
+
+
+def device_clocks():
+    """Clock / power state as rocm-smi reports it (nothing is pinned by this benchmark)."""
+    import subprocess
+    try:
+        r = subprocess.run(["rocm-smi", "--showclocks", "--showperflevel", "--showpower"],
+                           capture_output=True, text=True, timeout=20)
+        keep = [l.split(":", 1)[1].strip() if l.startswith("GPU[") else l.strip()
+                for l in r.stdout.splitlines() if any(k in l for k in ("clock", "Performance", "Power"))]
+        return keep[:12] or None
+    except Exception:
+        return None
 
 
 def measured_traffic(cfg, kernel):

@@ -27,13 +27,24 @@ def test_more_than_one_gpu_is_refused_with_a_message():
 def test_algorithmic_bytes_per_element(index):
     cfg = W.config(index)
     e = cfg.elem_bytes
-    a = bench.algorithmic_bytes(cfg)
+    key_len = W.attention_inputs(cfg)["key_len"] if index in (0, 1) else None
+    key_len = None if key_len is None else key_len.tolist()
+    a = bench.algorithmic_bytes(cfg, key_len)
     n_g = cfg.tokens * cfg.ffn
     n_a = cfg.batch * cfg.heads * cfg.seq * cfg.seq
     # reads of every input and writes of every output, masks at one bit per element
     assert a["gelu_fwd"] == n_g * (2 * e + 0.125)
     assert a["gelu_bwd"] == n_g * (3 * e + 0.125)
-    assert a["attn_fwd"] == n_a * (3 * e + 0.125)
+    assert a["attn_fwd_dense"] == n_a * (3 * e + 0.125)
+    # masked scores are not counted as read: padding beyond key_len[b], or above the diagonal
+    if cfg.mask == "causal":
+        frac = (cfg.seq + 1) / (2 * cfg.seq)
+    elif key_len is not None:
+        frac = sum(key_len) / (len(key_len) * cfg.seq)
+        assert 0.5 <= frac < 1.0
+    else:
+        frac = 1.0
+    assert a["attn_fwd"] == pytest.approx(n_a * ((2 + frac) * e + 0.125), rel=1e-12)
     assert a["attn_bwd"] == n_a * (4 * e + 0.125)
     assert a["attn_bwd_regen"] == n_a * 4 * e
     assert a["layernorm_fwd"] == cfg.tokens * (cfg.hidden * 2 * e + 4) + 8 * cfg.hidden

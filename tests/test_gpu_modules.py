@@ -111,6 +111,41 @@ def test_encoder_layer_keeps_fewer_activation_bytes(M):
           f"saved {saved / tokens:.0f} (expected >= {0.85 * expected / tokens:.0f})")
 
 
+def test_encoder_layer_holds_less_device_memory_between_forward_and_backward(M):
+    """The same saving as the allocator sees it: bytes allocated once forward has returned
+    (output and autograd stash alive), stock layer against the memory-reduced one."""
+    torch.manual_seed(5)
+    Bn, S, H, A = 8, 128, 512, 8
+    layer = M.TempoEncoderLayer(H, A, 4 * H, p_attn=0.1, eps=1e-5).cuda().train()
+    x = torch.randn(Bn, S, H, device="cuda", requires_grad=True)
+    keep = (torch.rand(Bn, A, S, S, device="cuda") < 0.9).float()
+
+    def held(fn):
+        torch.cuda.synchronize()
+        before = torch.cuda.memory_allocated()
+        torch.cuda.reset_peak_memory_stats()
+        out = fn()
+        torch.cuda.synchronize()
+        after = torch.cuda.memory_allocated()
+        out.sum().backward()
+        torch.cuda.synchronize()
+        peak = torch.cuda.max_memory_allocated() - before
+        del out
+        return after - before, peak
+
+    held(lambda: layer(x))                       # warm the allocator and the library
+    tempo_held, tempo_peak = held(lambda: layer(x))
+    stock_held, stock_peak = held(lambda: reference_layer(layer, x, None, keep))
+    tokens, e = Bn * S, 4
+    expected = tokens * ((4 * H * e - 4 * H // 8) + 2 * H * e + A * S * e)
+    saved = stock_held - tempo_held
+    print(f"held after forward per token: stock {stock_held / tokens:.0f} B, tempo {tempo_held / tokens:.0f} B, "
+          f"saved {saved / tokens:.0f} B (expected >= {0.85 * expected / tokens:.0f}); "
+          f"peak over forward+backward: stock {stock_peak / tokens:.0f} B, tempo {tempo_peak / tokens:.0f} B")
+    assert saved >= 0.85 * expected, (stock_held, tempo_held, expected)
+    assert tempo_peak <= stock_peak
+
+
 def test_attention_core_without_stored_mask(M):
     """store_mask=False: same gradients bit for bit, and the mask leaves the stash."""
     torch.manual_seed(3)
