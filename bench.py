@@ -384,16 +384,23 @@ def main():
 
 
 def device_clocks():
-    """Clock / power state as rocm-smi reports it (nothing is pinned by this benchmark)."""
-    import subprocess
-    try:
-        r = subprocess.run(["rocm-smi", "--showclocks", "--showperflevel", "--showpower"],
-                           capture_output=True, text=True, timeout=20)
-        keep = [l.split(":", 1)[1].strip() if l.startswith("GPU[") else l.strip()
-                for l in r.stdout.splitlines() if any(k in l for k in ("clock", "Performance", "Power"))]
-        return keep[:12] or None
-    except Exception:
-        return None
+    """Clock and power state as the driver's sysfs files report it (nothing is pinned by this
+    benchmark).  Plain file reads: no child process is started from a process that uses the GPU."""
+    import glob
+    out = {}
+    for card in sorted(glob.glob("/sys/class/drm/card[0-9]*/device")):
+        for name in ("pp_dpm_sclk", "pp_dpm_mclk", "power_dpm_force_performance_level"):
+            try:
+                with open(f"{card}/{name}") as f:
+                    text = f.read().strip()
+            except OSError:
+                continue
+            lines = text.splitlines()
+            active = [l.strip() for l in lines if l.rstrip().endswith("*")]
+            out[name] = (active or lines)[:2]
+        if out:
+            break
+    return out or None
 
 
 def measured_traffic(cfg, kernel):

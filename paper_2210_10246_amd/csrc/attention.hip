@@ -514,10 +514,14 @@ Shape pick_wide_shape(int pieces, int min_lanes, int max_ch) {
   return one;
 }
 
-// Rows a lane group of the forward kernel fetches at once: 2 (if the knob allows) while a row
-// is one or two pieces per lane, else 1.  Measured on [*,*,128..1024,*] maps: 2 rows beat 1 by
-// up to 25 % in forward and lose 3-8 % in backward, which therefore always takes 1.
-int attn_rows(int ch, int tuned) { return (ch <= 2 && tuned >= 2) ? 2 : 1; }
+// Rows a lane group of the forward kernel fetches at once: 2 (if the knob allows) when a
+// bfloat16 row is exactly one piece per lane of a whole wave, else 1.  Measured in steady state
+// on rows of 128..1024 elements: 2 rows gain 5-7 % there (512 columns) and lose 3-9 % for
+// shorter rows (several rows per wave already), for two pieces per lane and for float32;
+// backward always takes 1.
+int attn_rows(int ch, int lanes, int vec, int tuned) {
+  return (vec == 8 && ch == 1 && lanes == kWave && tuned >= 2) ? 2 : 1;
+}
 
 int row_grid(int64_t rows, int lanes, int blocks_per_cu, int rows_per_group = 1) {
   const int groups = (kThreads / lanes) * rows_per_group;
@@ -625,7 +629,7 @@ tempo_status launch_attn_fwd(const void* scores, const int32_t* key_len, int cau
                             tune_get(kTuneAttnFwdMaxPieces));
   if (Sk % 8 == 0 && sh.ch != 0 && rows <= UINT32_MAX) {  // rows counted in 32 bits
     const int slices = static_cast<int>(B * A);
-    const int rr = sh.lanes > kWave ? 1 : attn_rows(sh.ch, tune_get(kTuneAttnFwdRows));
+    const int rr = sh.lanes > kWave ? 1 : attn_rows(sh.ch, sh.lanes, vec, tune_get(kTuneAttnFwdRows));
     const int rows_per_set = (kThreads / sh.lanes) * rr;
     const int64_t total_sets =
         static_cast<int64_t>(slices) * ((Sq + rows_per_set - 1) / rows_per_set);
