@@ -16,7 +16,7 @@ static std::atomic<int> g_tune[kTuneCount] = {
     {65536},  // attention bwd: workgroups per CU
     {2},      // attention fwd: rows per lane group
     {2},      // layernorm fwd: rows per lane group
-    {2},      // attention fwd: most pieces per lane of a one-wave row
+    {4},      // attention fwd: most pieces per lane of a one-wave row
     {4},      // attention bwd: the same
     {4},      // layernorm fwd: the same
     {4},      // layernorm bwd: the same
