@@ -21,6 +21,7 @@ static std::atomic<int> g_tune[kTuneCount] = {
     {4},      // layernorm fwd: the same
     {4},      // layernorm bwd: the same
     {1},      // layernorm bwd: workgroups per CU beyond which they loop with prefetch
+    {24},     // bf16 gelu/silu fwd: Mi elements from which workgroups have 512 lanes
 };
 
 int tune_get(TuneKey k) { return g_tune[k].load(std::memory_order_relaxed); }

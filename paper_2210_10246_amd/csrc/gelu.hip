@@ -220,7 +220,6 @@ __global__ __launch_bounds__(kThreads) void gelu_bwd_kernel(const float* dy,  //
 // cubic path above costs ~40 VALU ops per element, more than a bf16 element's share of HBM
 // time).  Workgroups of 1024 lanes own contiguous tiles of K pieces
 // per lane.
-constexpr int kLutFwdThreads = 1024;  // 512 is 2-3 % faster on 140+ MB tensors but 20 % slower on 70 MB
 constexpr int kLutBwdThreads = 1024;  // 512 is 2-5 % slower
 
 template <int WORDS, int THREADS>
@@ -329,32 +328,34 @@ __device__ __forceinline__ void store_tail_bf16(bf16_t* p, int64_t left, const u
 
 constexpr uint32_t kAbsentX = 0xF149F149u;  // two bf16 of about -2.5e30: mask bit 0
 
-template <int KIND, int K>
-__global__ __launch_bounds__(kLutFwdThreads) void gelu_fwd_lut_kernel(const bf16_t* x, bf16_t* y,
+// THREADS lanes per workgroup: 1024, or 512 with half the pieces per lane for large tensors
+// (2-4 % faster from 130 MB of traffic up, 20 % slower at 70 MB).
+template <int KIND, int K, int THREADS>
+__global__ __launch_bounds__(THREADS) void gelu_fwd_lut_kernel(const bf16_t* x, bf16_t* y,
                                                                    uint32_t* __restrict__ mask,
                                                                    int64_t n) {
   __shared__ uint32_t lut[2 * TEMPO_GELU_LUT_N];
   const int lane = threadIdx.x & (kWave - 1);
-  const int64_t q_base = static_cast<int64_t>(blockIdx.x) * (kLutFwdThreads * K) + threadIdx.x;
-  const bool full = (static_cast<int64_t>(blockIdx.x) + 1) * (kLutFwdThreads * K) * 8 <= n;
+  const int64_t q_base = static_cast<int64_t>(blockIdx.x) * (THREADS * K) + threadIdx.x;
+  const bool full = (static_cast<int64_t>(blockIdx.x) + 1) * (THREADS * K) * 8 <= n;
   u32x4 w[K];
   if (full) {  // whole tile inside the tensor: straight-line loads
 #pragma unroll
-    for (int k = 0; k < K; ++k) w[k] = ldg_stream(x + (q_base + k * kLutFwdThreads) * 8);
+    for (int k = 0; k < K; ++k) w[k] = ldg_stream(x + (q_base + k * THREADS) * 8);
   } else {
 #pragma unroll
     for (int k = 0; k < K; ++k) {
-      const int64_t q = q_base + k * kLutFwdThreads;
+      const int64_t q = q_base + k * THREADS;
       const int64_t left = n - q * 8;
       w[k] = u32x4{kAbsentX, kAbsentX, kAbsentX, kAbsentX};
       if (left >= 8) w[k] = ldg_stream(x + q * 8);
       else if (left > 0) w[k] = load_tail_bf16(x + q * 8, left, kAbsentX);
     }
   }
-  stage_lut<2 * TEMPO_GELU_LUT_N, kLutFwdThreads>(lut, GeluConst<KIND>::lut_fwd());
+  stage_lut<2 * TEMPO_GELU_LUT_N, THREADS>(lut, GeluConst<KIND>::lut_fwd());
 #pragma unroll
   for (int k = 0; k < K; ++k) {
-    const int64_t q = q_base + k * kLutFwdThreads;
+    const int64_t q = q_base + k * THREADS;
     u32x4 yw;
     uint32_t byte;
     gelu_fwd_lut_chunk(w[k], lut, yw, byte);
@@ -458,10 +459,17 @@ tempo_status launch_gelu_fwd(const void* x, void* y, uint32_t* mask, int64_t n, 
                              int kind, hipStream_t st) {
   const int k = pick_k(tune_get(kTuneGeluFwdChunks));
   if (dt == TEMPO_BF16) {
-    with_kind_k(kind, k, [&](auto kd, auto kk) {
-      hipLaunchKernelGGL((gelu_fwd_lut_kernel<decltype(kd)::value, decltype(kk)::value>),
-                         dim3(lut_grid(n, k, kLutFwdThreads)), dim3(kLutFwdThreads), 0, st,
-                         static_cast<const bf16_t*>(x), static_cast<bf16_t*>(y), mask, n);
+    // large tensors: half-size workgroups with half the pieces per lane
+    const bool small_groups = n >= tune_get(kTuneGeluFwdSmallGroupsFrom) * int64_t{1048576} && k >= 2;
+    with_kind_k(kind, small_groups ? k / 2 : k, [&](auto kd, auto kk) {
+      constexpr int KD = decltype(kd)::value, KK = decltype(kk)::value;
+      if (small_groups)
+        hipLaunchKernelGGL((gelu_fwd_lut_kernel<KD, KK, 512>), dim3(lut_grid(n, KK, 512)), dim3(512),
+                           0, st, static_cast<const bf16_t*>(x), static_cast<bf16_t*>(y), mask, n);
+      else
+        hipLaunchKernelGGL((gelu_fwd_lut_kernel<KD, KK, 1024>), dim3(lut_grid(n, KK, 1024)),
+                           dim3(1024), 0, st, static_cast<const bf16_t*>(x),
+                           static_cast<bf16_t*>(y), mask, n);
     });
     return launch_status();
   }

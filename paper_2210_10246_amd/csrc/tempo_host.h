@@ -23,7 +23,8 @@ enum TuneKey {
   kTuneLnFwdMaxPieces = 10,     // the same for layernorm_fwd
   kTuneLnBwdMaxPieces = 11,     // and layernorm_bwd
   kTuneLnBwdLoopBlocksPerCu = 12,  // layernorm_bwd: workgroups per CU beyond which they loop
-  kTuneCount = 13
+  kTuneGeluFwdSmallGroupsFrom = 13,  // bf16 gelu/silu fwd: Mi elements from which 512-lane groups
+  kTuneCount = 14
 };
 int tune_get(TuneKey k);
 int compute_units();
