@@ -620,9 +620,10 @@ tempo_status launch_layernorm_fwd(const void* x, const float* gamma, const float
 
 // Launch plan of the register-resident backward kernel.  Rows per lane group and batch (r):
 // as many as the knob allows while the packed rows stay within ~64 registers and the grid
-// keeps one workgroup per compute unit.  If that leaves more than two batches per compute
-// unit, workgroups loop with prefetch instead (half the rows per batch, since two batches are
-// then held in registers) on a grid of two workgroups per compute unit.
+// keeps one workgroup per compute unit.  If that leaves more batches than the knob's number of
+// workgroups per compute unit (default 1), workgroups loop with prefetch instead (half the rows
+// per batch, since two batches are then held in registers) on a grid of that many workgroups
+// per compute unit.
 struct BwdPlan {
   int r;
   bool loop;
