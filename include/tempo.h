@@ -5,7 +5,8 @@
  *
  * Conventions shared by every entry point
  *   Pointers   All data pointers are DEVICE pointers, owned by the caller; the library
- *              allocates nothing, keeps no state and never frees.  Every base pointer must be
+ *              allocates nothing, never frees, and keeps no state besides the process-wide
+ *              launch knobs below.  Every base pointer must be
  *              16-byte aligned (TEMPO_ERR_UNSUPPORTED otherwise).
  *   Stream     hip_stream is a hipStream_t passed as void* (NULL = the default stream).  Work
  *              is enqueued on it and the call returns without synchronising.
@@ -55,9 +56,9 @@ TEMPO_API int tempo_version(void);
 
 /*
  * Launch-shape knobs for tuning and benchmarking (process-wide, not needed for correctness):
- *   key 0 / 1: 8-element chunks per lane in gelu_fwd / gelu_bwd (1, 2 or 4);
+ *   key 0 / 1: 16-byte pieces per lane in gelu_fwd / gelu_bwd (1, 2 or 4);
  *   key 13: tensor size in Mi elements from which the bfloat16 gelu/silu forward uses workgroups
- *   of 512 lanes with half the chunks per lane (65536: never);
+ *   of 512 lanes with half the pieces per lane (65536: never);
  *   key 2, 4, 5: cap on workgroups per compute unit of layernorm_fwd, attn fwd, attn bwd
  *   (rows beyond the cap are walked in a loop);
  *   key 6, 7: rows a lane group of attn fwd / layernorm_fwd fetches at once (1 or 2);
