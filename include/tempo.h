@@ -166,6 +166,8 @@ TEMPO_API tempo_status tempo_layernorm_bwd(const void* dy, const void* y, const 
  *   g = e >> 3; Philox4x32-10 with counter (g_lo, g_hi, offset_lo, offset_hi) and key
  *   (seed_lo, seed_hi) gives words w0..w3; r = (w[(e & 7) >> 1] >> (16 (e & 1))) & 0xFFFF;
  *   kept iff r < T16, T16 = floor((1 - (double)p) 65536 + 0.5).  p == 0 keeps everything.
+ *   (The words of group g are what rocRAND's philox4x32_10 engine returns when it is seeded
+ *   with (seed, subsequence = offset, offset = 4 g).)
  *   probs may alias scores.
  */
 TEMPO_API tempo_status tempo_attn_softmax_dropout_fwd(const void* scores, const int32_t* key_len, int causal,

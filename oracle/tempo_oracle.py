@@ -23,12 +23,12 @@ What is pinned and by what (tests/test_oracle_*.py):
                       rows sum to one; shift invariance; sum dS = 0
   activation_bytes_*  the twelve percentages of App. H (Fig. 10) and the 56 % / 17 %
                       statements of Sec. 2.1
-  philox4x32_10       PARITY UNPINNED against published known-answer vectors (none are
-                      available offline).  The paper fixes only the distribution of the
-                      dropout mask (i.i.d. Bernoulli), which is pinned statistically
-                      (keep rate, bit balance, lag correlations, avalanche), together
-                      with the bijectivity of the round function (explicit inverse) and
-                      the closed forms of the two Weyl key increments.
+  philox4x32_10       rocRAND's Philox4x32-10 engine run on the host (an independent
+                      implementation; same blocks for 64-bit seeds, counters and offsets),
+                      plus the closed forms of the two Weyl key increments, the bijectivity
+                      of the round function (explicit inverse) and avalanche
+  dropout_keep        the same engine's 16-bit lanes under the threshold rule; keep rate, bit
+                      balance, lag correlations
 """
 from __future__ import annotations
 

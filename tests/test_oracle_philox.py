@@ -2,12 +2,16 @@
 
 The paper fixes only the mask's distribution (Sec. 3.3: every entry dropped with
 probability p); the generator (Philox4x32-10, Salmon et al., SC'11) is this build's
-contract.  Published known-answer vectors are not available offline, so the stream is pinned
-by what mathematics fixes: the closed forms of the Weyl key increments, the bijectivity
-of a round, a scalar big-integer evaluation of the same rounds, avalanche, and the
-statistics of the keep bits.
+contract.  The stream is pinned to an independent implementation, rocRAND's Philox4x32-10
+engine run on the host (tests/philox_rocrand_host.cpp, built by the test with hipcc's host
+pass), and by what mathematics fixes: the closed forms of the Weyl key increments, the
+bijectivity of a round, a scalar big-integer evaluation of the same rounds, avalanche, and
+the statistics of the keep bits.
 """
 import math
+import os
+import shutil
+import subprocess
 
 import numpy as np
 import pytest
@@ -15,6 +19,56 @@ import pytest
 from oracle import tempo_oracle as O
 
 M32 = 0xFFFFFFFF
+
+
+@pytest.fixture(scope="module")
+def rocrand_philox(tmp_path_factory):
+    """Path of the host program over rocRAND's engine; skipped where the ROCm toolchain or the
+    rocRAND headers are missing."""
+    hipcc = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
+    if not os.path.exists(hipcc) or not os.path.exists("/opt/rocm/include/rocrand/rocrand_philox4x32_10.h"):
+        pytest.skip("hipcc or the rocRAND headers are not installed")
+    src = os.path.join(os.path.dirname(__file__), "philox_rocrand_host.cpp")
+    exe = str(tmp_path_factory.mktemp("philox") / "philox_rocrand_host")
+    r = subprocess.run([hipcc, "--cuda-host-only", "-O1", "-o", exe, src], capture_output=True, text=True,
+                       timeout=300)
+    assert r.returncode == 0, r.stderr[-2000:]
+
+    def run(seed, subsequence, offset, count):
+        out = subprocess.run([exe, str(seed), str(subsequence), str(offset), str(count)],
+                             capture_output=True, text=True, timeout=60, check=True)
+        return np.array(out.stdout.split(), dtype=np.uint64)
+    return run
+
+
+def test_stream_equals_rocrand_engine(rocrand_philox):
+    # counter (g_lo, g_hi, offset_lo, offset_hi), key (seed_lo, seed_hi): the engine's
+    # subsequence is the upper half of the counter, its offset counts single outputs
+    rng = np.random.default_rng(2022)
+    cases = [(0, 0, 0), (1, 0, 0), (0xFFFFFFFFFFFFFFFF, 0xFFFFFFFFFFFFFFFF, (1 << 61) - 3),
+             (0x5EED0001, 0, 12345), (0x0123456789ABCDEF, 1 << 33, (1 << 32) - 2)]
+    cases += [(int(rng.integers(0, 1 << 63)) * 2 + 1, int(rng.integers(0, 1 << 63)),
+               int(rng.integers(0, 1 << 60))) for _ in range(6)]
+    for seed, offset, g in cases:
+        blocks = 5
+        ref = rocrand_philox(seed, offset, 4 * g, 4 * blocks).reshape(blocks, 4)
+        gs = np.arange(g, g + blocks, dtype=np.uint64)
+        got = O.philox4x32_10((gs & np.uint64(M32), gs >> np.uint64(32), np.uint64(offset & M32),
+                               np.uint64(offset >> 32)), (seed & M32, seed >> 32))
+        got = np.stack([np.broadcast_to(w, gs.shape) for w in got], axis=1)
+        assert np.array_equal(got, ref), (hex(seed), hex(offset), hex(g))
+
+
+def test_keep_bits_from_the_rocrand_stream(rocrand_philox):
+    # the dropout contract on top of the independent stream: element e takes 16-bit lane
+    # (e & 7) of group e >> 3 (low half of a word first) and is kept iff lane < T16
+    seed, offset, start, n = 0x5EED0000ABCDEF01, 77, 8 * 1000 + 3, 501
+    p = np.float32(0.1)
+    first, last = start >> 3, (start + n - 1) >> 3
+    wordsr = rocrand_philox(seed, offset, 4 * first, 4 * (last - first + 1))
+    lanes = np.stack([wordsr & np.uint64(0xFFFF), wordsr >> np.uint64(16)], axis=1).reshape(-1)
+    keep_ref = lanes[start - 8 * first: start - 8 * first + n] < O.keep_threshold16(p)
+    assert np.array_equal(O.dropout_keep(n, p, seed, offset, start=start), keep_ref)
 
 
 def test_weyl_constants_closed_form():
