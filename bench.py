@@ -365,7 +365,7 @@ def main():
                    "hidden": cfg.hidden, "heads": cfg.heads, "ffn": cfg.ffn, "mask": cfg.mask,
                    "dropout_p": cfg.p, "gelu": cfg.gelu_kind,
                    "step": "attn fwd, LN fwd, GELU fwd, LN fwd, LN bwd, GELU bwd, LN bwd, attn bwd",
-                   "launch": "eager" if args.no_graph else "HIP graph replay (one graph per buffer phase)",
+                   "launch": "eager" if args.no_graph else "HIP graph replay (one graph of four steps, each on its own buffer sets)",
                    "algorithmic_bytes_per_step": int(step_bytes)},
         "frac_of_hbm_peak": None if value is None else round(value / HBM_PEAK_GBS, 4),
         # the same step with every score of the attention forward counted as read
