@@ -21,7 +21,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, vendor peak
-ROTATE_BYTES = 640 << 20       # distinct bytes a kernel must touch before it sees a buffer again
+ROTATE_BYTES = 2048 << 20      # distinct bytes a kernel must touch before it sees a buffer again
 METRIC = "fwd+bwd HBM GB/s (% of peak) per layer; activation bytes saved/token"
 
 
