@@ -17,8 +17,9 @@
  *              sizes a mask ceil(n/32) words; unused bits of the last word are written 0.
  *   In place   Only the aliasing named per function is allowed; nothing else may overlap.
  *   Errors     A status code is returned; nothing is thrown and nothing aborts.
- *              INVALID_ARG: NULL required pointer, negative size, bad enum, p outside [0,1) or
- *              NaN, eps < 0 or NaN.  UNSUPPORTED: misaligned pointer.  WORKSPACE: workspace too
+ *              INVALID_ARG: NULL required pointer, negative size, a tensor of more than 2^40
+ *              elements, a row length (M, Sq, Sk) or a slice count B*A above 2^31 - 1, bad
+ *              enum, p outside [0,1) or NaN, eps < 0 or NaN.  UNSUPPORTED: misaligned pointer.  WORKSPACE: workspace too
  *              small.  LAUNCH: the HIP runtime reported an error at launch.  Sizes of zero
  *              return TEMPO_OK without launching.
  */

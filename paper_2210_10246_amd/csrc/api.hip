@@ -45,6 +45,18 @@ static bool dtype_ok(tempo_dtype dt) { return dt == TEMPO_F32 || dt == TEMPO_BF1
 static bool kind_ok(tempo_gelu_kind k) { return k == TEMPO_GELU_ERF || k == TEMPO_GELU_TANH; }
 static bool prob_ok(float p) { return p >= 0.0f && p < 1.0f; }  // false for NaN
 
+// A tensor has at most 2^40 elements (terabytes: far beyond device memory), so that no product
+// of sizes and no grid computed from one can overflow.  Sizes are known to be >= 0 here.
+constexpr int64_t kMaxElements = int64_t{1} << 40;
+static bool count_ok(int64_t a, int64_t b = 1, int64_t c = 1, int64_t d = 1) {
+  int64_t n = a;
+  for (int64_t f : {b, c, d}) {
+    if (f != 0 && n > kMaxElements / f) return false;
+    n *= f;
+  }
+  return n <= kMaxElements;
+}
+
 // Plain streaming copy, 16 bytes per lane and access: the reference point for what the memory
 // system delivers to a kernel that does nothing else, and the known-size kernel against which
 // hardware byte counters are calibrated.
@@ -102,7 +114,7 @@ tempo_status tempo_copy(const void* src, void* dst, int64_t nbytes, int blocks_p
 
 tempo_status tempo_gelu_fwd(const void* x, void* y, uint32_t* mask, int64_t n, tempo_dtype dt,
                             tempo_gelu_kind kind, void* hip_stream) {
-  if (n < 0 || !dtype_ok(dt) || !kind_ok(kind)) return TEMPO_ERR_INVALID_ARG;
+  if (n < 0 || !count_ok(n) || !dtype_ok(dt) || !kind_ok(kind)) return TEMPO_ERR_INVALID_ARG;
   if (n == 0) return TEMPO_OK;
   if (!x || !y || !mask) return TEMPO_ERR_INVALID_ARG;
   if (!aligned16(x) || !aligned16(y) || !aligned16(mask)) return TEMPO_ERR_UNSUPPORTED;
@@ -111,7 +123,7 @@ tempo_status tempo_gelu_fwd(const void* x, void* y, uint32_t* mask, int64_t n, t
 
 tempo_status tempo_gelu_bwd(const void* dy, const void* y, const uint32_t* mask, void* dx,
                             int64_t n, tempo_dtype dt, tempo_gelu_kind kind, void* hip_stream) {
-  if (n < 0 || !dtype_ok(dt) || !kind_ok(kind)) return TEMPO_ERR_INVALID_ARG;
+  if (n < 0 || !count_ok(n) || !dtype_ok(dt) || !kind_ok(kind)) return TEMPO_ERR_INVALID_ARG;
   if (n == 0) return TEMPO_OK;
   if (!dy || !y || !mask || !dx) return TEMPO_ERR_INVALID_ARG;
   if (!aligned16(dy) || !aligned16(y) || !aligned16(mask) || !aligned16(dx))
@@ -121,7 +133,7 @@ tempo_status tempo_gelu_bwd(const void* dy, const void* y, const uint32_t* mask,
 
 tempo_status tempo_silu_fwd(const void* x, void* y, uint32_t* mask, int64_t n, tempo_dtype dt,
                             void* hip_stream) {
-  if (n < 0 || !dtype_ok(dt)) return TEMPO_ERR_INVALID_ARG;
+  if (n < 0 || !count_ok(n) || !dtype_ok(dt)) return TEMPO_ERR_INVALID_ARG;
   if (n == 0) return TEMPO_OK;
   if (!x || !y || !mask) return TEMPO_ERR_INVALID_ARG;
   if (!aligned16(x) || !aligned16(y) || !aligned16(mask)) return TEMPO_ERR_UNSUPPORTED;
@@ -130,7 +142,7 @@ tempo_status tempo_silu_fwd(const void* x, void* y, uint32_t* mask, int64_t n, t
 
 tempo_status tempo_silu_bwd(const void* dy, const void* y, const uint32_t* mask, void* dx,
                             int64_t n, tempo_dtype dt, void* hip_stream) {
-  if (n < 0 || !dtype_ok(dt)) return TEMPO_ERR_INVALID_ARG;
+  if (n < 0 || !count_ok(n) || !dtype_ok(dt)) return TEMPO_ERR_INVALID_ARG;
   if (n == 0) return TEMPO_OK;
   if (!dy || !y || !mask || !dx) return TEMPO_ERR_INVALID_ARG;
   if (!aligned16(dy) || !aligned16(y) || !aligned16(mask) || !aligned16(dx))
@@ -141,7 +153,7 @@ tempo_status tempo_silu_bwd(const void* dy, const void* y, const uint32_t* mask,
 tempo_status tempo_layernorm_fwd(const void* x, const float* gamma, const float* beta, void* y,
                                  float* rstd, float* mean, int64_t N, int64_t M, float eps,
                                  tempo_dtype dt, void* hip_stream) {
-  if (N < 0 || M < 0 || !dtype_ok(dt) || !(eps >= 0.0f) || M > INT32_MAX)
+  if (N < 0 || M < 0 || !dtype_ok(dt) || !(eps >= 0.0f) || M > INT32_MAX || !count_ok(N, M))
     return TEMPO_ERR_INVALID_ARG;
   if (N == 0 || M == 0) return TEMPO_OK;
   if (!x || !gamma || !beta || !y || !rstd) return TEMPO_ERR_INVALID_ARG;
@@ -153,7 +165,7 @@ tempo_status tempo_layernorm_fwd(const void* x, const float* gamma, const float*
 }
 
 size_t tempo_layernorm_bwd_workspace_bytes(int64_t N, int64_t M) {
-  if (N <= 0 || M <= 0) return 0;
+  if (N <= 0 || M <= 0 || M > INT32_MAX || !count_ok(N, M)) return 0;
   // the larger of the two dtypes' grids, so one query serves both
   const int a = layernorm_bwd_blocks(N, M, TEMPO_F32), b = layernorm_bwd_blocks(N, M, TEMPO_BF16);
   return static_cast<size_t>(a > b ? a : b) * 2 * static_cast<size_t>(M) * sizeof(float);
@@ -163,7 +175,8 @@ tempo_status tempo_layernorm_bwd(const void* dy, const void* y, const float* gam
                                  const float* beta, const float* rstd, void* dx, float* dgamma,
                                  float* dbeta, void* workspace, size_t workspace_bytes, int64_t N,
                                  int64_t M, tempo_dtype dt, void* hip_stream) {
-  if (N < 0 || M < 0 || !dtype_ok(dt) || M > INT32_MAX) return TEMPO_ERR_INVALID_ARG;
+  if (N < 0 || M < 0 || !dtype_ok(dt) || M > INT32_MAX || !count_ok(N, M))
+    return TEMPO_ERR_INVALID_ARG;
   if (N == 0 || M == 0) return TEMPO_OK;
   if (!dy || !y || !gamma || !beta || !rstd || !dx || !dgamma || !dbeta || !workspace)
     return TEMPO_ERR_INVALID_ARG;
@@ -183,7 +196,7 @@ tempo_status tempo_attn_softmax_dropout_fwd(const void* scores, const int32_t* k
                                             uint64_t seed, uint64_t offset, tempo_dtype dt,
                                             void* hip_stream) {
   if (B < 0 || A < 0 || Sq < 0 || Sk < 0 || !dtype_ok(dt) || !prob_ok(p) || Sq > INT32_MAX ||
-      Sk > INT32_MAX)
+      Sk > INT32_MAX || !count_ok(B, A, Sq, Sk) || B * A > INT32_MAX)
     return TEMPO_ERR_INVALID_ARG;
   if (B == 0 || A == 0 || Sq == 0 || Sk == 0) return TEMPO_OK;
   if (!scores || !probs || !keep_bits) return TEMPO_ERR_INVALID_ARG;
@@ -198,7 +211,7 @@ tempo_status tempo_attn_softmax_dropout_bwd(const void* dout, const void* probs,
                                             void* out_recomputed, int64_t B, int64_t A, int64_t Sq,
                                             int64_t Sk, float p, tempo_dtype dt, void* hip_stream) {
   if (B < 0 || A < 0 || Sq < 0 || Sk < 0 || !dtype_ok(dt) || !prob_ok(p) || Sq > INT32_MAX ||
-      Sk > INT32_MAX)
+      Sk > INT32_MAX || !count_ok(B, A, Sq, Sk) || B * A > INT32_MAX)
     return TEMPO_ERR_INVALID_ARG;
   if (B == 0 || A == 0 || Sq == 0 || Sk == 0) return TEMPO_OK;
   if (!dout || !probs || !keep_bits || !dscores) return TEMPO_ERR_INVALID_ARG;
@@ -215,7 +228,7 @@ tempo_status tempo_attn_softmax_dropout_bwd_regen(const void* dout, const void* 
                                                   uint64_t seed, uint64_t offset, tempo_dtype dt,
                                                   void* hip_stream) {
   if (B < 0 || A < 0 || Sq < 0 || Sk < 0 || !dtype_ok(dt) || !prob_ok(p) || Sq > INT32_MAX ||
-      Sk > INT32_MAX)
+      Sk > INT32_MAX || !count_ok(B, A, Sq, Sk) || B * A > INT32_MAX)
     return TEMPO_ERR_INVALID_ARG;
   if (B == 0 || A == 0 || Sq == 0 || Sk == 0) return TEMPO_OK;
   if (!dout || !probs || !dscores) return TEMPO_ERR_INVALID_ARG;
@@ -227,7 +240,7 @@ tempo_status tempo_attn_softmax_dropout_bwd_regen(const void* dout, const void* 
 
 tempo_status tempo_mask_bits_to_bytes(const uint32_t* bits, uint8_t* bytes, int64_t n,
                                       void* hip_stream) {
-  if (n < 0) return TEMPO_ERR_INVALID_ARG;
+  if (n < 0 || !count_ok(n)) return TEMPO_ERR_INVALID_ARG;
   if (n == 0) return TEMPO_OK;
   if (!bits || !bytes) return TEMPO_ERR_INVALID_ARG;
   if (!aligned16(bits) || !aligned16(bytes)) return TEMPO_ERR_UNSUPPORTED;
@@ -236,7 +249,7 @@ tempo_status tempo_mask_bits_to_bytes(const uint32_t* bits, uint8_t* bytes, int6
 
 tempo_status tempo_mask_bytes_to_bits(const uint8_t* bytes, uint32_t* bits, int64_t n,
                                       void* hip_stream) {
-  if (n < 0) return TEMPO_ERR_INVALID_ARG;
+  if (n < 0 || !count_ok(n)) return TEMPO_ERR_INVALID_ARG;
   if (n == 0) return TEMPO_OK;
   if (!bits || !bytes) return TEMPO_ERR_INVALID_ARG;
   if (!aligned16(bits) || !aligned16(bytes)) return TEMPO_ERR_UNSUPPORTED;

@@ -63,6 +63,19 @@ def test_invalid_arguments_are_rejected_before_any_launch():
     assert lib.tempo_mask_bytes_to_bits(16, None, 5, None) == INVALID
     assert lib.tempo_mask_bytes_to_bits(17, 16, 5, None) == UNSUPPORTED
     assert lib.tempo_attn_softmax_dropout_fwd(16, None, 0, 16, 16, 16, 1, -1, 8, 8, 0.1, 0, 0, 0, None) == INVALID
+    # sizes whose products would overflow, or that no device memory can hold
+    big = 1 << 62
+    assert lib.tempo_gelu_fwd(16, 16, 16, (1 << 40) + 1, 0, 0, None) == INVALID
+    assert lib.tempo_silu_bwd(16, 16, 16, 16, big, 0, None) == INVALID
+    assert lib.tempo_layernorm_fwd(16, 16, 16, 16, 16, None, big, 8, 1e-5, 0, None) == INVALID
+    assert lib.tempo_layernorm_fwd(16, 16, 16, 16, 16, None, 2, 1 << 31, 1e-5, 0, None) == INVALID
+    assert lib.tempo_layernorm_bwd(16, 16, 16, 16, 16, 16, 16, 16, 16, 1 << 40, 1 << 33, 1 << 20, 0, None) == INVALID
+    assert lib.tempo_layernorm_bwd_workspace_bytes(1 << 33, 1 << 20) == 0
+    assert lib.tempo_attn_softmax_dropout_fwd(16, None, 0, 16, 16, 16, 1 << 31, 1 << 31, 8, 8, 0.1, 0, 0, 0, None) == INVALID
+    assert lib.tempo_attn_softmax_dropout_fwd(16, None, 0, 16, 16, 16, 1 << 16, 1 << 16, 1, 8, 0.1, 0, 0, 0, None) == INVALID
+    assert lib.tempo_attn_softmax_dropout_bwd(16, 16, 16, 16, None, 1 << 20, 1 << 10, 1 << 10, 1 << 10, 0.1, 0, None) == INVALID
+    assert lib.tempo_attn_softmax_dropout_bwd_regen(16, 16, 16, None, 1, 1, 1 << 31, 8, 0.1, 0, 0, 0, None) == INVALID
+    assert lib.tempo_mask_bytes_to_bits(16, 16, big, None) == INVALID
     # workspace too small
     need = lib.tempo_layernorm_bwd_workspace_bytes(64, 128)
     assert need >= 2 * 128 * 4
