@@ -24,6 +24,8 @@ CASES = [
     pytest.param(dict(index=3), id="config3"),
     pytest.param(dict(index=4, batch=8, dtype="bf16"), id="config4-b8-bf16"),
     pytest.param(dict(index=4, batch=8, dtype="f32"), id="config4-b8-f32"),
+    pytest.param(dict(index=4, batch=64, dtype="bf16"), id="config4-b64-bf16"),
+    pytest.param(dict(index=4, batch=64, dtype="f32"), id="config4-b64-f32"),
 ]
 
 
