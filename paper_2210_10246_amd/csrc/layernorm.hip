@@ -207,11 +207,16 @@ __global__ __launch_bounds__(kBwdThreads) void ln_bwd_kernel(
   __shared__ float2 red[2][kBwdWaves];
   static_assert(LANES <= kWave || R == 1, "rows over several waves: one row per group");
   int flip = 0;
-  // gamma, 1/gamma and beta/gamma live in LDS (the first 3*M floats; the same memory is
-  // reused by the reduction tree at the end), the column sums in registers
+  // gamma, 1/gamma and beta/gamma of the lane's columns live in its registers when that share
+  // is at most 24 columns and a wave holds one row; otherwise in LDS (the first 3*M floats; the
+  // same memory is reused by the reduction tree at the end), where every row re-reads the three
+  // vectors twice: at 8 waves per compute unit that is microseconds of LDS time per batch.
+  // The column sums are always in registers.
+  constexpr bool kRegParams = CH * V <= 24 && LANES >= kWave;
   float* p_ga = lds;
   float* p_rg = lds + M;
   float* p_bg = lds + 2 * M;
+  float r_ga[kRegParams ? CH : 1][V], r_rg[kRegParams ? CH : 1][V], r_bg[kRegParams ? CH : 1][V];
   float acc_g[CH][V], acc_b[CH][V];
 #pragma unroll
   for (int c = 0; c < CH; ++c) {
@@ -243,14 +248,37 @@ __global__ __launch_bounds__(kBwdThreads) void ln_bwd_kernel(
   float rs[R];
   fetch(base, rd, ry, rs);
   // parameters after the first rows are on their way
-  for (int j = threadIdx.x; j < M; j += kBwdThreads) {
-    const float gj = gamma[j];
-    const float rj = 1.0f / gj;
-    p_ga[j] = gj;
-    p_rg[j] = rj;
-    p_bg[j] = beta[j] * rj;
+  if constexpr (kRegParams) {
+#pragma unroll
+    for (int c = 0; c < CH; ++c) {
+      const int ch = c * LANES + t;
+      float be[V];
+      if (ch < chunks) {
+        load_floats<V>(gamma + ch * V, r_ga[c]);
+        load_floats<V>(beta + ch * V, be);
+      } else {
+#pragma unroll
+        for (int i = 0; i < V; ++i) {
+          r_ga[c][i] = 1.0f;
+          be[i] = 0.0f;
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < V; ++i) {
+        r_rg[c][i] = 1.0f / r_ga[c][i];
+        r_bg[c][i] = be[i] * r_rg[c][i];
+      }
+    }
+  } else {
+    for (int j = threadIdx.x; j < M; j += kBwdThreads) {
+      const float gj = gamma[j];
+      const float rj = 1.0f / gj;
+      p_ga[j] = gj;
+      p_rg[j] = rj;
+      p_bg[j] = beta[j] * rj;
+    }
+    __syncthreads();
   }
-  __syncthreads();
   while (base < N) {
     const int64_t next = base + static_cast<int64_t>(gridDim.x) * batch_rows;
     Raw<T> nd[R][CH], ny[R][CH];  // unused (and eliminated) without LOOP
@@ -273,9 +301,18 @@ __global__ __launch_bounds__(kBwdThreads) void ln_bwd_kernel(
           float d8[V], y8[V], ga[V], rg[V], bg[V];
           rd[r][c].unpack(d8);
           ry[r][c].unpack(y8);
-          load_floats<V>(p_ga + ch * V, ga);
-          load_floats<V>(p_rg + ch * V, rg);
-          load_floats<V>(p_bg + ch * V, bg);
+          if constexpr (kRegParams) {
+#pragma unroll
+            for (int i = 0; i < V; ++i) {
+              ga[i] = r_ga[c][i];
+              rg[i] = r_rg[c][i];
+              bg[i] = r_bg[c][i];
+            }
+          } else {
+            load_floats<V>(p_ga + ch * V, ga);
+            load_floats<V>(p_rg + ch * V, rg);
+            load_floats<V>(p_bg + ch * V, bg);
+          }
 #pragma unroll
           for (int i = 0; i < V; ++i) {
             const float h = fmaf(y8[i], rg[i], -bg[i]);  // xhat = (y - beta) / gamma
@@ -307,9 +344,18 @@ __global__ __launch_bounds__(kBwdThreads) void ln_bwd_kernel(
           float d8[V], y8[V], o[V], ga[V], rg[V], bg[V];
           rd[r][c].unpack(d8);
           ry[r][c].unpack(y8);
-          load_floats<V>(p_ga + ch * V, ga);
-          load_floats<V>(p_rg + ch * V, rg);
-          load_floats<V>(p_bg + ch * V, bg);
+          if constexpr (kRegParams) {
+#pragma unroll
+            for (int i = 0; i < V; ++i) {
+              ga[i] = r_ga[c][i];
+              rg[i] = r_rg[c][i];
+              bg[i] = r_bg[c][i];
+            }
+          } else {
+            load_floats<V>(p_ga + ch * V, ga);
+            load_floats<V>(p_rg + ch * V, rg);
+            load_floats<V>(p_bg + ch * V, bg);
+          }
 #pragma unroll
           for (int i = 0; i < V; ++i) {
             const float h = fmaf(y8[i], rg[i], -bg[i]);
@@ -621,9 +667,9 @@ tempo_status launch_layernorm_fwd(const void* x, const float* gamma, const float
 // Launch plan of the register-resident backward kernel.  Rows per lane group and batch (r):
 // as many as the knob allows while the packed rows stay within ~64 registers and the grid
 // keeps one workgroup per compute unit.  If that leaves more batches than the knob's number of
-// workgroups per compute unit (default 1), workgroups loop with prefetch instead (half the rows
-// per batch, since two batches are then held in registers) on a grid of that many workgroups
-// per compute unit.
+// workgroups per compute unit (default 1), workgroups loop with prefetch instead (two batches
+// are then held in registers: half the rows per batch for one-piece rows, one row otherwise) on
+// a grid of that many workgroups per compute unit.
 struct BwdPlan {
   int r;
   bool loop;
@@ -645,7 +691,7 @@ static BwdPlan bwd_plan(int64_t N, const Shape& sh, tempo_dtype dt) {
   const int per_cu = tune_get(kTuneLnBwdLoopBlocksPerCu);
   if (batches(r) > static_cast<int64_t>(per_cu) * cus) {
     p.loop = true;
-    p.r = r > 1 ? r / 2 : 1;
+    p.r = (r > 1 && sh.ch == 1) ? r / 2 : 1;  // measured: rows of 2 pieces per lane loop best alone
     p.grid = per_cu * cus;
   }
   if (p.grid < 1) p.grid = 1;
