@@ -19,7 +19,7 @@ static std::atomic<int> g_tune[kTuneCount] = {
     {4},      // attention fwd: most pieces per lane of a one-wave row
     {4},      // attention bwd: the same
     {4},      // layernorm fwd: the same
-    {4},      // layernorm bwd: the same
+    {3},      // layernorm bwd: the same (3: rows of 4 pieces per lane would keep their parameters in LDS)
     {1},      // layernorm bwd: workgroups per CU beyond which they loop with prefetch
     {24},     // bf16 gelu/silu fwd: Mi elements from which workgroups have 512 lanes
 };

@@ -103,10 +103,10 @@ def test_launch_params():
     old = B.tempo_get_launch_param(3)
     B.tempo_set_launch_param(3, 1)
     assert B.tempo_get_launch_param(3) == 1
-    a = lib.tempo_layernorm_bwd_workspace_bytes(512, 1024)     # 8 rows per workgroup: 64 slots
+    a = lib.tempo_layernorm_bwd_workspace_bytes(512, 512)      # 8 rows per workgroup: 64 slots
     B.tempo_set_launch_param(3, 2)
-    b = lib.tempo_layernorm_bwd_workspace_bytes(512, 1024)     # still 64: never fewer workgroups than CUs
-    assert a == b == 64 * 2 * 1024 * 4                          # one [2, M] float slot per workgroup
+    b = lib.tempo_layernorm_bwd_workspace_bytes(512, 512)      # still 64: never fewer workgroups than CUs
+    assert a == b == 64 * 2 * 512 * 4                           # one [2, M] float slot per workgroup
     assert lib.tempo_layernorm_bwd_workspace_bytes(1 << 20, 1024) <= 4096 * 2 * 1024 * 4
     B.tempo_set_launch_param(3, old)
     assert lib.tempo_set_launch_param(99, 1) == 1 and lib.tempo_set_launch_param(0, 0) == 1
