@@ -217,6 +217,11 @@ __global__ __launch_bounds__(kBwdThreads) void ln_bwd_kernel(
   float* p_rg = lds + M;
   float* p_bg = lds + 2 * M;
   float r_ga[kRegParams ? CH : 1][V], r_rg[kRegParams ? CH : 1][V], r_bg[kRegParams ? CH : 1][V];
+  // xhat and dy*gamma of the batch stay in registers between the two passes when they fit (128
+  // registers; a workgroup of 8 waves has 256 per lane however few it uses): the second pass
+  // then neither unpacks nor recomputes them.  Same arithmetic either way.
+  constexpr bool kKeep = kRegParams && R * CH * V <= 64 && R * CH * 8 * (LOOP ? 2 : 1) <= 64;
+  float k_h[kKeep ? R : 1][kKeep ? CH : 1][V], k_q[kKeep ? R : 1][kKeep ? CH : 1][V];
   float acc_g[CH][V], acc_b[CH][V];
 #pragma unroll
   for (int c = 0; c < CH; ++c) {
@@ -265,7 +270,10 @@ __global__ __launch_bounds__(kBwdThreads) void ln_bwd_kernel(
       }
 #pragma unroll
       for (int i = 0; i < V; ++i) {
-        r_rg[c][i] = 1.0f / r_ga[c][i];
+        // reciprocal by the hardware estimate and one Newton step (within 1 ulp): a lane does this
+        // for each of its columns in every workgroup, and the IEEE division costs four times as much
+        const float est = __builtin_amdgcn_rcpf(r_ga[c][i]);
+        r_rg[c][i] = fmaf(fmaf(-r_ga[c][i], est, 1.0f), est, est);
         r_bg[c][i] = be[i] * r_rg[c][i];
       }
     }
@@ -321,6 +329,10 @@ __global__ __launch_bounds__(kBwdThreads) void ln_bwd_kernel(
             c2[r] += q;
             acc_g[c][i] = fmaf(d8[i], h, acc_g[c][i]);
             acc_b[c][i] += d8[i];
+            if constexpr (kKeep) {
+              k_h[r][c][i] = h;
+              k_q[r][c][i] = q;
+            }
           }
         }
       }
@@ -332,7 +344,7 @@ __global__ __launch_bounds__(kBwdThreads) void ln_bwd_kernel(
       c1[r] *= inv_m;
       c2[r] *= inv_m;
     }
-    // pass 2: dx, recomputing xhat and dy*gamma from the packed registers
+    // pass 2: dx, from the kept xhat and dy*gamma or recomputing them from the packed registers
 #pragma unroll
     for (int r = 0; r < R; ++r) {
       const int64_t row = base + r * kGroups + g;
@@ -341,25 +353,32 @@ __global__ __launch_bounds__(kBwdThreads) void ln_bwd_kernel(
       for (int c = 0; c < CH; ++c) {
         const int ch = c * LANES + t;
         if (ch < chunks) {
-          float d8[V], y8[V], o[V], ga[V], rg[V], bg[V];
-          rd[r][c].unpack(d8);
-          ry[r][c].unpack(y8);
-          if constexpr (kRegParams) {
+          float o[V];
+          if constexpr (kKeep) {
+#pragma unroll
+            for (int i = 0; i < V; ++i)
+              o[i] = rs[r] * (k_q[r][c][i] - fmaf(k_h[r][c][i], c1[r], c2[r]));
+          } else {
+            float d8[V], y8[V], ga[V], rg[V], bg[V];
+            rd[r][c].unpack(d8);
+            ry[r][c].unpack(y8);
+            if constexpr (kRegParams) {
+#pragma unroll
+              for (int i = 0; i < V; ++i) {
+                ga[i] = r_ga[c][i];
+                rg[i] = r_rg[c][i];
+                bg[i] = r_bg[c][i];
+              }
+            } else {
+              load_floats<V>(p_ga + ch * V, ga);
+              load_floats<V>(p_rg + ch * V, rg);
+              load_floats<V>(p_bg + ch * V, bg);
+            }
 #pragma unroll
             for (int i = 0; i < V; ++i) {
-              ga[i] = r_ga[c][i];
-              rg[i] = r_rg[c][i];
-              bg[i] = r_bg[c][i];
+              const float h = fmaf(y8[i], rg[i], -bg[i]);
+              o[i] = rs[r] * (d8[i] * ga[i] - fmaf(h, c1[r], c2[r]));
             }
-          } else {
-            load_floats<V>(p_ga + ch * V, ga);
-            load_floats<V>(p_rg + ch * V, rg);
-            load_floats<V>(p_bg + ch * V, bg);
-          }
-#pragma unroll
-          for (int i = 0; i < V; ++i) {
-            const float h = fmaf(y8[i], rg[i], -bg[i]);
-            o[i] = rs[r] * (d8[i] * ga[i] - fmaf(h, c1[r], c2[r]));
           }
           store_piece<T>(dx + row * M + ch * V, o);
         }
