@@ -572,3 +572,93 @@ def test_hip_graph_replays_match_eager(B):
         torch.cuda.synchronize()
         for name in eager:
             assert torch.equal(captured[name].view(torch.uint8), eager[name].view(torch.uint8)), (rep, name)
+
+
+# ------------------------------------------------------------------ degenerate inputs
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+@pytest.mark.parametrize("p", [0.9, 0.999, 0.99999])
+def test_attn_with_almost_everything_dropped(B, p, dt):
+    # keep thresholds of 6554, 66 and 1 out of 65536; scales of 10, 1e3 and 1e5
+    rng = np.random.default_rng(int(p * 1e6))
+    shape = (2, 4, 128, 128)
+    s = stored(rng, shape, dt, 0.125)
+    p = np.float32(p)
+    seed, offset = 77, 5                                    # keeps 12959, 132 and 3 elements
+    P_ref, out_ref, K_ref = O.attn_softmax_dropout_fwd(s, None, False, p, seed, offset, dt)
+    assert 0 < K_ref.sum() < K_ref.size // 5
+    sd = dev(s, dt)
+    Pd, od = torch.empty_like(sd), torch.empty_like(sd)
+    md = torch.empty(B.mask_words(s.size), dtype=torch.int32, device="cuda")
+    B.tempo_attn_softmax_dropout_fwd(sd, None, False, Pd, od, md, float(p), seed, offset)
+    assert np.array_equal(words(md), O.pack_bits(K_ref))
+    assert rel_err(host(Pd), P_ref) <= TOL[dt]
+    assert rel_err(host(od), out_ref) <= TOL[dt]
+    dout = stored(rng, shape, dt)
+    dS_ref, _ = O.attn_softmax_dropout_bwd(dout, P_ref, K_ref, p, dt)
+    dsd = torch.empty_like(sd)
+    B.tempo_attn_softmax_dropout_bwd(dev(dout, dt), dev(P_ref, dt), md, dsd, None, float(p))
+    assert rel_err(host(dsd), dS_ref) <= TOL[dt]
+    dsd2 = torch.empty_like(sd)
+    B.tempo_attn_softmax_dropout_bwd_regen(dev(dout, dt), dev(P_ref, dt), dsd2, None, float(p), seed, offset)
+    assert torch.equal(dsd, dsd2)
+
+
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+@pytest.mark.parametrize("Sk", [128, 1000, 2048])
+def test_attn_scores_with_minus_infinity_and_large_magnitudes(B, Sk, dt):
+    # scores that already carry an additive mask: -inf entries, one row of nothing but -inf,
+    # and magnitudes for which exp overflows without the max subtraction
+    rng = np.random.default_rng(Sk)
+    shape = (1, 2, 9, Sk)
+    s = stored(rng, shape, dt, 60.0)
+    s[rng.random(shape) < 0.1] = -np.inf
+    s[0, 1, 4, :] = -np.inf
+    s[0, 0, 2, :] = -300.0
+    s[0, 0, 2, 5] = 300.0
+    p, seed, offset = np.float32(0.1), 9, 0
+    with np.errstate(invalid="ignore"):
+        P_ref, out_ref, K_ref = O.attn_softmax_dropout_fwd(s, None, False, p, seed, offset, dt)
+    assert np.all(P_ref[0, 1, 4] == 0) and P_ref[0, 0, 2, 5] == 1.0
+    sd = dev(s, dt)
+    Pd, od = torch.empty_like(sd), torch.empty_like(sd)
+    md = torch.empty(B.mask_words(s.size), dtype=torch.int32, device="cuda")
+    B.tempo_attn_softmax_dropout_fwd(sd, None, False, Pd, od, md, float(p), seed, offset)
+    assert np.array_equal(words(md), O.pack_bits(K_ref))
+    assert rel_err(host(Pd), P_ref) <= TOL[dt]
+    assert rel_err(host(od), out_ref) <= TOL[dt]
+    assert np.all(host(Pd)[0, 1, 4] == 0)
+
+
+@pytest.mark.parametrize("eps", [1e-12, 1e-5])
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+@pytest.mark.parametrize("M", [64, 1024, 4104])
+def test_layernorm_constant_rows(B, M, dt, eps):
+    # zero variance: rstd = 1/sqrt(eps), y = beta exactly (the constants are chosen so that the
+    # float32 row sums are exact), and backward from y = beta
+    rng = np.random.default_rng(M)
+    consts = np.array([0.0, 1.0, -2.5, 1024.0, -0.0078125, 3.0])
+    N = consts.size
+    x = np.repeat(consts[:, None], M, axis=1)
+    gamma = O.round_to_dtype(1 + 0.1 * rng.standard_normal(M), "f32")
+    beta = O.round_to_dtype(0.1 * rng.standard_normal(M), "f32")
+    y_ref, rstd_ref, mean_ref = O.layernorm_fwd(x, gamma, beta, eps, dt)
+    assert np.array_equal(y_ref, O.round_to_dtype(np.broadcast_to(beta, x.shape), dt))
+    xd, gd, bd = dev(x, dt), dev(gamma, "f32"), dev(beta, "f32")
+    yd = torch.empty_like(xd)
+    rd = torch.empty(N, dtype=torch.float32, device="cuda")
+    md = torch.empty(N, dtype=torch.float32, device="cuda")
+    B.tempo_layernorm_fwd(xd, gd, bd, yd, rd, md, eps)
+    assert np.array_equal(host(yd), y_ref)
+    assert rel_err(host(rd), rstd_ref) <= TOL["f32"]
+    assert np.array_equal(host(md), mean_ref)
+    dy = stored(rng, (N, M), dt)
+    dx_ref, dg_ref, db_ref = O.layernorm_bwd(dy, y_ref, gamma, beta, host(rd), dt)
+    dxd = torch.empty_like(xd)
+    dgd = torch.empty(M, dtype=torch.float32, device="cuda")
+    dbd = torch.empty(M, dtype=torch.float32, device="cuda")
+    ws = torch.empty(B.tempo_layernorm_bwd_workspace_bytes(N, M), dtype=torch.uint8, device="cuda")
+    B.tempo_layernorm_bwd(dev(dy, dt), yd, gd, bd, rd, dxd, dgd, dbd, ws)
+    assert rel_err(host(dxd), dx_ref) <= TOL[dt]
+    assert rel_err(host(dbd), db_ref) <= TOL["f32"]
+    # dgamma = sum dy * xhat with xhat = 0 up to the rounding of y = beta to the storage dtype
+    assert np.abs(host(dgd) - dg_ref).max() <= 1e-5 * max(1.0, np.abs(dy).max()) * N
