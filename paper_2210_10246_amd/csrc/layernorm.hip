@@ -208,11 +208,11 @@ __global__ __launch_bounds__(kBwdThreads) void ln_bwd_kernel(
   static_assert(LANES <= kWave || R == 1, "rows over several waves: one row per group");
   int flip = 0;
   // gamma, 1/gamma and beta/gamma of the lane's columns live in its registers when that share
-  // is at most 24 columns and a wave holds one row; otherwise in LDS (the first 3*M floats; the
+  // is at most 24 columns; otherwise in LDS (the first 3*M floats; the
   // same memory is reused by the reduction tree at the end), where every row re-reads the three
   // vectors twice: at 8 waves per compute unit that is microseconds of LDS time per batch.
   // The column sums are always in registers.
-  constexpr bool kRegParams = CH * V <= 24 && LANES >= kWave;
+  constexpr bool kRegParams = CH * V <= 24;
   float* p_ga = lds;
   float* p_rg = lds + M;
   float* p_bg = lds + 2 * M;
