@@ -545,8 +545,11 @@ struct Shape {
 };
 
 // Lanes per row and pieces per lane for a row of `pieces` 16-byte pieces: least padding, then
-// the widest group.  ch == 0: no register-resident shape fits.
-Shape pick_shape(int pieces) {
+// the widest group.  ch == 0: no register-resident shape fits.  full_wave (the backward): a
+// whole wave per row counts as unpadded while at most a third of its lanes' pieces are
+// padding; one row per wave lets a lane group fetch up to 4 rows at once, which there is
+// worth more than the idle lanes (measured at 384 and 768 columns; the forward loses by it).
+Shape pick_shape(int pieces, bool full_wave) {
   static const int wide[] = {1, 2, 3, 4, 6, 8, 12, 16};  // 64 lanes
   static const int narrow[] = {1, 2, 3};                 // 32 and 16 lanes
   Shape best = {0, 0};
@@ -557,7 +560,8 @@ Shape pick_shape(int pieces) {
     const int count = lanes == 64 ? 8 : 3;
     for (int k = 0; k < count; ++k) {
       if (allowed[k] >= need) {
-        const int waste = lanes * allowed[k] - pieces;
+        int waste = lanes * allowed[k] - pieces;
+        if (full_wave && lanes == 64 && waste * 3 <= lanes * allowed[k]) waste = 0;
         if (waste < best_waste) {
           best_waste = waste;
           best = {lanes, allowed[k]};
@@ -644,7 +648,7 @@ static bool fast_shape(int64_t M, tempo_dtype dt, bool backward, Shape* sh) {
   const int vec = dt == TEMPO_F32 ? 4 : 8;
   if (M % vec != 0 || M > kMaxFastM) return false;
   const int pieces = static_cast<int>(M / vec);
-  *sh = widen_shape(pick_shape(pieces), pieces,
+  *sh = widen_shape(pick_shape(pieces, backward), pieces,
                     tune_get(backward ? kTuneLnBwdMaxPieces : kTuneLnFwdMaxPieces), 256);
   return sh->ch != 0;
 }
