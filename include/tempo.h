@@ -9,7 +9,9 @@
  *              launch knobs below.  Every base pointer must be
  *              16-byte aligned (TEMPO_ERR_UNSUPPORTED otherwise).
  *   Stream     hip_stream is a hipStream_t passed as void* (NULL = the default stream).  Work
- *              is enqueued on it and the call returns without synchronising.
+ *              is enqueued on it and the call returns without synchronising.  Every entry point
+ *              only launches kernels (no allocation, copy or memset), so a call may be recorded
+ *              into a HIP graph by stream capture, a process's first call included.
  *   Layout     Contiguous row-major.  Activations are float32 (TEMPO_F32) or bfloat16
  *              (TEMPO_BF16); gamma, beta, dgamma, dbeta, rstd and mean are always float32.
  *   Bit masks  Element e (flat row-major index) is bit (e mod 32) of 32-bit word (e div 32).
