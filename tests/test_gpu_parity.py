@@ -523,12 +523,13 @@ def test_non_default_stream(B):
     assert rel_err(host(yd), y_ref) <= TOL["f32"] and np.array_equal(words(md), O.pack_bits(m_ref))
 
 
-def test_hip_graph_replays_match_eager(B):
+@pytest.mark.parametrize("N", [64, 40_000])       # 40 000 rows: the LayerNorm kernels loop
+def test_hip_graph_replays_match_eager(B, N):
     """The benchmark replays captured HIP graphs: every replay must reproduce the eagerly
     launched results, with the program's own eager work and synchronisations in between."""
     rng = np.random.default_rng(11)
     dt = "bf16"
-    N, M, n = 64, 1024, 64 * 4096
+    M, n = 1024, 64 * 4096
     x = dev(stored(rng, n, dt), dt)
     dy = dev(stored(rng, n, dt), dt)
     lx = dev(stored(rng, (N, M), dt), dt)
