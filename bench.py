@@ -6,7 +6,12 @@ input: GELU fwd+bwd, two LayerNorms fwd+bwd, attention softmax-dropout fwd+bwd, 
 the C ABI.  Inputs are resident in HBM before the timed region; buffer sets are rotated so
 that nothing is served from the 256 MB Infinity Cache.  One JSON line is printed.
 
-    python bench.py [--steps K] [--warmup W] [--config 1] [--no-cpu-baseline]
+    python bench.py [--steps K] [--warmup W] [--config 4 --batch 64 --dtype f32] [--no-cpu-baseline]
+
+With no arguments the headline workload is configuration 4 (RoBERTa-large-shaped full-layer
+sweep) at its largest batch, 64, in float32 (the paper accounts activations at 32 bits), and
+the per-kernel tables of the same batch in bfloat16 and of configurations 1-3 are measured in
+the same run and reported under "other_workloads".
 """
 from __future__ import annotations
 
@@ -31,9 +36,13 @@ def parse():
     # defaults long enough for the clocks to settle: short runs read 3-4 % low
     ap.add_argument("--steps", type=int, default=2000)
     ap.add_argument("--warmup", type=int, default=400)
-    ap.add_argument("--config", type=int, default=1, help="workload configuration index (0-4)")
+    ap.add_argument("--config", type=int, default=None,
+                    help="workload configuration index (0-4); default: 4 at batch 64 in f32, "
+                         "followed by the other workloads' per-kernel tables")
     ap.add_argument("--batch", type=int, default=None, help="batch override (config 4 sweep)")
     ap.add_argument("--dtype", choices=["f32", "bf16"], default=None)
+    ap.add_argument("--no-other-workloads", action="store_true",
+                    help="default run only: skip the per-kernel tables of the other workloads")
     ap.add_argument("--seq", type=int, default=None, help="sequence length override (shape sweeps)")
     ap.add_argument("--hidden", type=int, default=None, help="hidden size override; heads = hidden/64")
     ap.add_argument("--kernel-iters", type=int, default=60, help="launches per kernel timing burst")
@@ -104,21 +113,29 @@ class Buffers:
         return s
 
 
+DEFAULT_WORKLOAD = dict(index=4, batch=64, dtype="f32")
+# measured beside the headline in a default run: per-kernel tables only
+OTHER_WORKLOADS = (dict(index=4, batch=64, dtype="bf16"), dict(index=1), dict(index=2), dict(index=3))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU; --gpus must be 1 (no multi-GPU path exists)",
               file=sys.stderr)
         sys.exit(2)
-    import numpy as np
     import torch
     from paper_2210_10246_amd import binding as B
     from paper_2210_10246_amd import workloads as W
 
     B.load()
     assert torch.cuda.is_available(), "bench.py needs the MI355X"
-    dev = torch.device("cuda:0")
-    cfg = W.config(args.config, batch=args.batch, dtype=args.dtype)
+    default_run = args.config is None
+    if default_run:
+        d = DEFAULT_WORKLOAD
+        cfg = W.config(d["index"], batch=args.batch or d["batch"], dtype=args.dtype or d["dtype"])
+    else:
+        cfg = W.config(args.config, batch=args.batch, dtype=args.dtype)
     if args.seq is not None or args.hidden is not None:
         from dataclasses import replace
         hidden = args.hidden or cfg.hidden
@@ -126,6 +143,35 @@ def main():
         lo, hi = (seq // 2, seq) if cfg.mask == "padding" else (0, 0)
         cfg = replace(cfg, seq=seq, hidden=hidden, heads=hidden // 64, len_lo=lo, len_hi=hi,
                       name=f"{cfg.name}-s{seq}-h{hidden}")
+    import gc
+    line = measure(cfg, args, headline=True)
+    if default_run and not args.no_other_workloads and args.only is None and not args.no_kernel_timing:
+        others = {}
+        for o in OTHER_WORKLOADS:
+            ocfg = W.config(o["index"], batch=o.get("batch"), dtype=o.get("dtype"))
+            gc.collect()             # the previous workload's buffers and graphs
+            torch.cuda.empty_cache()
+            r = measure(ocfg, args, headline=False)
+            others[r["config"]["workload"]] = {
+                "dtype": r["dtype"], "value": r["value"], "ms_per_step": r["ms_per_step"],
+                "frac_of_hbm_peak": r["frac_of_hbm_peak"], "worst_kernel": r["worst_kernel"],
+                "kernels": {k: {f: v[f] for f in ("us", "GB/s", "frac_of_peak", "bytes")}
+                            for k, v in r["kernels"].items()}}
+        line["other_workloads"] = others
+    print(json.dumps(line))
+
+
+def measure(cfg, args, headline):
+    """One workload: the whole step timed over args.steps steps (a fifth of that for the
+    workloads measured beside the headline), then every kernel on its own."""
+    import numpy as np
+    import torch
+    from paper_2210_10246_amd import binding as B
+    from paper_2210_10246_amd import workloads as W
+
+    dev = torch.device("cuda:0")
+    steps = args.steps if headline else max(8, args.steps // 5)
+    warmup = args.warmup if headline else max(4, args.warmup // 5)
     dt = cfg.dtype
     tdt = W.torch_dtype(dt)
     e = cfg.elem_bytes
@@ -239,12 +285,12 @@ def main():
             def run_steps(k):
                 for i in range(k):
                     step(i % PHASES)
-        run_steps(args.warmup)   # the untimed warm-up steps, launched the same way as the timed ones
+        run_steps(warmup)   # the untimed warm-up steps, launched the same way as the timed ones
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        run_steps(args.steps)
+        run_steps(steps)
         torch.cuda.synchronize()
-        ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+        ms_per_step = (time.perf_counter() - t0) * 1e3 / steps
 
     # ---- per-kernel launch durations: events on the stream the kernels are launched on,
     # around a replayed graph of kernel_iters back-to-back launches over rotating buffers
@@ -333,12 +379,22 @@ def main():
                   if k in kernels} or {k: v["us"] for k, v in per_kernel.items()}
         dom = max(weight, key=weight.get)
         k = per_kernel[dom]
+        traffic, traffic_source = recorded_traffic(cfg, dom)
         roofline = {"kernel": dom, "bound": "hbm", "achieved": k["GB/s"], "peak": HBM_PEAK_GBS,
-                    "unit": "GB/s", "frac": k["frac_of_peak"], "traffic": measured_traffic(cfg, dom),
+                    "unit": "GB/s", "frac": k["frac_of_peak"], "traffic": traffic,
+                    # not measured by this process: counters need a rocprofv3 run of their own
+                    "traffic_source": traffic_source,
                     "us_per_launch": k["us"], "algorithmic_bytes": k["bytes"]}
+    # the kernel of the step furthest below the roofline
+    worst = None
+    in_step = {k: v for k, v in per_kernel.items() if k in kernels}
+    if in_step:
+        w = min(in_step, key=lambda k: in_step[k]["frac_of_peak"])
+        worst = {"kernel": w, "frac": in_step[w]["frac_of_peak"], "GB/s": in_step[w]["GB/s"],
+                 "us_per_launch": in_step[w]["us"]}
 
     cpu = None
-    if not args.no_cpu_baseline and args.only is None:
+    if headline and not args.no_cpu_baseline and args.only is None:
         cpu = cpu_baseline(cfg, algo)
 
     saved = activation_bytes_saved(cfg)
@@ -357,11 +413,11 @@ def main():
               "clocks": device_clocks()}
     line = {
         "metric": METRIC, "value": None if value is None else round(value, 1), "unit": "GB/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "n_gpus": 1, "steps": steps, "warmup": warmup,
         "ms_per_step": None if value is None else round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": dt,
         "data": "synthetic",
-        "config": {"workload": f"config {cfg.index}: {cfg.name}", "batch": cfg.batch, "seq_len": cfg.seq,
+        "config": {"workload": f"config {cfg.index}: {cfg.name}, batch {cfg.batch}, {dt}", "batch": cfg.batch, "seq_len": cfg.seq,
                    "hidden": cfg.hidden, "heads": cfg.heads, "ffn": cfg.ffn, "mask": cfg.mask,
                    "dropout_p": cfg.p, "gelu": cfg.gelu_kind,
                    "step": "attn fwd, LN fwd, GELU fwd, LN fwd, LN bwd, GELU bwd, LN bwd, attn bwd",
@@ -374,13 +430,14 @@ def main():
         "copy_kernel_GB/s": copy_gbs,
         "copy_kernel_same_bytes": copy_same,
         "roofline": roofline,
+        "worst_kernel": worst,
         "cpu_baseline": cpu,
         "kernels": per_kernel,
         "activation_bytes_saved_per_token": {**saved, "total": sum(saved.values()),
                                              "from_buffers": measured},
         "device": device,
     }
-    print(json.dumps(line))
+    return line
 
 
 def device_clocks():
@@ -403,19 +460,31 @@ def device_clocks():
     return out or None
 
 
-def measured_traffic(cfg, kernel):
-    """HBM bytes per launch of `kernel` from the committed rocprofv3 FETCH_SIZE / WRITE_SIZE
-    summary of this configuration (counter values scaled by the copy-kernel calibration), or
-    None if no such summary has been recorded for it."""
-    path = os.path.join(ROOT, "profiles", f"hbm_traffic_config{cfg.index}.json")
-    if cfg != __import__("paper_2210_10246_amd.workloads", fromlist=["x"]).config(cfg.index):
-        return None          # a batch / dtype override: the recorded counters do not apply
+def profile_tag(cfg):
+    """Name of the committed rocprofv3 summaries of a workload: the configuration index, plus
+    batch and dtype where they differ from the configuration's own."""
+    from paper_2210_10246_amd import workloads as W
+    base = W.config(cfg.index)
+    tag = f"config{cfg.index}"
+    if (cfg.batch, cfg.dtype) != (base.batch, base.dtype):
+        tag += f"_b{cfg.batch}_{cfg.dtype}"
+    return tag
+
+
+def recorded_traffic(cfg, kernel):
+    """HBM bytes per launch of `kernel` as recorded in the committed rocprofv3 FETCH_SIZE /
+    WRITE_SIZE summary of this workload (counter values scaled by the copy-kernel calibration),
+    and where that figure comes from; (None, None) if no summary is kept for the workload."""
+    from paper_2210_10246_amd import workloads as W
+    rel = os.path.join("profiles", f"hbm_traffic_{profile_tag(cfg)}.json")
+    if cfg != W.config(cfg.index, batch=cfg.batch, dtype=cfg.dtype):
+        return None, None    # a shape override: the recorded counters do not apply
     try:
-        with open(path) as f:
+        with open(os.path.join(ROOT, rel)) as f:
             rec = json.load(f)["kernels"][kernel]
     except (OSError, KeyError, ValueError):
-        return None
-    return int(rec["fetch_bytes"] + rec["write_bytes"])
+        return None, None
+    return int(rec["fetch_bytes"] + rec["write_bytes"]), f"recorded: {rel}"
 
 
 def cpu_baseline(cfg, algo):
@@ -425,7 +494,12 @@ def cpu_baseline(cfg, algo):
     from oracle import tempo_oracle as O
     from paper_2210_10246_amd import workloads as W
 
-    frac = 8 if cfg.tokens * cfg.ffn > (1 << 22) else 1
+    # leading 1/frac of the rows: about 50 M element accesses, 10-30 s of numpy work
+    total = (algo["gelu_fwd"] + algo["gelu_bwd"] + 2 * (algo["layernorm_fwd"] + algo["layernorm_bwd"])
+             + algo["attn_fwd"] + algo["attn_bwd"]) / cfg.elem_bytes
+    frac = 1
+    while total / frac > 60e6 and frac < cfg.batch:
+        frac *= 2
     dt = cfg.dtype
     rows = max(1, cfg.tokens // frac)
     ab = max(1, cfg.batch // frac) if cfg.batch >= frac else 1

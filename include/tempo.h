@@ -5,9 +5,10 @@
  *
  * Conventions shared by every entry point
  *   Pointers   All data pointers are DEVICE pointers, owned by the caller; the library
- *              allocates nothing, never frees, and keeps no state besides the process-wide
- *              launch knobs below.  Every base pointer must be
- *              16-byte aligned (TEMPO_ERR_UNSUPPORTED otherwise).
+ *              allocates nothing, never frees, and keeps no state between calls (the
+ *              launch-shape knobs of tempo_tune.h, a separate interface for tuning and
+ *              benchmarking, are the one exception and are not needed to use the layers).
+ *              Every base pointer must be 16-byte aligned (TEMPO_ERR_UNSUPPORTED otherwise).
  *   Stream     hip_stream is a hipStream_t passed as void* (NULL = the default stream).  Work
  *              is enqueued on it and the call returns without synchronising.  Every entry point
  *              only launches kernels (no allocation, copy or memset), so a call may be recorded
@@ -56,36 +57,6 @@ TEMPO_API const char* tempo_status_string(tempo_status s);
 
 /* Library version as major*10000 + minor*100 + patch. */
 TEMPO_API int tempo_version(void);
-
-/*
- * Launch-shape knobs for tuning and benchmarking (process-wide, not needed for correctness):
- *   key 0 / 1: 16-byte pieces per lane in gelu_fwd / gelu_bwd (1, 2 or 4);
- *   key 13: tensor size in Mi elements from which the bfloat16 gelu/silu forward uses workgroups
- *   of 512 lanes with half the pieces per lane (65536: never);
- *   key 2, 4, 5: cap on workgroups per compute unit of layernorm_fwd, attn fwd, attn bwd
- *   (rows beyond the cap are walked in a loop);
- *   key 6, 7: rows a lane group of attn fwd / layernorm_fwd fetches at once (1 or 2);
- *   key 8, 9, 10, 11: attn fwd / attn bwd / layernorm_fwd / layernorm_bwd: 16-byte pieces per
- *   lane above which a row is spread over 2 or 4 waves instead of one (16 or more: never);
- *   key 3: rows each lane group of layernorm_bwd walks; key 12: workgroups per compute unit
- *   beyond which its workgroups loop over the rows; keys 3, 11 and 12 set its grid and the
- *   size of its workspace, so query tempo_layernorm_bwd_workspace_bytes after changing them.
- * Results never depend on these except the summation order of dgamma/dbeta and of the softmax
- * denominator and the other row sums (keys 8-11).  value in
- * [1, 65536].  tempo_set_launch_param returns TEMPO_OK or TEMPO_ERR_INVALID_ARG; the getter
- * returns -1 for an unknown key.
- */
-TEMPO_API int tempo_set_launch_param(int key, int value);
-TEMPO_API int tempo_get_launch_param(int key);
-
-/*
- * Plain device-to-device copy of nbytes (a multiple of 16) with 16-byte accesses, at most
- * blocks_per_cu workgroups per compute unit.  Not part of the method: it is the yardstick for
- * the bandwidth a pure streaming kernel reaches on this GPU and the known-size kernel used to
- * calibrate hardware byte counters.  src and dst must not overlap.
- */
-TEMPO_API tempo_status tempo_copy(const void* src, void* dst, int64_t nbytes, int blocks_per_cu,
-                                  void* hip_stream);
 
 /*
  * In-place GELU forward, (y, m) = GELU*(x)            [Sec. 3.1; App. E.1 eq. (1); App. F.1]

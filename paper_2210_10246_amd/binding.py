@@ -85,6 +85,26 @@ def _ptr(t: Optional[torch.Tensor]):
     return t.data_ptr()
 
 
+def _want(name: str, t: Optional[torch.Tensor], dtype, numel: Optional[int] = None,
+          at_least: Optional[int] = None):
+    """The C ABI reads raw bytes: a tensor of another dtype or size would be misread, or read
+    out of bounds, on the device.  None is let through (optional arguments)."""
+    if t is None:
+        return
+    if t.dtype != dtype:
+        raise ValueError(f"{name} must be {dtype}, got {t.dtype}")
+    if numel is not None and t.numel() != numel:
+        raise ValueError(f"{name} must have {numel} elements, got {t.numel()}")
+    if at_least is not None and t.numel() < at_least:
+        raise ValueError(f"{name} must have at least {at_least} elements, got {t.numel()}")
+
+
+def _act_dtype(name: str, t: torch.Tensor) -> int:
+    if t.dtype not in _DT:
+        raise ValueError(f"{name} must be float32 or bfloat16, got {t.dtype}")
+    return _DT[t.dtype]
+
+
 def _stream(stream):
     s = torch.cuda.current_stream() if stream is None else stream
     return s.cuda_stream
@@ -117,33 +137,57 @@ def tempo_copy(src, dst, blocks_per_cu=16, stream=None):
 
 def tempo_gelu_fwd(x, y, mask, kind="erf", stream=None):
     """(y, mask) = GELU*(x); y may be x."""
-    _check(load().tempo_gelu_fwd(_ptr(x), _ptr(y), _ptr(mask), x.numel(), _DT[x.dtype],
+    n = x.numel()
+    dt = _act_dtype("x", x)
+    _want("y", y, x.dtype, n)
+    _want("mask", mask, torch.int32, at_least=mask_words(n))
+    _check(load().tempo_gelu_fwd(_ptr(x), _ptr(y), _ptr(mask), n, dt,
                                  _KIND[kind], _stream(stream)), "tempo_gelu_fwd")
 
 
 def tempo_gelu_bwd(dy, y, mask, dx, kind="erf", stream=None):
     """dx = dy * GELU'(GELU*^-1(y, mask)); dx may be dy."""
-    _check(load().tempo_gelu_bwd(_ptr(dy), _ptr(y), _ptr(mask), _ptr(dx), y.numel(), _DT[y.dtype],
+    n = y.numel()
+    dt = _act_dtype("y", y)
+    _want("dy", dy, y.dtype, n)
+    _want("dx", dx, y.dtype, n)
+    _want("mask", mask, torch.int32, at_least=mask_words(n))
+    _check(load().tempo_gelu_bwd(_ptr(dy), _ptr(y), _ptr(mask), _ptr(dx), n, dt,
                                  _KIND[kind], _stream(stream)), "tempo_gelu_bwd")
 
 
 def tempo_silu_fwd(x, y, mask, stream=None):
     """(y, mask) = SiLU*(x); y may be x."""
-    _check(load().tempo_silu_fwd(_ptr(x), _ptr(y), _ptr(mask), x.numel(), _DT[x.dtype],
+    n = x.numel()
+    dt = _act_dtype("x", x)
+    _want("y", y, x.dtype, n)
+    _want("mask", mask, torch.int32, at_least=mask_words(n))
+    _check(load().tempo_silu_fwd(_ptr(x), _ptr(y), _ptr(mask), n, dt,
                                  _stream(stream)), "tempo_silu_fwd")
 
 
 def tempo_silu_bwd(dy, y, mask, dx, stream=None):
     """dx = dy * SiLU'(SiLU*^-1(y, mask)); dx may be dy."""
-    _check(load().tempo_silu_bwd(_ptr(dy), _ptr(y), _ptr(mask), _ptr(dx), y.numel(), _DT[y.dtype],
+    n = y.numel()
+    dt = _act_dtype("y", y)
+    _want("dy", dy, y.dtype, n)
+    _want("dx", dx, y.dtype, n)
+    _want("mask", mask, torch.int32, at_least=mask_words(n))
+    _check(load().tempo_silu_bwd(_ptr(dy), _ptr(y), _ptr(mask), _ptr(dx), n, dt,
                                  _stream(stream)), "tempo_silu_bwd")
 
 
 def tempo_layernorm_fwd(x, gamma, beta, y, rstd, mean=None, eps=1e-5, stream=None):
     M = x.shape[-1]
     N = x.numel() // M if M else 0
+    dt = _act_dtype("x", x)
+    _want("y", y, x.dtype, x.numel())
+    _want("gamma", gamma, torch.float32, M)
+    _want("beta", beta, torch.float32, M)
+    _want("rstd", rstd, torch.float32, N)
+    _want("mean", mean, torch.float32, N)
     _check(load().tempo_layernorm_fwd(_ptr(x), _ptr(gamma), _ptr(beta), _ptr(y), _ptr(rstd),
-                                      _ptr(mean), N, M, eps, _DT[x.dtype], _stream(stream)),
+                                      _ptr(mean), N, M, eps, dt, _stream(stream)),
            "tempo_layernorm_fwd")
 
 
@@ -155,41 +199,71 @@ def tempo_layernorm_bwd(dy, y, gamma, beta, rstd, dx, dgamma, dbeta, workspace, 
     M = y.shape[-1]
     N = y.numel() // M if M else 0
     ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    dt = _act_dtype("y", y)
+    _want("dy", dy, y.dtype, y.numel())
+    _want("dx", dx, y.dtype, y.numel())
+    _want("gamma", gamma, torch.float32, M)
+    _want("beta", beta, torch.float32, M)
+    _want("rstd", rstd, torch.float32, N)
+    _want("dgamma", dgamma, torch.float32, M)
+    _want("dbeta", dbeta, torch.float32, M)
     _check(load().tempo_layernorm_bwd(_ptr(dy), _ptr(y), _ptr(gamma), _ptr(beta), _ptr(rstd),
                                       _ptr(dx), _ptr(dgamma), _ptr(dbeta), _ptr(workspace),
-                                      ws_bytes, N, M, _DT[y.dtype], _stream(stream)),
+                                      ws_bytes, N, M, dt, _stream(stream)),
            "tempo_layernorm_bwd")
 
 
 def tempo_attn_softmax_dropout_fwd(scores, key_len, causal, probs, out, keep_bits, p, seed, offset,
                                    stream=None):
     B, A, Sq, Sk = scores.shape
+    n = scores.numel()
+    dt = _act_dtype("scores", scores)
+    _want("key_len", key_len, torch.int32, B)
+    _want("probs", probs, scores.dtype, n)
+    _want("out", out, scores.dtype, n)
+    _want("keep_bits", keep_bits, torch.int32, at_least=mask_words(n))
     _check(load().tempo_attn_softmax_dropout_fwd(
         _ptr(scores), _ptr(key_len), int(bool(causal)), _ptr(probs), _ptr(out), _ptr(keep_bits),
-        B, A, Sq, Sk, p, seed, offset, _DT[scores.dtype], _stream(stream)),
+        B, A, Sq, Sk, p, seed, offset, dt, _stream(stream)),
         "tempo_attn_softmax_dropout_fwd")
 
 
 def tempo_attn_softmax_dropout_bwd(dout, probs, keep_bits, dscores, out_recomputed, p, stream=None):
     B, A, Sq, Sk = probs.shape
+    n = probs.numel()
+    dt = _act_dtype("probs", probs)
+    _want("dout", dout, probs.dtype, n)
+    _want("dscores", dscores, probs.dtype, n)
+    _want("out_recomputed", out_recomputed, probs.dtype, n)
+    _want("keep_bits", keep_bits, torch.int32, at_least=mask_words(n))
     _check(load().tempo_attn_softmax_dropout_bwd(
         _ptr(dout), _ptr(probs), _ptr(keep_bits), _ptr(dscores), _ptr(out_recomputed),
-        B, A, Sq, Sk, p, _DT[probs.dtype], _stream(stream)), "tempo_attn_softmax_dropout_bwd")
+        B, A, Sq, Sk, p, dt, _stream(stream)),
+        "tempo_attn_softmax_dropout_bwd")
 
 
 def tempo_attn_softmax_dropout_bwd_regen(dout, probs, dscores, out_recomputed, p, seed, offset,
                                          stream=None):
     B, A, Sq, Sk = probs.shape
+    n = probs.numel()
+    dt = _act_dtype("probs", probs)
+    _want("dout", dout, probs.dtype, n)
+    _want("dscores", dscores, probs.dtype, n)
+    _want("out_recomputed", out_recomputed, probs.dtype, n)
     _check(load().tempo_attn_softmax_dropout_bwd_regen(
         _ptr(dout), _ptr(probs), _ptr(dscores), _ptr(out_recomputed), B, A, Sq, Sk, p, seed,
-        offset, _DT[probs.dtype], _stream(stream)), "tempo_attn_softmax_dropout_bwd_regen")
+        offset, dt, _stream(stream)), "tempo_attn_softmax_dropout_bwd_regen")
 
 
 def tempo_mask_bits_to_bytes(bits, bytes_, n, stream=None):
+    _want("bits", bits, torch.int32, at_least=mask_words(n))
+    _want("bytes", bytes_, torch.uint8, at_least=n)
     _check(load().tempo_mask_bits_to_bytes(_ptr(bits), _ptr(bytes_), n, _stream(stream)),
            "tempo_mask_bits_to_bytes")
 
 
 def tempo_mask_bytes_to_bits(bytes_, bits, n, stream=None):
+    _want("bits", bits, torch.int32, at_least=mask_words(n))
+    _want("bytes", bytes_, torch.uint8, at_least=n)
     _check(load().tempo_mask_bytes_to_bits(_ptr(bytes_), _ptr(bits), n, _stream(stream)),
            "tempo_mask_bytes_to_bits")

@@ -166,9 +166,10 @@ tempo_status tempo_layernorm_fwd(const void* x, const float* gamma, const float*
 
 size_t tempo_layernorm_bwd_workspace_bytes(int64_t N, int64_t M) {
   if (N <= 0 || M <= 0 || M > INT32_MAX || !count_ok(N, M)) return 0;
-  // the larger of the two dtypes' grids, so one query serves both
-  const int a = layernorm_bwd_blocks(N, M, TEMPO_F32), b = layernorm_bwd_blocks(N, M, TEMPO_BF16);
-  return static_cast<size_t>(a > b ? a : b) * 2 * static_cast<size_t>(M) * sizeof(float);
+  // the larger of the two dtypes' needs, so one query serves both
+  const size_t a = layernorm_bwd_workspace_bytes(N, M, TEMPO_F32);
+  const size_t b = layernorm_bwd_workspace_bytes(N, M, TEMPO_BF16);
+  return a > b ? a : b;
 }
 
 tempo_status tempo_layernorm_bwd(const void* dy, const void* y, const float* gamma,
@@ -184,9 +185,8 @@ tempo_status tempo_layernorm_bwd(const void* dy, const void* y, const float* gam
       !aligned16(rstd) || !aligned16(dx) || !aligned16(dgamma) || !aligned16(dbeta) ||
       !aligned16(workspace))
     return TEMPO_ERR_UNSUPPORTED;
-  if (workspace_bytes < tempo_layernorm_bwd_workspace_bytes(N, M)) return TEMPO_ERR_WORKSPACE;
   return launch_layernorm_bwd(dy, y, gamma, beta, rstd, dx, dgamma, dbeta,
-                              static_cast<float*>(workspace), N, M, dt,
+                              static_cast<float*>(workspace), workspace_bytes, N, M, dt,
                               static_cast<hipStream_t>(hip_stream));
 }
 

@@ -20,7 +20,7 @@ constexpr int kFwdThreads = 256;
 constexpr int kBwdWaves = 8;
 constexpr int kBwdThreads = kBwdWaves * kWave;
 constexpr int kMaxFastM = 4096;  // rows longer than this take the generic kernels; the backward
-                                 // LDS tree needs 16*M bytes (64 KiB at 4096)
+                                 // LDS tree needs 32*M bytes (128 KiB at 4096)
 
 // Forward.  A batch is kGroups*R consecutive rows; lane group g takes rows base + r*kGroups + g
 // and fetches all R of them (packed) before any arithmetic, so that short rows still keep
@@ -692,16 +692,16 @@ tempo_status launch_layernorm_fwd(const void* x, const float* gamma, const float
 // keeps one workgroup per compute unit.  If that leaves more batches than the knob's number of
 // workgroups per compute unit (default 1), workgroups loop with prefetch instead (two batches
 // are then held in registers: half the rows per batch for one-piece rows, one row otherwise) on
-// a grid of that many workgroups per compute unit.
+// a grid of that many workgroups per compute unit.  A grid that does not loop has exactly one
+// workgroup per batch, however many that is.
 struct BwdPlan {
   int r;
   bool loop;
   int grid;
 };
-static BwdPlan bwd_plan(int64_t N, const Shape& sh, tempo_dtype dt) {
+static BwdPlan bwd_plan(int64_t N, const Shape& sh) {
   const int tuned = tune_get(kTuneLnBwdRowsPerGroup);
   const int regs_per_row = sh.ch * 8;  // dy and y, 4 registers per packed piece
-  (void)dt;
   const int64_t groups = kBwdThreads / sh.lanes;
   const int cus = compute_units();
   auto batches = [&](int r) { return (N + groups * r - 1) / (groups * r); };
@@ -710,12 +710,16 @@ static BwdPlan bwd_plan(int64_t N, const Shape& sh, tempo_dtype dt) {
       sh.lanes > 64 ? 1 : ((sh.ch <= 2 && sh.lanes == 64) ? 4 : (sh.ch <= 4 ? 2 : 1));
   if (r > avail) r = avail;
   while (r > 1 && (r * regs_per_row > 64 || batches(r) < cus)) r >>= 1;
-  BwdPlan p = {r, false, static_cast<int>(batches(r) > 4096 ? 4096 : batches(r))};
-  const int per_cu = tune_get(kTuneLnBwdLoopBlocksPerCu);
-  if (batches(r) > static_cast<int64_t>(per_cu) * cus) {
+  const int64_t most = static_cast<int64_t>(tune_get(kTuneLnBwdLoopBlocksPerCu)) * cus;
+  BwdPlan p;
+  if (batches(r) > most) {
     p.loop = true;
     p.r = (r > 1 && sh.ch == 1) ? r / 2 : 1;  // measured: rows of 2 pieces per lane loop best alone
-    p.grid = per_cu * cus;
+    p.grid = static_cast<int>(most);
+  } else {
+    p.loop = false;
+    p.r = r;
+    p.grid = static_cast<int>(batches(r));  // <= most <= 65536 * compute units
   }
   if (p.grid < 1) p.grid = 1;
   return p;
@@ -776,21 +780,45 @@ static int ln_bwd_go(const BwdPlan& plan, size_t lds_bytes, hipStream_t st, cons
   return grid;
 }
 
-int layernorm_bwd_blocks(int64_t N, int64_t M, tempo_dtype dt) {
+// Everything a backward launch depends on, taken from the knobs once: the workspace check and
+// the launch of one call always see the same plan.
+struct BwdLaunch {
+  bool fast;    // register-resident kernel (else the any-M kernel)
   Shape sh;
-  if (fast_shape(M, dt, true, &sh)) return bwd_plan(N, sh, dt).grid;
-  return static_cast<int>(N > 4096 ? 4096 : (N < 1 ? 1 : N));  // one row per workgroup, strided
+  BwdPlan plan;
+  int slots;    // partial [2][M] slots the row kernel may write: an upper bound of its grid
+};
+static BwdLaunch bwd_launch(int64_t N, int64_t M, tempo_dtype dt) {
+  BwdLaunch b;
+  b.fast = fast_shape(M, dt, true, &b.sh);
+  if (b.fast) {
+    b.plan = bwd_plan(N, b.sh);
+    b.slots = b.plan.grid;
+  } else {
+    b.plan = {1, true, static_cast<int>(N > 4096 ? 4096 : (N < 1 ? 1 : N))};  // one row per workgroup, strided
+    b.slots = b.plan.grid;
+  }
+  return b;
+}
+static size_t slot_bytes(const BwdLaunch& b, int64_t M) {
+  return static_cast<size_t>(b.slots) * 2 * static_cast<size_t>(M) * sizeof(float);
+}
+
+size_t layernorm_bwd_workspace_bytes(int64_t N, int64_t M, tempo_dtype dt) {
+  return slot_bytes(bwd_launch(N, M, dt), M);
 }
 
 tempo_status launch_layernorm_bwd(const void* dy, const void* y, const float* gamma,
                                   const float* beta, const float* rstd, void* dx, float* dgamma,
-                                  float* dbeta, float* workspace, int64_t N, int64_t M,
-                                  tempo_dtype dt, hipStream_t st) {
-  Shape sh;
-  int grid = layernorm_bwd_blocks(N, M, dt);  // upper bound: the workspace has this many slots
-  if (fast_shape(M, dt, true, &sh)) {
+                                  float* dbeta, float* workspace, size_t workspace_bytes,
+                                  int64_t N, int64_t M, tempo_dtype dt, hipStream_t st) {
+  const BwdLaunch b = bwd_launch(N, M, dt);
+  if (workspace_bytes < slot_bytes(b, M)) return TEMPO_ERR_WORKSPACE;
+  int grid = b.plan.grid;
+  if (b.fast) {
+    const Shape sh = b.sh;
     const size_t lds_bytes = static_cast<size_t>(kBwdWaves / 2) * 2 * M * sizeof(float);
-    const BwdPlan plan = bwd_plan(N, sh, dt);
+    const BwdPlan plan = b.plan;
 #define TEMPO_LAUNCH(L, C)                                                                   \
   do {                                                                                       \
     if (dt == TEMPO_F32) grid = ln_bwd_go<float, L, C>(plan, lds_bytes, st, dy, y, gamma, beta, rstd, dx, workspace, N, M);   \

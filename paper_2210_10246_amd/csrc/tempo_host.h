@@ -5,6 +5,7 @@
 #include <stdint.h>
 
 #include "../../include/tempo.h"
+#include "../../include/tempo_tune.h"
 
 namespace tempo {
 
@@ -42,11 +43,13 @@ tempo_status launch_gelu_bwd(const void* dy, const void* y, const uint32_t* mask
 tempo_status launch_layernorm_fwd(const void* x, const float* gamma, const float* beta, void* y,
                                   float* rstd, float* mean, int64_t N, int64_t M, float eps,
                                   tempo_dtype dt, hipStream_t st);
-int layernorm_bwd_blocks(int64_t N, int64_t M, tempo_dtype dt);
+size_t layernorm_bwd_workspace_bytes(int64_t N, int64_t M, tempo_dtype dt);
+// TEMPO_ERR_WORKSPACE if workspace_bytes is less than this call's launch plan needs.
 tempo_status launch_layernorm_bwd(const void* dy, const void* y, const float* gamma,
                                   const float* beta, const float* rstd, void* dx, float* dgamma,
-                                  float* dbeta, float* workspace, int64_t N, int64_t M,
-                                  tempo_dtype dt, hipStream_t st);
+                                  float* dbeta, float* workspace, size_t workspace_bytes,
+                                  int64_t N, int64_t M, tempo_dtype dt, hipStream_t st);
+
 tempo_status launch_attn_fwd(const void* scores, const int32_t* key_len, int causal, void* probs,
                              void* out, uint32_t* keep_bits, int64_t B, int64_t A, int64_t Sq,
                              int64_t Sk, float p, uint64_t seed, uint64_t offset, tempo_dtype dt,

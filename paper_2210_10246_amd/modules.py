@@ -106,8 +106,21 @@ class InplaceLayerNorm(nn.Module):
         self.bias = nn.Parameter(torch.zeros(hidden, dtype=torch.float32))
         self.eps = eps
 
+    def _apply(self, fn, recurse=True):
+        # .bfloat16() / .half() / .to(dtype) on a model must not narrow gamma and beta: the
+        # kernels read them as float32.  Follow the device of the cast, keep the values.
+        def keep_float32(t):
+            out = fn(t)
+            if t.dtype == torch.float32 and out.dtype != torch.float32:
+                out = t.to(device=out.device)
+            return out
+        return super()._apply(keep_float32, recurse)
+
     def forward(self, x):
-        return _InplaceLayerNormFn.apply(x, self.weight, self.bias, self.eps)
+        w, b = self.weight, self.bias
+        if w.dtype != torch.float32 or b.dtype != torch.float32:   # parameters replaced by hand
+            w, b = w.float(), b.float()
+        return _InplaceLayerNormFn.apply(x, w, b, self.eps)
 
 
 class _AttentionCoreFn(torch.autograd.Function):

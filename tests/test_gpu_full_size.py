@@ -1,8 +1,9 @@
 """Parity at the full sizes of the benchmark configurations, in the launch configuration
 bench.py times (library defaults), on the seeded synthetic workloads.
 
-Where the float64 oracle is cheap (GELU forward, LayerNorm, attention of config 1) the whole
-tensor is compared; elsewhere (GELU backward: 200 bisection steps per element; the
+Every configuration is covered: 0-3 as they stand, 4 at every batch of its sweep (8, 16, 32,
+64) in both dtypes.  Where the float64 oracle is cheap (GELU forward, LayerNorm, attention of
+configs 0 and 1) the whole tensor is compared; elsewhere (GELU backward: 200 bisection steps per element; the
 [B,A,S,S] maps of configs 2-4) a sample of elements / of whole [S,S] slices is compared
 element by element, and the full keep mask is checked against its expected keep rate.
 """
@@ -19,11 +20,16 @@ from paper_2210_10246_amd import workloads as W
 pytestmark = pytest.mark.gpu
 
 CASES = [
+    pytest.param(dict(index=0), id="config0"),
     pytest.param(dict(index=1), id="config1"),
     pytest.param(dict(index=2), id="config2"),
     pytest.param(dict(index=3), id="config3"),
     pytest.param(dict(index=4, batch=8, dtype="bf16"), id="config4-b8-bf16"),
     pytest.param(dict(index=4, batch=8, dtype="f32"), id="config4-b8-f32"),
+    pytest.param(dict(index=4, batch=16, dtype="bf16"), id="config4-b16-bf16"),
+    pytest.param(dict(index=4, batch=16, dtype="f32"), id="config4-b16-f32"),
+    pytest.param(dict(index=4, batch=32, dtype="bf16"), id="config4-b32-bf16"),
+    pytest.param(dict(index=4, batch=32, dtype="f32"), id="config4-b32-f32"),
     pytest.param(dict(index=4, batch=64, dtype="bf16"), id="config4-b64-bf16"),
     pytest.param(dict(index=4, batch=64, dtype="f32"), id="config4-b64-f32"),
 ]
@@ -71,7 +77,7 @@ def test_gelu_full_size(B, case):
     assert rel_err(got, ref) <= TOL[dt]
 
 
-@pytest.mark.parametrize("case", [CASES[0], CASES[4]])
+@pytest.mark.parametrize("case", [c for c in CASES if c.id in ("config1", "config4-b8-f32")])
 def test_silu_full_size(B, case):
     """The same tensors through the SiLU entry points (Sec. 5.1)."""
     cfg = _cfg(case)
@@ -120,9 +126,12 @@ def test_layernorm_full_size(B, case):
     dx_ref, dg_ref, db_ref = O.layernorm_bwd(W.as_f64(l["dy"]), W.as_f64(yd), gamma64, beta64,
                                              W.as_f64(rd), dt)
     assert rel_err(W.as_f64(dxd), dx_ref) <= TOL[dt]
-    # column sums over N rows in float32: error grows like sqrt(N) ulp of the running sum
-    assert rel_err(W.as_f64(dgd), dg_ref) <= 4 * TOL["f32"]
-    assert rel_err(W.as_f64(dbd), db_ref) <= 4 * TOL["f32"]
+    # column sums over N rows, float32 partial sums added in a fixed near-pairwise order: held to
+    # the same bar as every other float32 result (the measured error is printed for the record)
+    e_dg, e_db = rel_err(W.as_f64(dgd), dg_ref), rel_err(W.as_f64(dbd), db_ref)
+    print(f"layernorm_bwd {case}: N={N} M={M} dgamma err {e_dg:.2e} dbeta err {e_db:.2e}")
+    assert e_dg <= TOL["f32"]
+    assert e_db <= TOL["f32"]
 
 
 @pytest.mark.parametrize("case", CASES)

@@ -73,8 +73,8 @@ def test_layernorm_random_shapes(B, dt):
                          device="cuda")
         B.tempo_layernorm_bwd(dev(dy, dt), dev(y, dt), gd, bd, dev(rstd, "f32"), dxd, dgd, dbd, ws)
         assert rel_err(host(dxd), dx_ref) <= TOL[dt], (N, M)
-        assert rel_err(host(dgd), dg_ref) <= 2 * TOL["f32"], (N, M)
-        assert rel_err(host(dbd), db_ref) <= 2 * TOL["f32"], (N, M)
+        assert rel_err(host(dgd), dg_ref) <= TOL["f32"], (N, M)
+        assert rel_err(host(dbd), db_ref) <= TOL["f32"], (N, M)
 
 
 @pytest.mark.parametrize("dt", ["f32", "bf16"])
