@@ -206,7 +206,13 @@ def test_layernorm_bwd(B, shape, dt):
     ws = torch.empty(max(B.tempo_layernorm_bwd_workspace_bytes(N, M), 16), dtype=torch.uint8, device="cuda")
     B.tempo_layernorm_bwd(dyd, yd, gd, bd, rd, dxd, dgd, dbd, ws)
     torch.cuda.synchronize()
-    assert rel_err(host(dxd), dx_ref) <= TOL[dt]
+    if M == 1:
+        # dx is nothing but the cancellation dy*gamma - dy*gamma (the stored y differs from beta
+        # only by its rounding): the error is measured against the terms that cancel
+        terms = np.abs(dy * gamma * rstd[:, None]).max()
+        assert np.abs(host(dxd) - dx_ref).max() <= 4 * 2.0 ** -24 * terms
+    else:
+        assert rel_err(host(dxd), dx_ref) <= TOL[dt]
     assert rel_err(host(dgd), dg_ref) <= TOL["f32"]
     assert rel_err(host(dbd), db_ref) <= TOL["f32"]
     dg2, db2 = torch.empty_like(dgd), torch.empty_like(dbd)
@@ -215,7 +221,7 @@ def test_layernorm_bwd(B, shape, dt):
     assert torch.equal(dyd, dxd)
     assert torch.equal(dg2, dgd) and torch.equal(db2, dbd)          # fixed summation order
     with pytest.raises(B.TempoError):
-        B.tempo_layernorm_bwd(dyd, yd, gd, bd, rd, dxd, dgd, dbd, ws[:16])
+        B.tempo_layernorm_bwd(dyd, yd, gd, bd, rd, dxd, dgd, dbd, ws[:2 * M * 4 - 1])   # under one slot
 
 
 @pytest.mark.parametrize("dt", ["f32", "bf16"])
