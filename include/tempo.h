@@ -127,6 +127,28 @@ TEMPO_API tempo_status tempo_layernorm_bwd(const void* dy, const void* y, const 
                                  int64_t N, int64_t M, tempo_dtype dt, void* hip_stream);
 
 /*
+ * tempo_layernorm_bwd for callers that cannot allocate device memory: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels
+ * and bit-identical results, but the partial column sums go to a scratch array of
+ * TEMPO_STATIC_SCRATCH_BYTES that lives in the library's code object (one copy per GPU, held
+ * until the process ends) instead of a caller's workspace.  The call allocates nothing and
+ * frees nothing.  Nothing in the array has to be zero between calls (every slot that is read
+ * is written first by the same call).
+ *   TEMPO_ERR_WORKSPACE: the problem needs more scratch than the array holds.  With the default
+ *   launch shapes every M <= 4096 that is a multiple of 8 (bfloat16) or 4 (float32) fits for any
+ *   N; other M fit while min(N, 4096) * 8 * M bytes do.
+ *   TEMPO_ERR_LAUNCH: the array's device address could not be obtained.
+ * All calls on one GPU share that GPU's array: calls that may run at the same time on one GPU
+ * (different streams, or graphs replayed concurrently) race on it and must be serialised by the
+ * caller; calls on different GPUs are independent.
+ */
+#define TEMPO_STATIC_SCRATCH_BYTES (8u << 20)
+TEMPO_API tempo_status tempo_layernorm_bwd_static(const void* dy, const void* y, const float* gamma,
+                                 const float* beta, const float* rstd,
+                                 void* dx, float* dgamma, float* dbeta,
+                                 int64_t N, int64_t M, tempo_dtype dt, void* hip_stream);
+
+/*
  * Attention softmax -> dropout forward, keeping only P and a bit mask  [Sec. 3.3, 3.4; App. E.3, E.4]
  *   scores [B,A,Sq,Sk] in (dt), already scaled by 1/sqrt(d).
  *   key_len [B] int32 in, may be NULL: key column j >= key_len[b] is masked (treated as -inf).

@@ -38,6 +38,8 @@ _SIGNATURES = {
     "tempo_layernorm_bwd_workspace_bytes": (_sz, [_i64, _i64]),
     "tempo_layernorm_bwd": (_int, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _i64, _i64,
                                    _int, _vp]),
+    "tempo_layernorm_bwd_static": (_int, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i64, _i64, _int,
+                                          _vp]),
     "tempo_attn_softmax_dropout_fwd": (_int, [_vp, _vp, _int, _vp, _vp, _vp, _i64, _i64, _i64,
                                               _i64, _f32, _u64, _u64, _int, _vp]),
     "tempo_attn_softmax_dropout_bwd": (_int, [_vp, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _i64,
@@ -211,6 +213,23 @@ def tempo_layernorm_bwd(dy, y, gamma, beta, rstd, dx, dgamma, dbeta, workspace, 
                                       _ptr(dx), _ptr(dgamma), _ptr(dbeta), _ptr(workspace),
                                       ws_bytes, N, M, dt, _stream(stream)),
            "tempo_layernorm_bwd")
+
+
+def tempo_layernorm_bwd_static(dy, y, gamma, beta, rstd, dx, dgamma, dbeta, stream=None):
+    """tempo_layernorm_bwd with the library's static scratch array as workspace."""
+    M = y.shape[-1]
+    N = y.numel() // M if M else 0
+    dt = _act_dtype("y", y)
+    _want("dy", dy, y.dtype, y.numel())
+    _want("dx", dx, y.dtype, y.numel())
+    _want("gamma", gamma, torch.float32, M)
+    _want("beta", beta, torch.float32, M)
+    _want("rstd", rstd, torch.float32, N)
+    _want("dgamma", dgamma, torch.float32, M)
+    _want("dbeta", dbeta, torch.float32, M)
+    _check(load().tempo_layernorm_bwd_static(_ptr(dy), _ptr(y), _ptr(gamma), _ptr(beta), _ptr(rstd),
+                                             _ptr(dx), _ptr(dgamma), _ptr(dbeta), N, M, dt,
+                                             _stream(stream)), "tempo_layernorm_bwd_static")
 
 
 def tempo_attn_softmax_dropout_fwd(scores, key_len, causal, probs, out, keep_bits, p, seed, offset,

@@ -190,6 +190,27 @@ tempo_status tempo_layernorm_bwd(const void* dy, const void* y, const float* gam
                               static_cast<hipStream_t>(hip_stream));
 }
 
+tempo_status tempo_layernorm_bwd_static(const void* dy, const void* y, const float* gamma,
+                                        const float* beta, const float* rstd, void* dx,
+                                        float* dgamma, float* dbeta, int64_t N, int64_t M,
+                                        tempo_dtype dt, void* hip_stream) {
+  if (N < 0 || M < 0 || !dtype_ok(dt) || M > INT32_MAX || !count_ok(N, M))
+    return TEMPO_ERR_INVALID_ARG;
+  if (N == 0 || M == 0) return TEMPO_OK;
+  if (!dy || !y || !gamma || !beta || !rstd || !dx || !dgamma || !dbeta)
+    return TEMPO_ERR_INVALID_ARG;
+  if (!aligned16(dy) || !aligned16(y) || !aligned16(gamma) || !aligned16(beta) ||
+      !aligned16(rstd) || !aligned16(dx) || !aligned16(dgamma) || !aligned16(dbeta))
+    return TEMPO_ERR_UNSUPPORTED;
+  void* ptr = nullptr;
+  const tempo_status got = static_scratch(&ptr);
+  if (got != TEMPO_OK) return got;
+  // the launcher checks the plan's need against the array's size before it launches anything
+  return launch_layernorm_bwd(dy, y, gamma, beta, rstd, dx, dgamma, dbeta,
+                              static_cast<float*>(ptr), TEMPO_STATIC_SCRATCH_BYTES, N, M, dt,
+                              static_cast<hipStream_t>(hip_stream));
+}
+
 tempo_status tempo_attn_softmax_dropout_fwd(const void* scores, const int32_t* key_len, int causal,
                                             void* probs, void* out, uint32_t* keep_bits, int64_t B,
                                             int64_t A, int64_t Sq, int64_t Sk, float p,

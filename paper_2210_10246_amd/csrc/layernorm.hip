@@ -843,4 +843,28 @@ tempo_status launch_layernorm_bwd(const void* dy, const void* y, const float* ga
   return launch_status();
 }
 
+// Scratch for callers that cannot allocate: one array per GPU, living in the code object.  Its
+// name is only a host-side handle; the address kernels can use is looked up once per device.
+static __device__ __align__(256) unsigned char scratch[TEMPO_STATIC_SCRATCH_BYTES];
+constexpr int kMaxDevices = 64;
+static std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+tempo_status static_scratch(void** ptr) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+    (void)hipGetLastError();
+    return TEMPO_ERR_LAUNCH;
+  }
+  void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (p == nullptr) {  // first call on this device (threads racing here find the same address)
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) {
+      (void)hipGetLastError();
+      return TEMPO_ERR_LAUNCH;
+    }
+    g_scratch_ptr[dev].store(p, std::memory_order_release);
+  }
+  *ptr = p;
+  return TEMPO_OK;
+}
+
 }  // namespace tempo

@@ -50,6 +50,8 @@ tempo_status launch_layernorm_bwd(const void* dy, const void* y, const float* ga
                                   float* dbeta, float* workspace, size_t workspace_bytes,
                                   int64_t N, int64_t M, tempo_dtype dt, hipStream_t st);
 
+// Device address of the current device's static scratch array (TEMPO_STATIC_SCRATCH_BYTES).
+tempo_status static_scratch(void** ptr);
 tempo_status launch_attn_fwd(const void* scores, const int32_t* key_len, int causal, void* probs,
                              void* out, uint32_t* keep_bits, int64_t B, int64_t A, int64_t Sq,
                              int64_t Sk, float p, uint64_t seed, uint64_t offset, tempo_dtype dt,
