@@ -50,7 +50,9 @@ __device__ __forceinline__ float cubic(const f32x4 c, float z) {
   return fmaf(fmaf(fmaf(c.w, z, c.z), z, c.y), z, c.x);
 }
 
-// GELU(x), erf form: cubic pieces of width 1/16 on [-8, 8); x outside is x (right) or -0.
+// GELU(x) = x Phi(x), erf form: Phi as cubic pieces of width 1/16 on [-8, 8); x outside is x
+// (right) or -0 (left).  Multiplying by x keeps the zero at x = 0 exact and the relative error
+// that of Phi however small |x| is.
 __device__ __forceinline__ float gelu_erf_value(float x, const f32x4* tab) {
   const float t = x * static_cast<float>(TEMPO_GELU_FWD_PER_UNIT);
   const float lo = TEMPO_GELU_FWD_LO * TEMPO_GELU_FWD_PER_UNIT;
@@ -58,7 +60,7 @@ __device__ __forceinline__ float gelu_erf_value(float x, const f32x4* tab) {
   const float fl = floorf(fminf(fmaxf(t, lo), hi));
   const float z = t - fl;  // exact inside the table range; NaN stays NaN
   const int idx = static_cast<int>(fl) - static_cast<int>(lo);
-  float y = cubic(tab[idx], z);
+  float y = x * cubic(tab[idx], z);
   y = (x >= TEMPO_GELU_FWD_HI) ? x : y;
   y = (x < TEMPO_GELU_FWD_LO) ? -0.0f : y;
   return y;

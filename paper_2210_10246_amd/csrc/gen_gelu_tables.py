@@ -3,7 +3,7 @@
 kernels: GELU in its erf and tanh forms, and SiLU (the same recipe on another activation with
 a single minimum, Sec. 5.1).  "GELU" and G below stand for whichever of the three is meant.
 
-    python paper_2210_10246_amd/csrc/gen_gelu_tables.py
+    python paper_2210_10246_amd/csrc/gen_gelu_tables.py [output path]
 
 Backward composite d(y, m) = GELU'(GELU*^-1(y, m))  (App. E.1 eq. 2).  The paper fits
 piecewise polynomials of degree up to 13 in y (App. F.1) without printing them; a
@@ -23,8 +23,11 @@ No inversion is needed to fit: sample x densely, compute y = GELU(x) and d = GEL
 exactly in float64, derive the piece and local variable from y, least-squares fit in the
 Chebyshev basis per piece.  The script prints the worst absolute error of each region.
 
-Forward (erf kind) table: GELU(x) itself as cubics on uniform pieces of width 1/16 in
-x over [-8, 8); outside, GELU(x) = x (right) or -0 (left) to below 1e-14.
+Forward (erf kind) table: the factor Phi(x) of GELU(x) = x Phi(x) as cubics on uniform pieces
+of width 1/16 in x over [-8, 8); the kernel multiplies by x, so that GELU(0) = 0 exactly and
+the relative error stays that of Phi for arbitrarily small |x| (a cubic of GELU itself leaves
+an absolute error of ~1e-9 around its zero).  Outside the range GELU(x) = x (right) or -0 (left)
+to below 1e-14.
 
 bfloat16 lookup tables.  A bfloat16 input has only 2^16 bit patterns, so for bf16 storage
 both GELU and the backward composite are tabulated per pattern instead of being evaluated:
@@ -35,10 +38,14 @@ both GELU and the backward composite are tabulated per pattern instead of being 
   backward  D[m][sign][k] = d(y, m) as float32, same key; the left branch (m=0) shifts the key
             window down by 6 octaves to [2^-18, 2^-2) where d still matters (|d| < 5e-5 below).
             m=0 with y >= 0 is all zero (cannot come from a forward).
-The table entries need d at given y: here (and only here) x is found by bisection.
+The table entries need d at a given y.  No root finder is run per entry: the branch is sampled
+densely forward (x -> y, d), x at the wanted y is read off by linear interpolation in a
+variable in which x is smooth (sqrt(y - y*) next to the minimum, log(-y) on the left tail), and
+one Newton step on G(x) = y takes the interpolation error (<= 1e-9) to rounding level.
 
-This file shares nothing with the CPU checker: its GELU, derivative and minimum search
-are written here with the math/scipy primitives only.
+This file shares nothing with the CPU checker: the three activations and their derivatives are
+written here on scipy's normal distribution function and logistic function, the minimum is
+found with scipy's Brent root finder on the derivative.
 """
 import math
 import os
@@ -47,7 +54,8 @@ import struct
 import numpy as np
 from numpy.polynomial import chebyshev as cheb
 from numpy.polynomial import polynomial as poly
-from scipy.special import erfc
+from scipy.optimize import brentq
+from scipy.special import expit, ndtr
 
 CR = 32          # right-branch pieces per unit s
 CL = 64          # left-branch pieces per unit s
@@ -59,14 +67,13 @@ CL = 64          # left-branch pieces per unit s
 #   bracket  an interval around the minimum on which G' changes sign once
 #   lut_left_shift  how many bf16 patterns lower the left branch's lookup window starts:
 #       GELU 6 octaves ([2^-18, 2^-2), y* = -0.17), SiLU 5 octaves ([2^-17, 2^-1), y* = -0.28)
-#   left_floor  lower end of the bisection bracket of the left branch
 GEOM = {
     "erf": dict(NR=82, NL=21, right_top=9.0, left_span=14.5, bracket=(-1.0, -0.5),
-                lut_left_shift=0x300, left_floor=-64.0),
+                lut_left_shift=0x300),
     "tanh": dict(NR=82, NL=21, right_top=9.0, left_span=14.5, bracket=(-1.0, -0.5),
-                 lut_left_shift=0x300, left_floor=-64.0),
+                 lut_left_shift=0x300),
     "silu": dict(NR=136, NL=30, right_top=19.0, left_span=30.0, bracket=(-2.0, -1.0),
-                 lut_left_shift=0x280, left_floor=-128.0),
+                 lut_left_shift=0x280),
 }
 KINDS = ("erf", "tanh", "silu")
 TAIL_TOP_EXP = -4          # tail is -y < 2^-4
@@ -81,38 +88,38 @@ A_TANH = 0.044715
 K_TANH = math.sqrt(2.0 / math.pi)
 
 
-def g_val(x, kind):
+def inner(x):
+    """Argument 2u of the logistic function in the tanh form, and its derivative."""
+    return 2.0 * K_TANH * (x + A_TANH * x**3), 2.0 * K_TANH * (1.0 + 3.0 * A_TANH * x * x)
+
+
+def factor(x, kind):
+    """G(x) / x: the normal distribution function (erf form), logistic(2u) (tanh form, which is
+    0.5 (1 + tanh u) without the cancellation on the left), logistic(x) (SiLU)."""
     if kind == "erf":
-        return x * 0.5 * erfc(-x / math.sqrt(2.0))
+        return ndtr(x)
     if kind == "silu":
-        with np.errstate(over="ignore"):
-            return x / (1.0 + np.exp(-x))
-    u = K_TANH * (x + A_TANH * x**3)
-    with np.errstate(over="ignore"):
-        return x / (1.0 + np.exp(-2.0 * u))
+        return expit(x)
+    return expit(inner(x)[0])
+
+
+def g_val(x, kind):
+    return x * factor(x, kind)
 
 
 def g_der(x, kind):
+    """(x f(x))' = f + x f'; the logistic function has s' = s(v) s(-v)."""
     if kind == "erf":
-        return 0.5 * erfc(-x / math.sqrt(2.0)) + x * np.exp(-0.5 * x * x) / math.sqrt(2.0 * math.pi)
+        return ndtr(x) + x * np.exp(-0.5 * x * x) / math.sqrt(2.0 * math.pi)
     if kind == "silu":
-        with np.errstate(over="ignore"):
-            return (1.0 + x / (1.0 + np.exp(x))) / (1.0 + np.exp(-x))
-    u = K_TANH * (x + A_TANH * x**3)
-    with np.errstate(over="ignore"):
-        sg = 1.0 / (1.0 + np.exp(-2.0 * u))
-    return sg + x * sg * (1.0 - sg) * 2.0 * K_TANH * (1.0 + 3.0 * A_TANH * x * x)
+        return expit(x) * (1.0 + x * expit(-x))
+    v, dv = inner(x)
+    return expit(v) * (1.0 + x * expit(-v) * dv)
 
 
 def minimum(kind):
     lo, hi = GEOM[kind]["bracket"]
-    for _ in range(200):
-        mid = 0.5 * (lo + hi)
-        if g_der(np.float64(mid), kind) < 0:
-            lo = mid
-        else:
-            hi = mid
-    xs = 0.5 * (lo + hi)
+    xs = brentq(lambda t: float(g_der(np.float64(t), kind)), lo, hi, xtol=1e-16, rtol=8.9e-16)
     return xs, float(g_val(np.float64(xs), kind))
 
 
@@ -194,7 +201,7 @@ def fwd_table():
         a = FWD_LO + i / FWD_PER_UNIT
         z = 0.5 - 0.5 * np.cos(np.linspace(0, math.pi, 400))
         x = a + z / FWD_PER_UNIT
-        rows[i], e = fit_piece(z, g_val(x, "erf"))
+        rows[i], e = fit_piece(z, factor(x, "erf"))
         worst = max(worst, e)
     return rows, worst
 
@@ -207,18 +214,36 @@ def bf16_value(pattern):
     return np.array(pattern, dtype=np.uint32).astype(np.uint32).__lshift__(16).view(np.float32).astype(np.float64)
 
 
-def invert(y, right, kind, xs):
-    """x with G(x) = y on one branch, bisection in float64."""
-    y = np.asarray(y, dtype=np.float64)
-    lo = np.full(y.shape, xs if right else GEOM[kind]["left_floor"])
-    hi = np.maximum(y, 0.0) + 1.0 if right else np.full(y.shape, xs)
-    for _ in range(200):
-        mid = 0.5 * (lo + hi)
-        g = g_val(mid, kind)
-        up = (g < y) if right else (g > y)
-        lo = np.where(up, mid, lo)
-        hi = np.where(up, hi, mid)
-    return 0.5 * (lo + hi)
+class Branch:
+    """One monotone branch of G sampled forward, for reading x off at given y."""
+
+    def __init__(self, kind, right, xs, ys, n=4_000_001):
+        self.kind, self.right, self.xs, self.ys = kind, right, xs, ys
+        t = np.linspace(0.0, 1.0, n) ** 2          # dense next to the minimum
+        geo = GEOM[kind]
+        # right: up to where y reaches the largest table key (bf16 values below 16, G(x) > x - 1)
+        # left: as far as the cubic fit samples, beyond the smallest |y| of the table's window
+        x = xs + t * (17.5 - xs) if right else xs - t * geo["left_span"]
+        y = g_val(x, kind)
+        self.x = x
+        self.s = np.sqrt(np.maximum(y - ys, 0.0))                  # increasing along the samples
+        with np.errstate(divide="ignore"):
+            self.neg_log = -np.log(np.maximum(-y, 1e-320))         # left branch: increasing too
+
+    def x_at(self, y):
+        y = np.asarray(y, dtype=np.float64)
+        x = np.interp(np.sqrt(np.maximum(y - self.ys, 0.0)), self.s, self.x)
+        if not self.right:                                          # tail: x is smooth in log(-y)
+            tail = y > -(2.0 ** TAIL_TOP_EXP)
+            with np.errstate(divide="ignore", invalid="ignore"):
+                x_t = np.interp(-np.log(-y), self.neg_log, self.x)
+            x = np.where(tail, x_t, x)
+        # one Newton step on G(x) - y (skipped where G' vanishes: y at the minimum itself)
+        d = g_der(x, self.kind)
+        ok = np.abs(d) > 1e-300
+        step = np.where(ok, (g_val(x, self.kind) - y) / np.where(ok, d, 1.0), 0.0)
+        x = x - step
+        return np.maximum(x, self.xs) if self.right else np.minimum(x, self.xs)
 
 
 def lut_tables(kind):
@@ -229,26 +254,25 @@ def lut_tables(kind):
     fwd = np.zeros((2, LUT_N), dtype=np.uint32)
     for sgn in (0, 1):
         x = mag if sgn == 0 else -mag
-        with np.errstate(over="ignore", invalid="ignore"):
-            phi = np.where(x != 0, g_val(x, kind) / x, 0.5)
-        bits = phi.astype(np.float32).view(np.uint32)
+        bits = factor(x, kind).astype(np.float32).view(np.uint32)
         m = (x >= xs32).astype(np.uint32)
         fwd[sgn] = (bits & np.uint32(0xFFFFFFFE)) | m
     bwd = np.zeros((2, 2, LUT_N), dtype=np.float32)      # [m][sign][k]
+    right, left = Branch(kind, True, xs, ys), Branch(kind, False, xs, ys)
     # right branch, y >= 0 and y < 0
     y = mag
-    bwd[1, 0] = g_der(invert(y, True, kind, xs), kind)
+    bwd[1, 0] = g_der(right.x_at(y), kind)
     y = -mag
     ok = y > ys
     d = np.zeros(LUT_N)
-    d[ok] = g_der(invert(y[ok], True, kind, xs), kind)
+    d[ok] = g_der(right.x_at(y[ok]), kind)
     bwd[1, 1] = d                                        # y <= y*: 0
     # left branch, y < 0, key window some octaves lower
     magl = bf16_value(LUT_LO - GEOM[kind]["lut_left_shift"] + k)
     y = -magl
     ok = y > ys
     d = np.zeros(LUT_N)
-    d[ok] = g_der(invert(y[ok], False, kind, xs), kind)
+    d[ok] = g_der(left.x_at(y[ok]), kind)
     bwd[0, 1] = d
     return fwd.reshape(-1), bwd.reshape(-1).view(np.uint32)
 
@@ -273,7 +297,7 @@ def emit_rows(name, rows):
     return out
 
 
-def main():
+def main(path=None):
     lines = [
         "// Generated by gen_gelu_tables.py -- do not edit.  IEEE binary32 bit patterns.",
         "#pragma once",
@@ -319,9 +343,10 @@ def main():
         lines += emit_flat(f"tempo_gelu_lut_bwd_{kind}", bwd)
     rows, worst = fwd_table()
     lines += emit_rows("tempo_gelu_fwd_table_erf", rows)
-    report.append(f"fwd erf table: {worst:.2e}")
+    report.append(f"fwd erf table (Phi): {worst:.2e}")
     lines.insert(1, "// worst abs fit error (float64 coefficients): " + "; ".join(report))
-    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "gelu_tables.inc")
+    if path is None:
+        path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "gelu_tables.inc")
     with open(path, "w") as f:
         f.write("\n".join(lines) + "\n")
     print("\n".join(report))
@@ -329,4 +354,5 @@ def main():
 
 
 if __name__ == "__main__":
-    main()
+    import sys
+    main(sys.argv[1] if len(sys.argv) > 1 else None)
