@@ -85,6 +85,8 @@ def algorithmic_bytes(cfg, key_len=None):
         "attn_bwd": n_a * 4 * e + n_a / 8,
         # variant outside the step: backward that draws the keep bits again, no mask read
         "attn_bwd_regen": n_a * 4 * e,
+        # and the backward that reads the paper's mask layout, one byte per element
+        "attn_bwd_bytemask": n_a * 4 * e + n_a,
         # the activation kernels on SiLU tables (same traffic as GELU)
         "silu_fwd": n_g * 2 * e + n_g / 8,
         "silu_bwd": n_g * 3 * e + n_g / 8,
@@ -221,6 +223,12 @@ def measure(cfg, args, headline):
 
     def k_attn_bwd_regen(s): B.tempo_attn_softmax_dropout_bwd_regen(s["do"], s["P"], s["dS"], s["out_re"], p, seed, 0)
 
+    def k_attn_bwd_bytemask(s):
+        if "kb" not in s:      # the byte mask of this set, made once from its bit mask
+            s["kb"] = torch.empty(n_a, dtype=torch.uint8, device=dev)
+            B.tempo_mask_bits_to_bytes(s["k"], s["kb"], n_a)
+        B.tempo_attn_softmax_dropout_bwd_bytemask(s["do"], s["P"], s["kb"], s["dS"], s["out_re"], p)
+
     kernels = {
         "gelu_fwd": (k_gelu_fwd, gelu_b), "gelu_bwd": (k_gelu_bwd, gelu_b),
         "layernorm_fwd": (k_ln_fwd, ln_b), "layernorm_bwd": (k_ln_bwd, ln_b),
@@ -231,6 +239,7 @@ def measure(cfg, args, headline):
 
     # timed, not part of the step
     variants = {"attn_bwd_regen": (k_attn_bwd_regen, attn_b),
+                "attn_bwd_bytemask": (k_attn_bwd_bytemask, attn_b),
                 "silu_fwd": (k_silu_fwd, gelu_b), "silu_bwd": (k_silu_bwd, gelu_b)}
 
     # every set gets a valid forward state once (backward kernels read y / P / masks)

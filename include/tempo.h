@@ -203,6 +203,20 @@ TEMPO_API tempo_status tempo_attn_softmax_dropout_bwd_regen(const void* dout, co
                                             tempo_dtype dt, void* hip_stream);
 
 /*
+ * The same backward reading a mask of one byte per element            [Sec. 3.3 (8-bit masks)]
+ *   The paper's implementation keeps the dropout mask as 8-bit booleans.  This entry point
+ *   consumes such a mask directly (no conversion pass): keep_bytes [B A Sq Sk] device bytes,
+ *   element e kept iff keep_bytes[e] != 0.  Everything else as
+ *   tempo_attn_softmax_dropout_bwd, with which it agrees bit for bit on the same mask.
+ *   Costs one byte instead of one bit of mask traffic per element.
+ */
+TEMPO_API tempo_status tempo_attn_softmax_dropout_bwd_bytemask(const void* dout, const void* probs,
+                                            const uint8_t* keep_bytes, void* dscores,
+                                            void* out_recomputed,
+                                            int64_t B, int64_t A, int64_t Sq, int64_t Sk, float p,
+                                            tempo_dtype dt, void* hip_stream);
+
+/*
  * Mask layout conversion: packed bits <-> one byte per element        [Sec. 3.3 (8-bit masks)]
  *   The paper's implementation keeps the dropout mask as one byte per element; this library
  *   keeps one bit (bit e & 31 of word e >> 5).  These two calls convert between the layouts,

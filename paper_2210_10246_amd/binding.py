@@ -44,6 +44,8 @@ _SIGNATURES = {
                                               _i64, _f32, _u64, _u64, _int, _vp]),
     "tempo_attn_softmax_dropout_bwd": (_int, [_vp, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _i64,
                                               _f32, _int, _vp]),
+    "tempo_attn_softmax_dropout_bwd_bytemask": (_int, [_vp, _vp, _vp, _vp, _vp, _i64, _i64, _i64,
+                                                       _i64, _f32, _int, _vp]),
     "tempo_attn_softmax_dropout_bwd_regen": (_int, [_vp, _vp, _vp, _vp, _i64, _i64, _i64, _i64,
                                                     _f32, _u64, _u64, _int, _vp]),
     "tempo_mask_bits_to_bytes": (_int, [_vp, _vp, _i64, _vp]),
@@ -259,6 +261,23 @@ def tempo_attn_softmax_dropout_bwd(dout, probs, keep_bits, dscores, out_recomput
         _ptr(dout), _ptr(probs), _ptr(keep_bits), _ptr(dscores), _ptr(out_recomputed),
         B, A, Sq, Sk, p, dt, _stream(stream)),
         "tempo_attn_softmax_dropout_bwd")
+
+
+def tempo_attn_softmax_dropout_bwd_bytemask(dout, probs, keep_bytes, dscores, out_recomputed, p,
+                                            stream=None):
+    """Backward reading a mask of one byte per element (uint8 or bool tensor; non-zero = kept)."""
+    B, A, Sq, Sk = probs.shape
+    n = probs.numel()
+    dt = _act_dtype("probs", probs)
+    _want("dout", dout, probs.dtype, n)
+    _want("dscores", dscores, probs.dtype, n)
+    _want("out_recomputed", out_recomputed, probs.dtype, n)
+    if keep_bytes.dtype not in (torch.uint8, torch.bool) or keep_bytes.numel() != n:
+        raise ValueError(f"keep_bytes must be uint8 or bool with {n} elements, got "
+                         f"{keep_bytes.dtype} with {keep_bytes.numel()}")
+    _check(load().tempo_attn_softmax_dropout_bwd_bytemask(
+        _ptr(dout), _ptr(probs), _ptr(keep_bytes), _ptr(dscores), _ptr(out_recomputed),
+        B, A, Sq, Sk, p, dt, _stream(stream)), "tempo_attn_softmax_dropout_bwd_bytemask")
 
 
 def tempo_attn_softmax_dropout_bwd_regen(dout, probs, dscores, out_recomputed, p, seed, offset,

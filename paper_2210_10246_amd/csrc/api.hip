@@ -243,6 +243,23 @@ tempo_status tempo_attn_softmax_dropout_bwd(const void* dout, const void* probs,
                          static_cast<hipStream_t>(hip_stream));
 }
 
+tempo_status tempo_attn_softmax_dropout_bwd_bytemask(const void* dout, const void* probs,
+                                                     const uint8_t* keep_bytes, void* dscores,
+                                                     void* out_recomputed, int64_t B, int64_t A,
+                                                     int64_t Sq, int64_t Sk, float p,
+                                                     tempo_dtype dt, void* hip_stream) {
+  if (B < 0 || A < 0 || Sq < 0 || Sk < 0 || !dtype_ok(dt) || !prob_ok(p) || Sq > INT32_MAX ||
+      Sk > INT32_MAX || !count_ok(B, A, Sq, Sk) || B * A > INT32_MAX)
+    return TEMPO_ERR_INVALID_ARG;
+  if (B == 0 || A == 0 || Sq == 0 || Sk == 0) return TEMPO_OK;
+  if (!dout || !probs || !keep_bytes || !dscores) return TEMPO_ERR_INVALID_ARG;
+  if (!aligned16(dout) || !aligned16(probs) || !aligned16(keep_bytes) || !aligned16(dscores) ||
+      !aligned16(out_recomputed))
+    return TEMPO_ERR_UNSUPPORTED;
+  return launch_attn_bwd_bytemask(dout, probs, keep_bytes, dscores, out_recomputed, B, A, Sq, Sk,
+                                  p, dt, static_cast<hipStream_t>(hip_stream));
+}
+
 tempo_status tempo_attn_softmax_dropout_bwd_regen(const void* dout, const void* probs,
                                                   void* dscores, void* out_recomputed, int64_t B,
                                                   int64_t A, int64_t Sq, int64_t Sk, float p,

@@ -302,10 +302,35 @@ __global__ __launch_bounds__(kThreads) void attn_fwd_kernel(
   }
 }
 
-// MASK says where backward takes the keep bits from: the stored mask read as whole words
-// (Sk % 32 == 0) or as bytes, or the generator (no mask is read; Sec. 3.3 weighs storing the
-// mask against drawing it again).
-enum MaskSource { kMaskWords, kMaskBytes, kMaskRegen };
+// Keep bits of one piece from a mask kept the way the paper's implementation keeps it, one
+// byte per element (Sec. 3.3; any non-zero byte means kept): one 4-byte (float32 piece) or
+// 8-byte (bfloat16 piece) load per lane.  Per 32-bit word: fold each byte's bits onto its bit 0,
+// then gather the four bit-0s by one multiply (the partial products land on distinct bits).
+__device__ __forceinline__ uint32_t nonzero_bytes_to_bits(uint32_t w) {
+  w |= w >> 4;
+  w |= w >> 2;
+  w |= w >> 1;
+  w &= 0x01010101u;
+  return (w * 0x01020408u) >> 24;  // byte i -> bit i
+}
+template <typename T>
+__device__ __forceinline__ uint32_t load_keep_bools(const uint8_t* keep_bytes, int64_t element) {
+  if constexpr (Store<T>::kVec == 4) {
+    return nonzero_bytes_to_bits(
+        __builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(keep_bytes + element)));
+  } else {
+    typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+    const u32x2 w =
+        __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(keep_bytes + element));
+    return nonzero_bytes_to_bits(w.x) | (nonzero_bytes_to_bits(w.y) << 4);
+  }
+}
+
+// MASK says where backward takes the keep bits from: the stored bit mask read as whole words
+// (Sk % 32 == 0) or as bytes, the generator (no mask is read; Sec. 3.3 weighs storing the
+// mask against drawing it again), or a mask of one byte per element (keep_bits then points to
+// bytes).
+enum MaskSource { kMaskWords, kMaskBytes, kMaskRegen, kMaskBools };
 
 template <typename T, int LANES, int CH, int R, MaskSource MASK>
 __global__ __launch_bounds__(kThreads) void attn_bwd_kernel(
@@ -334,7 +359,10 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_kernel(
           const int64_t row0 = row_offset(static_cast<uint32_t>(row), Sk);
           rdo[r][c].load(dout + row0 + pc * V);
           rp[r][c].load(probs + row0 + pc * V);
-          if constexpr (MASK != kMaskRegen)
+          if constexpr (MASK == kMaskBools)
+            bits[r][c] = load_keep_bools<T>(reinterpret_cast<const uint8_t*>(keep_bits),
+                                            row0 + pc * V);
+          else if constexpr (MASK != kMaskRegen)
             bits[r][c] = load_keep_bits<T, MASK == kMaskWords>(keep_bits, row0 / V + pc);
         }
       }
@@ -448,12 +476,13 @@ __global__ __launch_bounds__(kThreads) void keep_words_kernel(uint32_t* __restri
   }
 }
 
-template <typename T, bool REGEN>
+template <typename T, MaskSource MASK>
 __global__ __launch_bounds__(kThreads) void attn_bwd_generic_kernel(
     const T* dout, const T* __restrict__ probs, const uint32_t* __restrict__ keep_bits,
     T* dscores, T* __restrict__ out_re, int64_t rows, int Sk, float scale, RngArgs rng) {
   auto kept = [&](int64_t e) -> bool {
-    if constexpr (REGEN) return keep_bit_of(e, rng);
+    if constexpr (MASK == kMaskRegen) return keep_bit_of(e, rng);
+    else if constexpr (MASK == kMaskBools) return reinterpret_cast<const uint8_t*>(keep_bits)[e] != 0;
     else return (keep_bits[e >> 5] >> (e & 31)) & 1u;
   };
   const int lane = threadIdx.x & (kWave - 1);
@@ -600,6 +629,7 @@ static void attn_bwd_go(MaskSource mask, int grid, hipStream_t st, const void* d
   using std::integral_constant;
   if (mask == kMaskWords) return go(integral_constant<MaskSource, kMaskWords>{});
   if (mask == kMaskBytes) return go(integral_constant<MaskSource, kMaskBytes>{});
+  if (mask == kMaskBools) return go(integral_constant<MaskSource, kMaskBools>{});
   go(integral_constant<MaskSource, kMaskRegen>{});
 }
 
@@ -671,10 +701,11 @@ tempo_status launch_attn_fwd(const void* scores, const int32_t* key_len, int cau
 }
 
 // keep_bits == nullptr: no stored mask, the bits are drawn again from (seed, offset).
+// bools: keep_bits points to one byte per element instead of packed bits.
 static tempo_status attn_bwd_any(const void* dout, const void* probs, const uint32_t* keep_bits,
-                                 void* dscores, void* out_re, int64_t B, int64_t A, int64_t Sq,
-                                 int64_t Sk, float p, const RngArgs& rng, tempo_dtype dt,
-                                 hipStream_t st) {
+                                 bool bools, void* dscores, void* out_re, int64_t B, int64_t A,
+                                 int64_t Sq, int64_t Sk, float p, const RngArgs& rng,
+                                 tempo_dtype dt, hipStream_t st) {
   const int64_t rows = B * A * Sq;
   const float scale = 1.0f / (1.0f - p);
   const bool regen = keep_bits == nullptr;
@@ -684,7 +715,8 @@ static tempo_status attn_bwd_any(const void* dout, const void* probs, const uint
                             tune_get(kTuneAttnBwdMaxPieces));
   if (Sk % 8 == 0 && sh.ch != 0 && rows <= UINT32_MAX) {  // rows counted in 32 bits
     const int grid = row_grid(rows, sh.lanes, bpc);
-    const MaskSource mask = regen ? kMaskRegen : (Sk % 32 == 0 ? kMaskWords : kMaskBytes);
+    const MaskSource mask =
+        regen ? kMaskRegen : (bools ? kMaskBools : (Sk % 32 == 0 ? kMaskWords : kMaskBytes));
 #define TEMPO_LAUNCH(L, C)                                                                   \
   do {                                                                                       \
     if (dt == TEMPO_F32) attn_bwd_go<float, L, C>(mask, grid, st, dout, probs, keep_bits, dscores, out_re, rows, Sk, scale, rng);   \
@@ -699,35 +731,44 @@ static tempo_status attn_bwd_any(const void* dout, const void* probs, const uint
     return launch_status();
   }
   const int grid = row_grid(rows, kWave, bpc);
-  auto go = [&](auto tag, auto re) {
+  auto go = [&](auto tag, auto m) {
     using T = decltype(tag);
-    hipLaunchKernelGGL((attn_bwd_generic_kernel<T, decltype(re)::value>), dim3(grid),
+    hipLaunchKernelGGL((attn_bwd_generic_kernel<T, decltype(m)::value>), dim3(grid),
                        dim3(kThreads), 0, st, static_cast<const T*>(dout),
                        static_cast<const T*>(probs), keep_bits, static_cast<T*>(dscores),
                        static_cast<T*>(out_re), rows, static_cast<int>(Sk), scale, rng);
   };
-  if (dt == TEMPO_F32) {
-    if (regen) go(float{}, std::true_type{});
-    else go(float{}, std::false_type{});
-  } else {
-    if (regen) go(bf16_t{}, std::true_type{});
-    else go(bf16_t{}, std::false_type{});
-  }
+  using std::integral_constant;
+  auto with_mask = [&](auto tag) {
+    if (regen) go(tag, integral_constant<MaskSource, kMaskRegen>{});
+    else if (bools) go(tag, integral_constant<MaskSource, kMaskBools>{});
+    else go(tag, integral_constant<MaskSource, kMaskWords>{});
+  };
+  if (dt == TEMPO_F32) with_mask(float{});
+  else with_mask(bf16_t{});
   return launch_status();
 }
 
 tempo_status launch_attn_bwd(const void* dout, const void* probs, const uint32_t* keep_bits,
                              void* dscores, void* out_re, int64_t B, int64_t A, int64_t Sq,
                              int64_t Sk, float p, tempo_dtype dt, hipStream_t st) {
-  return attn_bwd_any(dout, probs, keep_bits, dscores, out_re, B, A, Sq, Sk, p,
+  return attn_bwd_any(dout, probs, keep_bits, false, dscores, out_re, B, A, Sq, Sk, p,
                       make_rng(0.0f, 0, 0), dt, st);
+}
+
+tempo_status launch_attn_bwd_bytemask(const void* dout, const void* probs,
+                                      const uint8_t* keep_bytes, void* dscores, void* out_re,
+                                      int64_t B, int64_t A, int64_t Sq, int64_t Sk, float p,
+                                      tempo_dtype dt, hipStream_t st) {
+  return attn_bwd_any(dout, probs, reinterpret_cast<const uint32_t*>(keep_bytes), true, dscores,
+                      out_re, B, A, Sq, Sk, p, make_rng(0.0f, 0, 0), dt, st);
 }
 
 tempo_status launch_attn_bwd_regen(const void* dout, const void* probs, void* dscores,
                                    void* out_re, int64_t B, int64_t A, int64_t Sq, int64_t Sk,
                                    float p, uint64_t seed, uint64_t offset, tempo_dtype dt,
                                    hipStream_t st) {
-  return attn_bwd_any(dout, probs, nullptr, dscores, out_re, B, A, Sq, Sk, p,
+  return attn_bwd_any(dout, probs, nullptr, false, dscores, out_re, B, A, Sq, Sk, p,
                       make_rng(p, seed, offset), dt, st);
 }
 

@@ -59,6 +59,10 @@ tempo_status launch_attn_fwd(const void* scores, const int32_t* key_len, int cau
 tempo_status launch_attn_bwd(const void* dout, const void* probs, const uint32_t* keep_bits,
                              void* dscores, void* out_re, int64_t B, int64_t A, int64_t Sq,
                              int64_t Sk, float p, tempo_dtype dt, hipStream_t st);
+tempo_status launch_attn_bwd_bytemask(const void* dout, const void* probs,
+                                      const uint8_t* keep_bytes, void* dscores, void* out_re,
+                                      int64_t B, int64_t A, int64_t Sq, int64_t Sk, float p,
+                                      tempo_dtype dt, hipStream_t st);
 tempo_status launch_attn_bwd_regen(const void* dout, const void* probs, void* dscores,
                                    void* out_re, int64_t B, int64_t A, int64_t Sq, int64_t Sk,
                                    float p, uint64_t seed, uint64_t offset, tempo_dtype dt,

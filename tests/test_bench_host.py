@@ -47,6 +47,7 @@ def test_algorithmic_bytes_per_element(index):
     assert a["attn_fwd"] == pytest.approx(n_a * ((2 + frac) * e + 0.125), rel=1e-12)
     assert a["attn_bwd"] == n_a * (4 * e + 0.125)
     assert a["attn_bwd_regen"] == n_a * 4 * e
+    assert a["attn_bwd_bytemask"] == n_a * (4 * e + 1)
     assert a["layernorm_fwd"] == cfg.tokens * (cfg.hidden * 2 * e + 4) + 8 * cfg.hidden
     assert a["layernorm_bwd"] == cfg.tokens * (cfg.hidden * 3 * e + 4) + 16 * cfg.hidden
 

@@ -90,6 +90,28 @@ def test_gelu_fwd(B, n, dt, kind):
 
 @pytest.mark.parametrize("kind", ACT_KINDS)
 @pytest.mark.parametrize("dt", ["f32", "bf16"])
+def test_gelu_fwd_next_to_its_zero(B, dt, kind):
+    """x = 0 is a plain zero of the activation, not a cancellation point: for |x| from 1e-12 to
+    1e-3 the error is held relative to the value itself (no RMS floor), the sign must be that
+    of x, and +-0 map to +-0."""
+    mag = np.logspace(-12, -3, 1000)
+    x = O.round_to_dtype(np.concatenate([mag, -mag, [0.0, -0.0]]), dt)
+    y_ref, m_ref = O.gelu_fwd(x, kind, dt)
+    xd = dev(x, dt)
+    yd = torch.full_like(xd, 7.0)
+    md = torch.empty(B.mask_words(x.size), dtype=torch.int32, device="cuda")
+    act_fwd(B, kind, xd, yd, md)
+    torch.cuda.synchronize()
+    got = host(yd)
+    assert np.array_equal(words(md), O.pack_bits(m_ref))
+    assert np.array_equal(np.signbit(got), np.signbit(x))
+    assert got[-2] == 0.0 and got[-1] == 0.0
+    nz = x != 0
+    assert np.max(np.abs(got[nz] - y_ref[nz]) / np.abs(y_ref[nz])) <= TOL[dt]
+
+
+@pytest.mark.parametrize("kind", ACT_KINDS)
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
 @pytest.mark.parametrize("n", [1, 9, 33, 4099, 300_000])
 def test_gelu_bwd(B, n, dt, kind):
     rng = np.random.default_rng(100 + n)
@@ -440,6 +462,38 @@ def test_attn_bwd_without_stored_mask(B, case, dt):
     B.tempo_attn_softmax_dropout_bwd(dod, Pd, md, ds2, or2, float(p))
     torch.cuda.synchronize()
     assert torch.equal(dsd, ds2) and torch.equal(ord_, or2)
+
+
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+@pytest.mark.parametrize("case", ATTN_CASES, ids=lambda c: "x".join(map(str, c)))
+def test_attn_bwd_with_a_mask_of_one_byte_per_element(B, case, dt):
+    """Backward fed the paper's mask layout (8-bit booleans, Sec. 3.3) against the oracle, and bit
+    for bit against the backward that reads packed bits; any non-zero byte means kept."""
+    rng = np.random.default_rng(hash(case[:4]) % (1 << 31) + 3)
+    s, key_len, causal, p = _attn_inputs(case, dt, rng)
+    seed, offset = 7, 9
+    P, _, K = O.attn_softmax_dropout_fwd(s, key_len, causal, p, seed, offset, dt)
+    dout = stored(rng, s.shape, dt)
+    dS_ref, out_re_ref = O.attn_softmax_dropout_bwd(dout, P, K, p, dt)
+    dod, Pd = dev(dout, dt), dev(P, dt)
+    md = torch.from_numpy(O.pack_bits(K).view(np.int32)).cuda()
+    ds0, or0 = torch.empty_like(dod), torch.empty_like(dod)
+    B.tempo_attn_softmax_dropout_bwd(dod, Pd, md, ds0, or0, float(p))
+    n = s.size
+    pad = (-n) % 16
+    for marks in (np.ones(n, dtype=np.uint8), rng.integers(1, 256, n).astype(np.uint8)):
+        kb = torch.zeros(n + pad, dtype=torch.uint8, device="cuda")
+        kb[:n] = torch.from_numpy(K.reshape(-1).astype(np.uint8) * marks).cuda()
+        dsd, ord_ = torch.full_like(dod, 3.0), torch.full_like(dod, 3.0)
+        B.tempo_attn_softmax_dropout_bwd_bytemask(dod, Pd, kb[:n], dsd, ord_, float(p))
+        torch.cuda.synchronize()
+        assert rel_err(host(dsd), dS_ref) <= TOL[dt]
+        assert rel_err(host(ord_), out_re_ref) <= TOL[dt]
+        assert torch.equal(dsd, ds0) and torch.equal(ord_, or0)
+    kbool = torch.from_numpy(K.reshape(-1)).cuda()                     # a torch.bool tensor as it is
+    B.tempo_attn_softmax_dropout_bwd_bytemask(dod, Pd, kbool, dod, None, float(p))   # in place, no Out
+    torch.cuda.synchronize()
+    assert torch.equal(dod, ds0)
 
 
 @pytest.mark.parametrize("n", [1, 15, 16, 17, 31, 32, 33, 4096, 100_003, 3_000_000])

@@ -56,6 +56,10 @@ def test_invalid_arguments_are_rejected_before_any_launch():
     assert lib.tempo_attn_softmax_dropout_bwd_regen(16, None, 16, None, 1, 1, 8, 8, 0.1, 0, 0, 0, None) == INVALID
     assert lib.tempo_attn_softmax_dropout_bwd_regen(16, 16, 24, None, 1, 1, 8, 8, 0.1, 0, 0, 0, None) == UNSUPPORTED
     assert lib.tempo_mask_bits_to_bytes(16, 16, -1, None) == INVALID
+    assert lib.tempo_attn_softmax_dropout_bwd_bytemask(16, 16, None, 16, None, 1, 1, 8, 8, 0.1, 0, None) == INVALID
+    assert lib.tempo_attn_softmax_dropout_bwd_bytemask(16, 16, 24, 16, None, 1, 1, 8, 8, 0.1, 0, None) == UNSUPPORTED
+    assert lib.tempo_attn_softmax_dropout_bwd_bytemask(16, 16, 16, 16, None, 1, 1, 8, 8, 1.0, 0, None) == INVALID
+    assert lib.tempo_attn_softmax_dropout_bwd_bytemask(None, None, None, None, None, 0, 1, 8, 8, 0.1, 0, None) == 0
     assert lib.tempo_silu_fwd(16, 16, 16, -1, 0, None) == INVALID
     assert lib.tempo_silu_fwd(16, 16, 16, 8, 5, None) == INVALID
     assert lib.tempo_silu_bwd(16, 16, None, 16, 8, 0, None) == INVALID
