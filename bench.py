@@ -157,7 +157,8 @@ def main():
             others[r["config"]["workload"]] = {
                 "dtype": r["dtype"], "value": r["value"], "ms_per_step": r["ms_per_step"],
                 "frac_of_hbm_peak": r["frac_of_hbm_peak"], "worst_kernel": r["worst_kernel"],
-                "kernels": {k: {f: v[f] for f in ("us", "GB/s", "frac_of_peak", "bytes")}
+                "kernels": {k: {f: v[f] for f in ("us", "GB/s", "frac_of_peak", "bytes",
+                                                  "frac_of_pattern_copy") if f in v}
                             for k, v in r["kernels"].items()}}
         line["other_workloads"] = others
     print(json.dumps(line))
@@ -303,34 +304,38 @@ def measure(cfg, args, headline):
 
     # ---- per-kernel launch durations: events on the stream the kernels are launched on,
     # around a replayed graph of kernel_iters back-to-back launches over rotating buffers
+    def time_launches(fn, bufs):
+        """Average duration of one launch of fn: events on the launch stream around
+        kernel_bursts replays of a graph of kernel_iters back-to-back launches over the
+        rotating buffer sets, after the clocks have settled."""
+        for _ in range(max(3, bufs.n)):
+            fn(bufs.next())
+        torch.cuda.synchronize()
+
+        def burst():
+            for _ in range(args.kernel_iters):
+                fn(bufs.next())
+        body = capture(burst).replay if use_graph else burst
+        t_warm = time.perf_counter()
+        while True:
+            body()
+            torch.cuda.synchronize()
+            if time.perf_counter() - t_warm > args.kernel_warm_ms * 1e-3:
+                break
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        ev0.record()
+        for _ in range(args.kernel_bursts):
+            body()
+        ev1.record()
+        ev1.synchronize()
+        return ev0.elapsed_time(ev1) * 1e3 / (args.kernel_iters * args.kernel_bursts)
+
     per_kernel = {}
     if not args.no_kernel_timing:
         for name, (fn, bufs) in {**kernels, **variants}.items():
             if args.only is not None and name != args.only:
                 continue
-            for _ in range(max(3, bufs.n)):
-                fn(bufs.next())
-            torch.cuda.synchronize()
-
-            def burst(fn=fn, bufs=bufs):
-                for _ in range(args.kernel_iters):
-                    fn(bufs.next())
-            body = capture(burst).replay if use_graph else burst
-            # steady state first (clocks ramp over some milliseconds of load), then the average
-            # launch duration over kernel_bursts bursts of kernel_iters launches
-            t_warm = time.perf_counter()
-            while True:
-                body()
-                torch.cuda.synchronize()
-                if time.perf_counter() - t_warm > args.kernel_warm_ms * 1e-3:
-                    break
-            ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            ev0.record()
-            for _ in range(args.kernel_bursts):
-                body()
-            ev1.record()
-            ev1.synchronize()
-            us = ev0.elapsed_time(ev1) * 1e3 / (args.kernel_iters * args.kernel_bursts)
+            us = time_launches(fn, bufs)
             gbs = algo[name] / us * 1e-3
             per_kernel[name] = {"us": round(us, 2), "GB/s": round(gbs, 1),
                                 "frac_of_peak": round(gbs / HBM_PEAK_GBS, 4),
@@ -338,6 +343,31 @@ def measure(cfg, args, headline):
             if name + "_dense" in algo:   # every input element counted as read
                 per_kernel[name]["dense_bytes"] = int(algo[name + "_dense"])
                 per_kernel[name]["dense_GB/s"] = round(algo[name + "_dense"] / us * 1e-3, 1)
+
+    # ---- the plain streaming kernel with each kernel's own mix of read and write tensors, on
+    # that kernel's own buffers (run after every kernel has been timed: it overwrites outputs).
+    # What the memory system delivers depends on the mix, so this is the ceiling to hold a
+    # kernel against; the mask's 1/8 byte per element is left out of the pattern.
+    pattern = {
+        "gelu_fwd": (lambda s: ([s["x"]], [s["y"]]), gelu_b),
+        "gelu_bwd": (lambda s: ([s["dy"], s["y"]], [s["dx"]]), gelu_b),
+        "layernorm_fwd": (lambda s: ([s["x"]], [s["y"]]), ln_b),
+        "layernorm_bwd": (lambda s: ([s["dy"], s["y"]], [s["dx"]]), ln_b),
+        "attn_fwd": (lambda s: ([s["s"]], [s["P"], s["out"]]), attn_b),
+        "attn_bwd": (lambda s: ([s["do"], s["P"]], [s["dS"], s["out_re"]]), attn_b),
+    }
+    if not args.no_kernel_timing:
+        for name, (pick, bufs) in pattern.items():
+            if name not in per_kernel:
+                continue
+            r0, w0 = pick(bufs.sets[0])
+            us = time_launches(lambda s, pick=pick: B.tempo_copy_streams(*pick(s)), bufs)
+            nb = (len(r0) + len(w0)) * r0[0].numel() * r0[0].element_size()
+            gbs = nb / us * 1e-3
+            k = per_kernel[name]
+            k["pattern_copy"] = {"reads": len(r0), "writes": len(w0), "bytes": nb,
+                                 "us": round(us, 2), "GB/s": round(gbs, 1)}
+            k["frac_of_pattern_copy"] = round(k["GB/s"] / gbs, 4)
 
     # ---- what a plain 16-byte copy reaches on this GPU (read + write bytes per second): at
     # 256 MiB, and moving as many bytes as the slowest kernel of the step moves per launch
@@ -393,14 +423,18 @@ def measure(cfg, args, headline):
                     "unit": "GB/s", "frac": k["frac_of_peak"], "traffic": traffic,
                     # not measured by this process: counters need a rocprofv3 run of their own
                     "traffic_source": traffic_source,
-                    "us_per_launch": k["us"], "algorithmic_bytes": k["bytes"]}
+                    "us_per_launch": k["us"], "algorithmic_bytes": k["bytes"],
+                    # the plain streaming kernel with this kernel's mix of read and write tensors
+                    "pattern_copy": k.get("pattern_copy"),
+                    "frac_of_pattern_copy": k.get("frac_of_pattern_copy")}
     # the kernel of the step furthest below the roofline
     worst = None
     in_step = {k: v for k, v in per_kernel.items() if k in kernels}
     if in_step:
         w = min(in_step, key=lambda k: in_step[k]["frac_of_peak"])
         worst = {"kernel": w, "frac": in_step[w]["frac_of_peak"], "GB/s": in_step[w]["GB/s"],
-                 "us_per_launch": in_step[w]["us"]}
+                 "us_per_launch": in_step[w]["us"],
+                 "frac_of_pattern_copy": in_step[w].get("frac_of_pattern_copy")}
 
     cpu = None
     if headline and not args.no_cpu_baseline and args.only is None:

@@ -46,6 +46,19 @@ TEMPO_API int tempo_get_launch_param(int key);
 TEMPO_API tempo_status tempo_copy(const void* src, void* dst, int64_t nbytes, int blocks_per_cu,
                                   void* hip_stream);
 
+/*
+ * The same yardstick for a given mix of streams: reads n_reads (1..3) tensors of nbytes each,
+ * combines them and writes n_writes (1..2) tensors of nbytes each, one 16-byte access per lane
+ * and tensor.  The bandwidth a streaming kernel can reach on this GPU depends on how many
+ * tensors it reads and writes at once; this is the plain kernel to hold a layer kernel against
+ * (GELU forward and LayerNorm forward: 1 read 1 write; their backwards: 2 and 1; attention
+ * forward: 1 and 2; attention backward: 2 and 2).  reads / writes are HOST arrays of device
+ * pointers; no tensor may overlap another.  nbytes a multiple of 16.
+ */
+TEMPO_API tempo_status tempo_copy_streams(const void* const* reads, int n_reads,
+                                          void* const* writes, int n_writes, int64_t nbytes,
+                                          void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

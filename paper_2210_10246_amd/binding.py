@@ -30,6 +30,7 @@ _SIGNATURES = {
     "tempo_set_launch_param": (_int, [_int, _int]),
     "tempo_get_launch_param": (_int, [_int]),
     "tempo_copy": (_int, [_vp, _vp, _i64, _int, _vp]),
+    "tempo_copy_streams": (_int, [_vp, _int, _vp, _int, _i64, _vp]),
     "tempo_gelu_fwd": (_int, [_vp, _vp, _vp, _i64, _int, _int, _vp]),
     "tempo_gelu_bwd": (_int, [_vp, _vp, _vp, _vp, _i64, _int, _int, _vp]),
     "tempo_silu_fwd": (_int, [_vp, _vp, _vp, _i64, _int, _vp]),
@@ -137,6 +138,18 @@ def tempo_copy(src, dst, blocks_per_cu=16, stream=None):
     assert nbytes == dst.numel() * dst.element_size()
     _check(load().tempo_copy(_ptr(src), _ptr(dst), nbytes, blocks_per_cu, _stream(stream)),
            "tempo_copy")
+
+
+def tempo_copy_streams(reads, writes, stream=None):
+    """Plain streaming kernel over len(reads) input and len(writes) output tensors of one size."""
+    nbytes = reads[0].numel() * reads[0].element_size()
+    for t in list(reads) + list(writes):
+        if t.numel() * t.element_size() != nbytes:
+            raise ValueError("all tensors must have the same size in bytes")
+    r = (ctypes.c_void_p * len(reads))(*[_ptr(t) for t in reads])
+    w = (ctypes.c_void_p * len(writes))(*[_ptr(t) for t in writes])
+    _check(load().tempo_copy_streams(r, len(reads), w, len(writes), nbytes, _stream(stream)),
+           "tempo_copy_streams")
 
 
 def tempo_gelu_fwd(x, y, mask, kind="erf", stream=None):

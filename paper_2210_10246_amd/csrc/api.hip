@@ -67,6 +67,24 @@ __global__ __launch_bounds__(256) void copy_kernel(const u32x4* __restrict__ src
     __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
 }
 
+// The same with several streams: reads NR tensors, combines them (XOR, so that no load can be
+// dropped) and writes NW tensors, one 16-byte piece per lane and stream, a full grid of
+// short-lived workgroups.  What the memory system delivers depends on the mix of read and
+// write streams (two reads and two writes reach less than one and one), so each layer kernel
+// is held against the plain kernel of its own mix.
+template <int NR, int NW>
+__global__ __launch_bounds__(256) void copy_streams_kernel(const u32x4* r0, const u32x4* r1,
+                                                           const u32x4* r2, u32x4* w0, u32x4* w1,
+                                                           int64_t n16) {
+  const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+  if (i >= n16) return;
+  u32x4 v = __builtin_nontemporal_load(r0 + i);
+  if constexpr (NR >= 2) v ^= __builtin_nontemporal_load(r1 + i);
+  if constexpr (NR >= 3) v ^= __builtin_nontemporal_load(r2 + i);
+  __builtin_nontemporal_store(v, w0 + i);
+  if constexpr (NW >= 2) __builtin_nontemporal_store(v + 1u, w1 + i);
+}
+
 }  // namespace tempo
 
 using namespace tempo;
@@ -109,6 +127,43 @@ tempo_status tempo_copy(const void* src, void* dst, int64_t nbytes, int blocks_p
   hipLaunchKernelGGL(copy_kernel, dim3(static_cast<int>(want < cap ? want : cap)), dim3(256), 0,
                      static_cast<hipStream_t>(hip_stream), static_cast<const u32x4*>(src),
                      static_cast<u32x4*>(dst), n16);
+  return launch_status();
+}
+
+tempo_status tempo_copy_streams(const void* const* reads, int n_reads, void* const* writes,
+                                int n_writes, int64_t nbytes, void* hip_stream) {
+  if (nbytes < 0 || (nbytes & 15) != 0 || n_reads < 1 || n_reads > 3 || n_writes < 1 ||
+      n_writes > 2 || nbytes / 16 > (int64_t{1} << 31) * 256)
+    return TEMPO_ERR_INVALID_ARG;
+  if (nbytes == 0) return TEMPO_OK;
+  if (!reads || !writes) return TEMPO_ERR_INVALID_ARG;
+  const u32x4* r[3] = {nullptr, nullptr, nullptr};
+  u32x4* w[2] = {nullptr, nullptr};
+  for (int i = 0; i < n_reads; ++i) {
+    if (!reads[i]) return TEMPO_ERR_INVALID_ARG;
+    if (!aligned16(reads[i])) return TEMPO_ERR_UNSUPPORTED;
+    r[i] = static_cast<const u32x4*>(reads[i]);
+  }
+  for (int i = 0; i < n_writes; ++i) {
+    if (!writes[i]) return TEMPO_ERR_INVALID_ARG;
+    if (!aligned16(writes[i])) return TEMPO_ERR_UNSUPPORTED;
+    w[i] = static_cast<u32x4*>(writes[i]);
+  }
+  const int64_t n16 = nbytes / 16;
+  const dim3 grid(static_cast<unsigned>((n16 + 255) / 256));
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+#define TEMPO_LAUNCH(NR, NW)                                                                 \
+  hipLaunchKernelGGL((copy_streams_kernel<NR, NW>), grid, dim3(256), 0, st, r[0], r[1], r[2], w[0], \
+                     w[1], n16)
+  switch (n_reads * 10 + n_writes) {
+    case 11: TEMPO_LAUNCH(1, 1); break;
+    case 12: TEMPO_LAUNCH(1, 2); break;
+    case 21: TEMPO_LAUNCH(2, 1); break;
+    case 22: TEMPO_LAUNCH(2, 2); break;
+    case 31: TEMPO_LAUNCH(3, 1); break;
+    default: TEMPO_LAUNCH(3, 2); break;
+  }
+#undef TEMPO_LAUNCH
   return launch_status();
 }
 

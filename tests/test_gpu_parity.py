@@ -752,3 +752,22 @@ def test_layernorm_constant_rows(B, M, dt, eps):
     assert rel_err(host(dbd), db_ref) <= TOL["f32"]
     # dgamma = sum dy * xhat with xhat = 0 up to the rounding of y = beta to the storage dtype
     assert np.abs(host(dgd) - dg_ref).max() <= 1e-5 * max(1.0, np.abs(dy).max()) * N
+
+
+@pytest.mark.parametrize("nr,nw", [(1, 1), (2, 1), (1, 2), (2, 2), (3, 2)])
+def test_copy_streams_yardstick(B, nr, nw):
+    """The plain multi-stream kernel bench.py holds the layer kernels against: every write
+    tensor is the XOR of the read tensors (the second one plus one per 32-bit word)."""
+    n = 256 * 1000 + 16            # int32 words; a ragged last workgroup
+    g = torch.Generator(device="cuda").manual_seed(nr * 10 + nw)
+    reads = [torch.randint(-2**31, 2**31 - 1, (n,), dtype=torch.int32, device="cuda", generator=g)
+             for _ in range(nr)]
+    writes = [torch.zeros(n, dtype=torch.int32, device="cuda") for _ in range(nw)]
+    B.tempo_copy_streams(reads, writes)
+    torch.cuda.synchronize()
+    want = reads[0].clone()
+    for r in reads[1:]:
+        want ^= r
+    assert torch.equal(writes[0], want)
+    if nw == 2:
+        assert torch.equal(writes[1], want + 1)       # wraps like the kernel's unsigned add
