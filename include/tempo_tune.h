@@ -26,6 +26,7 @@ extern "C" {
  *   key 6, 7: rows a lane group of attn fwd / layernorm_fwd fetches at once (1 or 2);
  *   key 8, 9, 10, 11: attn fwd / attn bwd / layernorm_fwd / layernorm_bwd: 16-byte pieces per
  *   lane above which a row is spread over 2 or 4 waves instead of one (16 or more: never);
+ *   key 14: lanes per workgroup of attn fwd / bwd (64, 128 or 256; never fewer than a row's);
  *   key 3: rows each lane group of layernorm_bwd walks; key 12: workgroups per compute unit
  *   beyond which its workgroups loop over the rows; keys 3, 11 and 12 set its grid and the
  *   size of its workspace, so query tempo_layernorm_bwd_workspace_bytes after changing them.

@@ -22,6 +22,7 @@ static std::atomic<int> g_tune[kTuneCount] = {
     {3},      // layernorm bwd: the same (3: rows of 4 pieces per lane would keep their parameters in LDS)
     {1},      // layernorm bwd: workgroups per CU beyond which they loop with prefetch
     {24},     // bf16 gelu/silu fwd: Mi elements from which workgroups have 512 lanes
+    {128},    // attention fwd / bwd: lanes per workgroup
 };
 
 int tune_get(TuneKey k) { return g_tune[k].load(std::memory_order_relaxed); }
@@ -57,13 +58,18 @@ static bool count_ok(int64_t a, int64_t b = 1, int64_t c = 1, int64_t d = 1) {
   return n <= kMaxElements;
 }
 
+// Workgroups of the yardstick kernels are single waves: measured on 1 GiB tensors, one-wave
+// workgroups move 3.5 % (one read, one write) to 6 % (two and two) more than four-wave ones.
+constexpr int kCopyThreads = kWave;
+
 // Plain streaming copy, 16 bytes per lane and access: the reference point for what the memory
 // system delivers to a kernel that does nothing else, and the known-size kernel against which
 // hardware byte counters are calibrated.
-__global__ __launch_bounds__(256) void copy_kernel(const u32x4* __restrict__ src,
-                                                   u32x4* __restrict__ dst, int64_t n16) {
-  const int64_t stride = static_cast<int64_t>(gridDim.x) * 256;
-  for (int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x; i < n16; i += stride)
+__global__ __launch_bounds__(kCopyThreads) void copy_kernel(const u32x4* __restrict__ src,
+                                                            u32x4* __restrict__ dst, int64_t n16) {
+  const int64_t stride = static_cast<int64_t>(gridDim.x) * kCopyThreads;
+  for (int64_t i = static_cast<int64_t>(blockIdx.x) * kCopyThreads + threadIdx.x; i < n16;
+       i += stride)
     __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
 }
 
@@ -73,10 +79,10 @@ __global__ __launch_bounds__(256) void copy_kernel(const u32x4* __restrict__ src
 // write streams (two reads and two writes reach less than one and one), so each layer kernel
 // is held against the plain kernel of its own mix.
 template <int NR, int NW>
-__global__ __launch_bounds__(256) void copy_streams_kernel(const u32x4* r0, const u32x4* r1,
+__global__ __launch_bounds__(kCopyThreads) void copy_streams_kernel(const u32x4* r0, const u32x4* r1,
                                                            const u32x4* r2, u32x4* w0, u32x4* w1,
                                                            int64_t n16) {
-  const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+  const int64_t i = static_cast<int64_t>(blockIdx.x) * kCopyThreads + threadIdx.x;
   if (i >= n16) return;
   u32x4 v = __builtin_nontemporal_load(r0 + i);
   if constexpr (NR >= 2) v ^= __builtin_nontemporal_load(r1 + i);
@@ -122,9 +128,10 @@ tempo_status tempo_copy(const void* src, void* dst, int64_t nbytes, int blocks_p
   if (!src || !dst) return TEMPO_ERR_INVALID_ARG;
   if (!aligned16(src) || !aligned16(dst)) return TEMPO_ERR_UNSUPPORTED;
   const int64_t n16 = nbytes / 16;
-  const int64_t want = (n16 + 255) / 256;
+  const int64_t want = (n16 + kCopyThreads - 1) / kCopyThreads;
   const int64_t cap = static_cast<int64_t>(compute_units()) * blocks_per_cu;
-  hipLaunchKernelGGL(copy_kernel, dim3(static_cast<int>(want < cap ? want : cap)), dim3(256), 0,
+  hipLaunchKernelGGL(copy_kernel, dim3(static_cast<unsigned>(want < cap ? want : cap)),
+                     dim3(kCopyThreads), 0,
                      static_cast<hipStream_t>(hip_stream), static_cast<const u32x4*>(src),
                      static_cast<u32x4*>(dst), n16);
   return launch_status();
@@ -133,7 +140,7 @@ tempo_status tempo_copy(const void* src, void* dst, int64_t nbytes, int blocks_p
 tempo_status tempo_copy_streams(const void* const* reads, int n_reads, void* const* writes,
                                 int n_writes, int64_t nbytes, void* hip_stream) {
   if (nbytes < 0 || (nbytes & 15) != 0 || n_reads < 1 || n_reads > 3 || n_writes < 1 ||
-      n_writes > 2 || nbytes / 16 > (int64_t{1} << 31) * 256)
+      n_writes > 2 || nbytes / 16 > (int64_t{1} << 31) * kCopyThreads)
     return TEMPO_ERR_INVALID_ARG;
   if (nbytes == 0) return TEMPO_OK;
   if (!reads || !writes) return TEMPO_ERR_INVALID_ARG;
@@ -150,11 +157,11 @@ tempo_status tempo_copy_streams(const void* const* reads, int n_reads, void* con
     w[i] = static_cast<u32x4*>(writes[i]);
   }
   const int64_t n16 = nbytes / 16;
-  const dim3 grid(static_cast<unsigned>((n16 + 255) / 256));
+  const dim3 grid(static_cast<unsigned>((n16 + kCopyThreads - 1) / kCopyThreads));
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
 #define TEMPO_LAUNCH(NR, NW)                                                                 \
-  hipLaunchKernelGGL((copy_streams_kernel<NR, NW>), grid, dim3(256), 0, st, r[0], r[1], r[2], w[0], \
-                     w[1], n16)
+  hipLaunchKernelGGL((copy_streams_kernel<NR, NW>), grid, dim3(kCopyThreads), 0, st, r[0], r[1], \
+                     r[2], w[0], w[1], n16)
   switch (n_reads * 10 + n_writes) {
     case 11: TEMPO_LAUNCH(1, 1); break;
     case 12: TEMPO_LAUNCH(1, 2); break;

@@ -192,12 +192,13 @@ __device__ __forceinline__ uint32_t load_keep_bits(const uint32_t* keep_bits, in
 // LANES = 128 or 256 spreads a long row over 2 or 4 waves: the pieces per lane, and with them
 // the registers per lane, stay small enough for many resident waves (a 3072-element bfloat16
 // row on one wave needs over 200 registers per lane, which leaves 2 waves per SIMD).
-template <typename T, int LANES, int CH, int R, bool WORDS>
-__global__ __launch_bounds__(kThreads) void attn_fwd_kernel(
+template <typename T, int LANES, int CH, int R, bool WORDS, int THREADS>
+__global__ __launch_bounds__(THREADS) void attn_fwd_kernel(
     const T* scores, const int32_t* __restrict__ key_len, int causal, T* probs,
     T* __restrict__ out, uint32_t* __restrict__ keep_bits, int slices, int A, int Sq, int Sk,
     float scale, RngArgs rng) {
-  constexpr int kGroups = kThreads / LANES;
+  static_assert(THREADS % LANES == 0 && THREADS % kWave == 0, "whole lane groups, whole waves");
+  constexpr int kGroups = THREADS / LANES;
   constexpr int V = Store<T>::kVec;
   const int g = threadIdx.x / LANES;
   const int t = threadIdx.x % LANES;
@@ -205,7 +206,7 @@ __global__ __launch_bounds__(kThreads) void attn_fwd_kernel(
   const int sets_per_slice = (Sq + kGroups * R - 1) / (kGroups * R);
   const int64_t total_sets = static_cast<int64_t>(slices) * sets_per_slice;
   const int64_t total_pieces = static_cast<int64_t>(slices) * Sq * pieces;
-  __shared__ float red[2][kThreads / kWave];
+  __shared__ float red[2][THREADS / kWave];
   static_assert(LANES <= kWave || R == 1, "rows over several waves: one row per group");
 
   for (int64_t rs = blockIdx.x; rs < total_sets; rs += gridDim.x) {
@@ -332,16 +333,17 @@ __device__ __forceinline__ uint32_t load_keep_bools(const uint8_t* keep_bytes, i
 // bytes).
 enum MaskSource { kMaskWords, kMaskBytes, kMaskRegen, kMaskBools };
 
-template <typename T, int LANES, int CH, int R, MaskSource MASK>
-__global__ __launch_bounds__(kThreads) void attn_bwd_kernel(
+template <typename T, int LANES, int CH, int R, MaskSource MASK, int THREADS>
+__global__ __launch_bounds__(THREADS) void attn_bwd_kernel(
     const T* dout, const T* __restrict__ probs, const uint32_t* __restrict__ keep_bits,
     T* dscores, T* __restrict__ out_re, uint32_t rows, int Sk, float scale, RngArgs rng) {
-  constexpr int kGroups = kThreads / LANES;
+  static_assert(THREADS % LANES == 0 && THREADS % kWave == 0, "whole lane groups, whole waves");
+  constexpr int kGroups = THREADS / LANES;
   constexpr int V = Store<T>::kVec;
   const int g = threadIdx.x / LANES;
   const int t = threadIdx.x % LANES;
   const int pieces = Sk / V;
-  __shared__ float red[2][kThreads / kWave];
+  __shared__ float red[2][THREADS / kWave];
   static_assert(LANES <= kWave || R == 1, "rows over several waves: one row per group");
   int flip = 0;  // one reduction per row set: consecutive sets alternate between the slot arrays
   for (int64_t base = static_cast<int64_t>(blockIdx.x) * (kGroups * R); base < rows;
@@ -552,8 +554,20 @@ int attn_rows(int ch, int lanes, int vec, int tuned) {
   return (vec == 8 && ch == 1 && lanes == kWave && tuned >= 2) ? 2 : 1;
 }
 
-int row_grid(int64_t rows, int lanes, int blocks_per_cu, int rows_per_group = 1) {
-  const int groups = (kThreads / lanes) * rows_per_group;
+// Lanes per workgroup of the register-resident kernels.  Small workgroups come and go
+// independently, which the memory system rewards: against workgroups of four waves, two waves
+// gain 2-8 % (forward at every size, backward on tensors from 2 GB up, never a loss); single
+// waves do no better than two and lose 1-2 % in places.  So: two waves, and never fewer lanes
+// than a row takes.
+int group_threads(int lanes) {
+  const int least = lanes > kWave ? lanes : kWave;  // 64, 128 or 256
+  int want = tune_get(kTuneAttnThreads);
+  want = want >= 256 ? 256 : (want >= 128 ? 128 : kWave);
+  return want > least ? want : least;
+}
+
+int row_grid(int64_t rows, int lanes, int blocks_per_cu, int rows_per_group = 1, int threads = kThreads) {
+  const int groups = (threads / lanes) * rows_per_group;
   const int64_t want = (rows + groups - 1) / groups;
   const int64_t cap = static_cast<int64_t>(compute_units()) * blocks_per_cu;
   const int64_t b = want < cap ? want : cap;
@@ -593,16 +607,33 @@ int row_grid(int64_t rows, int lanes, int blocks_per_cu, int rows_per_group = 1)
     default: return TEMPO_ERR_UNSUPPORTED;                                                 \
   }
 
+// Calls f with the workgroup size as a compile-time constant (64, 128 or 256, at least L).
+template <int L, typename F>
+static void with_threads(int threads, F&& f) {
+  using std::integral_constant;
+  if constexpr (L <= 64) {
+    if (threads == 64) return f(integral_constant<int, 64>{});
+  }
+  if constexpr (L <= 128) {
+    if (threads == 128) return f(integral_constant<int, 128>{});
+  }
+  f(integral_constant<int, 256>{});
+}
+
 template <typename T, int L, int C>
-static void attn_fwd_go(int rr, bool words, dim3 grid, hipStream_t st, const void* scores,
-                        const int32_t* key_len, int causal, void* probs, void* out,
-                        uint32_t* keep_bits, int slices, int64_t A, int64_t Sq, int64_t Sk,
-                        float scale, const RngArgs& rng) {
+static void attn_fwd_go(int rr, bool words, int threads, dim3 grid, hipStream_t st,
+                        const void* scores, const int32_t* key_len, int causal, void* probs,
+                        void* out, uint32_t* keep_bits, int slices, int64_t A, int64_t Sq,
+                        int64_t Sk, float scale, const RngArgs& rng) {
   auto go = [&](auto rows, auto w) {
-    hipLaunchKernelGGL((attn_fwd_kernel<T, L, C, decltype(rows)::value, decltype(w)::value>), grid,
-                       dim3(kThreads), 0, st, static_cast<const T*>(scores), key_len, causal,
-                       static_cast<T*>(probs), static_cast<T*>(out), keep_bits, slices,
-                       static_cast<int>(A), static_cast<int>(Sq), static_cast<int>(Sk), scale, rng);
+    with_threads<L>(threads, [&](auto th) {
+      constexpr int TH = decltype(th)::value;
+      hipLaunchKernelGGL(
+          (attn_fwd_kernel<T, L, C, decltype(rows)::value, decltype(w)::value, TH>), grid, dim3(TH),
+          0, st, static_cast<const T*>(scores), key_len, causal, static_cast<T*>(probs),
+          static_cast<T*>(out), keep_bits, slices, static_cast<int>(A), static_cast<int>(Sq),
+          static_cast<int>(Sk), scale, rng);
+    });
   };
   using std::integral_constant;
   if constexpr (C <= 2 && L <= kWave) {
@@ -616,15 +647,17 @@ static void attn_fwd_go(int rr, bool words, dim3 grid, hipStream_t st, const voi
 }
 
 template <typename T, int L, int C>
-static void attn_bwd_go(MaskSource mask, int grid, hipStream_t st, const void* dout,
+static void attn_bwd_go(MaskSource mask, int threads, int grid, hipStream_t st, const void* dout,
                         const void* probs, const uint32_t* keep_bits, void* dscores, void* out_re,
                         int64_t rows, int64_t Sk, float scale, const RngArgs& rng) {
   auto go = [&](auto m) {
-    hipLaunchKernelGGL((attn_bwd_kernel<T, L, C, 1, decltype(m)::value>), dim3(grid),
-                       dim3(kThreads), 0, st, static_cast<const T*>(dout),
-                       static_cast<const T*>(probs), keep_bits, static_cast<T*>(dscores),
-                       static_cast<T*>(out_re), static_cast<uint32_t>(rows), static_cast<int>(Sk),
-                       scale, rng);
+    with_threads<L>(threads, [&](auto th) {
+      constexpr int TH = decltype(th)::value;
+      hipLaunchKernelGGL((attn_bwd_kernel<T, L, C, 1, decltype(m)::value, TH>), dim3(grid), dim3(TH),
+                         0, st, static_cast<const T*>(dout), static_cast<const T*>(probs), keep_bits,
+                         static_cast<T*>(dscores), static_cast<T*>(out_re),
+                         static_cast<uint32_t>(rows), static_cast<int>(Sk), scale, rng);
+    });
   };
   using std::integral_constant;
   if (mask == kMaskWords) return go(integral_constant<MaskSource, kMaskWords>{});
@@ -660,7 +693,8 @@ tempo_status launch_attn_fwd(const void* scores, const int32_t* key_len, int cau
   if (Sk % 8 == 0 && sh.ch != 0 && rows <= UINT32_MAX) {  // rows counted in 32 bits
     const int slices = static_cast<int>(B * A);
     const int rr = sh.lanes > kWave ? 1 : attn_rows(sh.ch, sh.lanes, vec, tune_get(kTuneAttnFwdRows));
-    const int rows_per_set = (kThreads / sh.lanes) * rr;
+    const int threads = group_threads(sh.lanes);
+    const int rows_per_set = (threads / sh.lanes) * rr;
     const int64_t total_sets =
         static_cast<int64_t>(slices) * ((Sq + rows_per_set - 1) / rows_per_set);
     const int64_t cap = static_cast<int64_t>(compute_units()) * bpc;
@@ -668,8 +702,8 @@ tempo_status launch_attn_fwd(const void* scores, const int32_t* key_len, int cau
     const bool words = (Sk % 32 == 0);
 #define TEMPO_LAUNCH(L, C)                                                                   \
   do {                                                                                       \
-    if (dt == TEMPO_F32) attn_fwd_go<float, L, C>(rr, words, grid, st, scores, key_len, causal, probs, out, keep_bits, slices, A, Sq, Sk, scale, rng);   \
-    else attn_fwd_go<bf16_t, L, C>(rr, words, grid, st, scores, key_len, causal, probs, out, keep_bits, slices, A, Sq, Sk, scale, rng);                  \
+    if (dt == TEMPO_F32) attn_fwd_go<float, L, C>(rr, words, threads, grid, st, scores, key_len, causal, probs, out, keep_bits, slices, A, Sq, Sk, scale, rng);   \
+    else attn_fwd_go<bf16_t, L, C>(rr, words, threads, grid, st, scores, key_len, causal, probs, out, keep_bits, slices, A, Sq, Sk, scale, rng);                  \
   } while (0)
     if (sh.lanes > kWave) {
       TEMPO_ATTN_WIDE_DISPATCH(TEMPO_LAUNCH)
@@ -714,13 +748,14 @@ static tempo_status attn_bwd_any(const void* dout, const void* probs, const uint
   Shape sh = pick_wide_shape(static_cast<int>(Sk / vec), 32 / vec,
                             tune_get(kTuneAttnBwdMaxPieces));
   if (Sk % 8 == 0 && sh.ch != 0 && rows <= UINT32_MAX) {  // rows counted in 32 bits
-    const int grid = row_grid(rows, sh.lanes, bpc);
+    const int threads = group_threads(sh.lanes);
+    const int grid = row_grid(rows, sh.lanes, bpc, 1, threads);
     const MaskSource mask =
         regen ? kMaskRegen : (bools ? kMaskBools : (Sk % 32 == 0 ? kMaskWords : kMaskBytes));
 #define TEMPO_LAUNCH(L, C)                                                                   \
   do {                                                                                       \
-    if (dt == TEMPO_F32) attn_bwd_go<float, L, C>(mask, grid, st, dout, probs, keep_bits, dscores, out_re, rows, Sk, scale, rng);   \
-    else attn_bwd_go<bf16_t, L, C>(mask, grid, st, dout, probs, keep_bits, dscores, out_re, rows, Sk, scale, rng);                  \
+    if (dt == TEMPO_F32) attn_bwd_go<float, L, C>(mask, threads, grid, st, dout, probs, keep_bits, dscores, out_re, rows, Sk, scale, rng);   \
+    else attn_bwd_go<bf16_t, L, C>(mask, threads, grid, st, dout, probs, keep_bits, dscores, out_re, rows, Sk, scale, rng);                  \
   } while (0)
     if (sh.lanes > kWave) {
       TEMPO_ATTN_WIDE_DISPATCH(TEMPO_LAUNCH)

@@ -25,7 +25,8 @@ enum TuneKey {
   kTuneLnBwdMaxPieces = 11,     // and layernorm_bwd
   kTuneLnBwdLoopBlocksPerCu = 12,  // layernorm_bwd: workgroups per CU beyond which they loop
   kTuneGeluFwdSmallGroupsFrom = 13,  // bf16 gelu/silu fwd: Mi elements from which 512-lane groups
-  kTuneCount = 14
+  kTuneAttnThreads = 14,        // attn fwd / bwd: lanes per workgroup (64, 128 or 256; at least one row's)
+  kTuneCount = 15
 };
 int tune_get(TuneKey k);
 int compute_units();

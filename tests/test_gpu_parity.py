@@ -754,6 +754,38 @@ def test_layernorm_constant_rows(B, M, dt, eps):
     assert np.abs(host(dgd) - dg_ref).max() <= 1e-5 * max(1.0, np.abs(dy).max()) * N
 
 
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+@pytest.mark.parametrize("shape", [(2, 3, 70, 128), (1, 2, 37, 512), (1, 1, 9, 2048), (1, 2, 5, 4104)])
+def test_attention_does_not_depend_on_workgroup_size(B, shape, dt):
+    """Knob 14: one, two or four waves per workgroup (never fewer lanes than a row takes) give
+    bit-identical P, Out, mask, dS and recomputed Out, equal to the default choice."""
+    rng = np.random.default_rng(sum(shape))
+    sd = dev(stored(rng, shape, dt, 0.125), dt)
+    dod = dev(stored(rng, shape, dt), dt)
+    n = sd.numel()
+    kl = torch.tensor([shape[3] - 3] * shape[0], dtype=torch.int32, device="cuda")
+    results = []
+    old = B.tempo_get_launch_param(14)
+    try:
+        for threads in (old, 64, 128, 256):
+            B.tempo_set_launch_param(14, threads)
+            Pd, od = torch.full_like(sd, 3.0), torch.full_like(sd, 3.0)
+            md = torch.zeros(B.mask_words(n), dtype=torch.int32, device="cuda")
+            B.tempo_attn_softmax_dropout_fwd(sd, kl, True, Pd, od, md, 0.1, 5, 6)
+            dsd, ord_ = torch.full_like(sd, 3.0), torch.full_like(sd, 3.0)
+            B.tempo_attn_softmax_dropout_bwd(dod, Pd, md, dsd, ord_, 0.1)
+            torch.cuda.synchronize()
+            results.append((Pd, od, md, dsd, ord_))
+    finally:
+        B.tempo_set_launch_param(14, old)
+    view = torch.int16 if dt == "bf16" else torch.int32
+    for r in results[1:]:
+        for a, b in zip(results[0], r):
+            assert torch.equal(a.view(view) if a.dtype != torch.int32 else a,
+                               b.view(view) if b.dtype != torch.int32 else b)
+    assert torch.equal(results[0][1].view(view), results[0][4].view(view))   # Out recomputed
+
+
 @pytest.mark.parametrize("nr,nw", [(1, 1), (2, 1), (1, 2), (2, 2), (3, 2)])
 def test_copy_streams_yardstick(B, nr, nw):
     """The plain multi-stream kernel bench.py holds the layer kernels against: every write
