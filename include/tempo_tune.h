@@ -18,7 +18,7 @@ extern "C" {
  * reads the knobs it depends on once per call, so its workspace check and its launch always
  * agree; a knob changed between tempo_layernorm_bwd_workspace_bytes and the call can at worst
  * make that call return TEMPO_ERR_WORKSPACE.
- *   key 0 / 1: 16-byte pieces per lane in gelu_fwd / gelu_bwd (1, 2 or 4);
+ *   key 0 / 1: 16-byte pieces per lane in gelu_fwd / gelu_bwd (1, 2 or 4; float32: see key 15);
  *   key 13: tensor size in Mi elements from which the bfloat16 gelu/silu forward uses workgroups
  *   of 512 lanes with half the pieces per lane (65536: never);
  *   key 2, 4, 5: cap on workgroups per compute unit of layernorm_fwd, attn fwd, attn bwd
@@ -26,6 +26,9 @@ extern "C" {
  *   key 6, 7: rows a lane group of attn fwd / layernorm_fwd fetches at once (1 or 2);
  *   key 8, 9, 10, 11: attn fwd / attn bwd / layernorm_fwd / layernorm_bwd: 16-byte pieces per
  *   lane above which a row is spread over 2 or 4 waves instead of one (16 or more: never);
+ *   key 15: lanes per workgroup of the float32 gelu / silu kernels (64, 128 or 256, with the
+ *   pieces per lane of keys 0 / 1; 1, the default: one wave and one piece for the forwards that
+ *   stage no table, four waves and four (forward) or two (backward) pieces for the others);
  *   key 14: lanes per workgroup of attn fwd / bwd (64, 128 or 256; never fewer than a row's);
  *   key 3: rows each lane group of layernorm_bwd walks; key 12: workgroups per compute unit
  *   beyond which its workgroups loop over the rows; keys 3, 11 and 12 set its grid and the

@@ -23,6 +23,7 @@ static std::atomic<int> g_tune[kTuneCount] = {
     {1},      // layernorm bwd: workgroups per CU beyond which they loop with prefetch
     {24},     // bf16 gelu/silu fwd: Mi elements from which workgroups have 512 lanes
     {128},    // attention fwd / bwd: lanes per workgroup
+    {1},      // float32 gelu/silu: lanes per workgroup (1: chosen per kernel)
 };
 
 int tune_get(TuneKey k) { return g_tune[k].load(std::memory_order_relaxed); }

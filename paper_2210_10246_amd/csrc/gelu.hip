@@ -20,8 +20,6 @@
 namespace tempo {
 namespace {
 
-constexpr int kThreads = 256;
-
 template <int KIND>
 struct GeluConst;
 // Per activation: the minimum (x* as compared in float32, y* split hi + lo), the number of
@@ -121,9 +119,9 @@ __device__ __forceinline__ float gelu_composite(float y, bool right, const f32x4
   return (y != y) ? y : d;
 }
 
-template <int ROWS>
+template <int ROWS, int THREADS>
 __device__ __forceinline__ void load_table(f32x4* lds, const uint32_t (*src)[4]) {
-  for (int i = threadIdx.x; i < ROWS; i += kThreads) {
+  for (int i = threadIdx.x; i < ROWS; i += THREADS) {
     const u32x4 r = *reinterpret_cast<const u32x4*>(src[i]);
     f32x4 f = {as_f32(r.x), as_f32(r.y), as_f32(r.z), as_f32(r.w)};
     lds[i] = f;
@@ -133,22 +131,28 @@ __device__ __forceinline__ void load_table(f32x4* lds, const uint32_t (*src)[4])
 
 
 // ---- float32 storage: piecewise cubics ------------------------------------------------------
-// Work decomposition: workgroup b owns the contiguous tile of kThreads*K pieces (4 floats each)
-// starting at piece b*kThreads*K; piece k of lane t is tile_base + k*kThreads + t, so each
+// Work decomposition: workgroup b owns the contiguous tile of THREADS*K pieces (4 floats each)
+// starting at piece b*THREADS*K; piece k of lane t is tile_base + k*THREADS + t, so each
 // access of a wave is one contiguous 1 KiB run, workgroups are short-lived, and the whole grid
 // sweeps memory front to back.  All of a lane's loads are issued before the table is staged
 // into LDS, so the two latencies overlap.  8 lanes share a 32-bit mask word.
-template <int KIND, int K>
-__global__ __launch_bounds__(kThreads) void gelu_fwd_kernel(const float* x, float* y,  // may alias
-                                                            uint32_t* __restrict__ mask,
-                                                            int64_t n) {
+// Workgroup size: the memory system moves the most for workgroups of a single wave with one
+// piece per lane (a plain copy gains 3-6 % over four waves), and the kernels without a table
+// (tanh form, SiLU) take exactly that shape (5 % faster than four waves of four pieces); a
+// kernel that stages a table pays for it once per workgroup and does best with four waves
+// (two waves measured equal within noise for the 4 KiB forward table and 5 % slower for the
+// 17 KiB backward table of SiLU).
+template <int KIND, int K, int THREADS>
+__global__ __launch_bounds__(THREADS) void gelu_fwd_kernel(const float* x, float* y,  // may alias
+                                                           uint32_t* __restrict__ mask,
+                                                           int64_t n) {
   __shared__ f32x4 tab[KIND == TEMPO_GELU_ERF ? TEMPO_GELU_FWD_ROWS : 1];
   const float xstar = as_f32(GeluConst<KIND>::xstar);
-  const int64_t q_base = static_cast<int64_t>(blockIdx.x) * (kThreads * K) + threadIdx.x;
+  const int64_t q_base = static_cast<int64_t>(blockIdx.x) * (THREADS * K) + threadIdx.x;
   float v[K][4];
 #pragma unroll
   for (int k = 0; k < K; ++k) {
-    const int64_t q = q_base + k * kThreads;
+    const int64_t q = q_base + k * THREADS;
     const int64_t left = n - q * 4;
     if (left > 0) {
       load_piece_guarded<float>(x + q * 4, left, v[k], -1.0e30f);
@@ -157,10 +161,10 @@ __global__ __launch_bounds__(kThreads) void gelu_fwd_kernel(const float* x, floa
       for (int i = 0; i < 4; ++i) v[k][i] = -1.0e30f;  // absent: mask bit 0
     }
   }
-  if (KIND == TEMPO_GELU_ERF) load_table<TEMPO_GELU_FWD_ROWS>(tab, tempo_gelu_fwd_table_erf);
+  if (KIND == TEMPO_GELU_ERF) load_table<TEMPO_GELU_FWD_ROWS, THREADS>(tab, tempo_gelu_fwd_table_erf);
 #pragma unroll
   for (int k = 0; k < K; ++k) {
-    const int64_t q = q_base + k * kThreads;
+    const int64_t q = q_base + k * THREADS;
     const int64_t left = n - q * 4;
     uint32_t bits = 0;
     float r[4];
@@ -177,18 +181,18 @@ __global__ __launch_bounds__(kThreads) void gelu_fwd_kernel(const float* x, floa
   }
 }
 
-template <int KIND, int K>
-__global__ __launch_bounds__(kThreads) void gelu_bwd_kernel(const float* dy,  // may alias dx
-                                                            const float* __restrict__ y,
-                                                            const uint32_t* __restrict__ mask,
-                                                            float* dx, int64_t n) {
+template <int KIND, int K, int THREADS>
+__global__ __launch_bounds__(THREADS) void gelu_bwd_kernel(const float* dy,  // may alias dx
+                                                           const float* __restrict__ y,
+                                                           const uint32_t* __restrict__ mask,
+                                                           float* dx, int64_t n) {
   __shared__ f32x4 tab[GeluConst<KIND>::kBwdRows];
-  const int64_t q_base = static_cast<int64_t>(blockIdx.x) * (kThreads * K) + threadIdx.x;
+  const int64_t q_base = static_cast<int64_t>(blockIdx.x) * (THREADS * K) + threadIdx.x;
   float g[K][4], o[K][4];
   uint32_t w[K];
 #pragma unroll
   for (int k = 0; k < K; ++k) {
-    const int64_t q = q_base + k * kThreads;
+    const int64_t q = q_base + k * THREADS;
     const int64_t left = n - q * 4;
     w[k] = 0;
     if (left > 0) {
@@ -197,10 +201,10 @@ __global__ __launch_bounds__(kThreads) void gelu_bwd_kernel(const float* dy,  //
       w[k] = __builtin_nontemporal_load(mask + (q >> 3));
     }
   }
-  load_table<GeluConst<KIND>::kBwdRows>(tab, GeluConst<KIND>::bwd_table());
+  load_table<GeluConst<KIND>::kBwdRows, THREADS>(tab, GeluConst<KIND>::bwd_table());
 #pragma unroll
   for (int k = 0; k < K; ++k) {
-    const int64_t q = q_base + k * kThreads;
+    const int64_t q = q_base + k * THREADS;
     const int64_t left = n - q * 4;
     if (left <= 0) continue;
     const uint32_t bits = w[k] >> (4 * static_cast<int>(q & 7));
@@ -433,15 +437,38 @@ int lut_grid(int64_t n, int k, int threads) {
 }
 
 
-int tile_grid(int64_t n, int k) {  // float32 pieces of 4 elements
+int tile_grid(int64_t n, int k, int threads) {  // float32 pieces of 4 elements
   const int64_t n_pieces = (n + 3) / 4;
-  const int64_t per_block = static_cast<int64_t>(kThreads) * k;
+  const int64_t per_block = static_cast<int64_t>(threads) * k;
   return static_cast<int>((n_pieces + per_block - 1) / per_block);
 }
 
 int pick_k(int tuned) { return tuned >= 4 ? 4 : (tuned >= 2 ? 2 : 1); }
 
 }  // namespace
+
+// Shape of the float32 kernels: lanes per workgroup and pieces per lane.  Knob 15 at 1: the
+// measured optimum (see gelu_fwd_kernel: one wave of one piece without a table, else four waves
+// of four (forward) or two (backward) pieces); else that many lanes with the pieces of knobs 0 / 1.
+struct F32Shape {
+  int threads;
+  int k;
+};
+static F32Shape f32_shape(bool forward, int kind) {
+  const int forced = tune_get(kTuneGeluF32Threads);
+  if (forced == 1) {
+    const bool table = !forward || kind == TEMPO_GELU_ERF;
+    return table ? F32Shape{256, forward ? 4 : 2} : F32Shape{64, 1};
+  }
+  const int k = pick_k(tune_get(forward ? kTuneGeluFwdChunks : kTuneGeluBwdChunks));
+  return {forced >= 256 ? 256 : (forced >= 128 ? 128 : 64), k};
+}
+template <typename F>
+static void with_f32_threads(int threads, F&& f) {
+  if (threads == 64) f(std::integral_constant<int, 64>{});
+  else if (threads == 128) f(std::integral_constant<int, 128>{});
+  else f(std::integral_constant<int, 256>{});
+}
 
 // Launch KERNEL<KIND, K> for the run-time (kind, k); THREADS lanes per workgroup.
 template <int KIND, typename F>
@@ -475,10 +502,14 @@ tempo_status launch_gelu_fwd(const void* x, void* y, uint32_t* mask, int64_t n, 
     });
     return launch_status();
   }
-  with_kind_k(kind, k, [&](auto kd, auto kk) {
-    hipLaunchKernelGGL((gelu_fwd_kernel<decltype(kd)::value, decltype(kk)::value>),
-                       dim3(tile_grid(n, k)), dim3(kThreads), 0, st, static_cast<const float*>(x),
-                       static_cast<float*>(y), mask, n);
+  const F32Shape sh = f32_shape(true, kind);
+  with_kind_k(kind, sh.k, [&](auto kd, auto kk) {
+    with_f32_threads(sh.threads, [&](auto th) {
+      constexpr int TH = decltype(th)::value;
+      hipLaunchKernelGGL((gelu_fwd_kernel<decltype(kd)::value, decltype(kk)::value, TH>),
+                         dim3(tile_grid(n, sh.k, TH)), dim3(TH), 0, st, static_cast<const float*>(x),
+                         static_cast<float*>(y), mask, n);
+    });
   });
   return launch_status();
 }
@@ -495,10 +526,14 @@ tempo_status launch_gelu_bwd(const void* dy, const void* y, const uint32_t* mask
     });
     return launch_status();
   }
-  with_kind_k(kind, k, [&](auto kd, auto kk) {
-    hipLaunchKernelGGL((gelu_bwd_kernel<decltype(kd)::value, decltype(kk)::value>),
-                       dim3(tile_grid(n, k)), dim3(kThreads), 0, st, static_cast<const float*>(dy),
-                       static_cast<const float*>(y), mask, static_cast<float*>(dx), n);
+  const F32Shape sh = f32_shape(false, kind);
+  with_kind_k(kind, sh.k, [&](auto kd, auto kk) {
+    with_f32_threads(sh.threads, [&](auto th) {
+      constexpr int TH = decltype(th)::value;
+      hipLaunchKernelGGL((gelu_bwd_kernel<decltype(kd)::value, decltype(kk)::value, TH>),
+                         dim3(tile_grid(n, sh.k, TH)), dim3(TH), 0, st, static_cast<const float*>(dy),
+                         static_cast<const float*>(y), mask, static_cast<float*>(dx), n);
+    });
   });
   return launch_status();
 }

@@ -26,7 +26,8 @@ enum TuneKey {
   kTuneLnBwdLoopBlocksPerCu = 12,  // layernorm_bwd: workgroups per CU beyond which they loop
   kTuneGeluFwdSmallGroupsFrom = 13,  // bf16 gelu/silu fwd: Mi elements from which 512-lane groups
   kTuneAttnThreads = 14,        // attn fwd / bwd: lanes per workgroup (64, 128 or 256; at least one row's)
-  kTuneCount = 15
+  kTuneGeluF32Threads = 15,     // float32 gelu/silu: lanes per workgroup (64, 128, 256; 1 = per kernel)
+  kTuneCount = 16
 };
 int tune_get(TuneKey k);
 int compute_units();

@@ -112,6 +112,37 @@ def test_gelu_fwd_next_to_its_zero(B, dt, kind):
 
 @pytest.mark.parametrize("kind", ACT_KINDS)
 @pytest.mark.parametrize("dt", ["f32", "bf16"])
+def test_activation_does_not_depend_on_launch_shape(B, dt, kind):
+    """Knobs 0, 1 (pieces per lane), 13 (bf16 forward workgroup size) and 15 (float32 lanes per
+    workgroup): every shape gives bit-identical y, mask and dx, equal to the default's."""
+    n = 300_007
+    rng = np.random.default_rng(15)
+    xd, dyd = dev(stored(rng, n, dt, 1.5), dt), dev(stored(rng, n, dt), dt)
+    keys = (0, 1, 13, 15)
+    old = [B.tempo_get_launch_param(k) for k in keys]
+    results = []
+    try:
+        shapes = [tuple(old)] + [(k0, k1, g, t) for k0 in (1, 2, 4) for k1 in (1, 2, 4)
+                                 for g, t in ((1, 64), (65536, 128), (old[2], 256), (old[2], 1))]
+        for shape in shapes:
+            for k, v in zip(keys, shape):
+                B.tempo_set_launch_param(k, v)
+            yd = torch.full_like(xd, 7.0)
+            md = torch.zeros(B.mask_words(n), dtype=torch.int32, device="cuda")
+            dxd = torch.full_like(xd, 7.0)
+            act_fwd(B, kind, xd, yd, md)
+            act_bwd(B, kind, dyd, yd, md, dxd)
+            torch.cuda.synchronize()
+            results.append((yd, md, dxd))
+    finally:
+        for k, v in zip(keys, old):
+            B.tempo_set_launch_param(k, v)
+    for r in results[1:]:
+        assert all(torch.equal(a, b) for a, b in zip(results[0], r))
+
+
+@pytest.mark.parametrize("kind", ACT_KINDS)
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
 @pytest.mark.parametrize("n", [1, 9, 33, 4099, 300_000])
 def test_gelu_bwd(B, n, dt, kind):
     rng = np.random.default_rng(100 + n)
