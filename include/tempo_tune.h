@@ -27,8 +27,8 @@ extern "C" {
  *   key 8, 9, 10, 11: attn fwd / attn bwd / layernorm_fwd / layernorm_bwd: 16-byte pieces per
  *   lane above which a row is spread over 2 or 4 waves instead of one (16 or more: never);
  *   key 15: lanes per workgroup of the float32 gelu / silu kernels (64, 128 or 256, with the
- *   pieces per lane of keys 0 / 1; 1, the default: one wave and one piece for the forwards that
- *   stage no table, four waves and four (forward) or two (backward) pieces for the others);
+ *   pieces per lane of keys 0 / 1; 1, the default: one wave of one piece per lane forward, four
+ *   waves of two pieces backward);
  *   key 14: lanes per workgroup of attn fwd / bwd (64, 128 or 256; never fewer than a row's);
  *   key 3: rows each lane group of layernorm_bwd walks; key 12: workgroups per compute unit
  *   beyond which its workgroups loop over the rows; keys 3, 11 and 12 set its grid and the

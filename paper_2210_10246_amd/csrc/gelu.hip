@@ -6,9 +6,10 @@
 //
 // Both kernels are streaming: every lane owns 16-byte pieces (8 bf16 or 4 f32 elements); the
 // mask bits of a piece are merged over the 4 (bf16) or 8 (f32) adjacent lanes that share a
-// word, so the mask is written and read as whole 32-bit words.  float32 evaluates piecewise
-// cubics whose coefficient rows live in LDS (one ds_read_b128 per element); bfloat16 looks the
-// function value up per bit pattern.
+// word, so the mask is written and read as whole 32-bit words.  float32 forward evaluates the
+// activation directly (exp2 and rcp), float32 backward piecewise cubics whose coefficient rows
+// live in LDS (one ds_read_b128 per element); bfloat16 looks the function value up per bit
+// pattern.
 #include <type_traits>
 
 #include "tempo_device.h"
@@ -48,20 +49,29 @@ __device__ __forceinline__ float cubic(const f32x4 c, float z) {
   return fmaf(fmaf(fmaf(c.w, z, c.z), z, c.y), z, c.x);
 }
 
-// GELU(x) = x Phi(x), erf form: Phi as cubic pieces of width 1/16 on [-8, 8); x outside is x
-// (right) or -0 (left).  Multiplying by x keeps the zero at x = 0 exact and the relative error
-// that of Phi however small |x| is.
-__device__ __forceinline__ float gelu_erf_value(float x, const f32x4* tab) {
-  const float t = x * static_cast<float>(TEMPO_GELU_FWD_PER_UNIT);
-  const float lo = TEMPO_GELU_FWD_LO * TEMPO_GELU_FWD_PER_UNIT;
-  const float hi = TEMPO_GELU_FWD_HI * TEMPO_GELU_FWD_PER_UNIT - 0.0078125f;
-  const float fl = floorf(fminf(fmaxf(t, lo), hi));
-  const float z = t - fl;  // exact inside the table range; NaN stays NaN
-  const int idx = static_cast<int>(fl) - static_cast<int>(lo);
-  float y = x * cubic(tab[idx], z);
-  y = (x >= TEMPO_GELU_FWD_HI) ? x : y;
-  y = (x < TEMPO_GELU_FWD_LO) ? -0.0f : y;
-  return y;
+// GELU(x) = x Phi(x), erf form.  Phi(x) = 1/2 erfc(-x / sqrt 2); for z >= 0,
+// erfc(z) = exp(-z^2) erfcx(z), and 1/2 erfcx(z) (1 + z/2) is one polynomial of degree 8 in
+// t = 1 / (1 + z/2) (relative error 9e-8 up to |x| = 9; beyond, the exponential has long made
+// Phi 0 or 1).  With w = |x| sqrt(log2(e)/2) the exponential is exp2(-w^2).  x < 0 takes the
+// small value itself, so the left tail keeps its relative accuracy, and the product with x comes
+// last, so the zero at x = 0 is exact.  No table: the kernel needs no LDS.
+__device__ __forceinline__ float gelu_erf_value(float x) {
+  const float w = fabsf(x) * as_f32(TEMPO_GELU_ERFC_W_SCALE);
+  const float t = __builtin_amdgcn_rcpf(fmaf(w, as_f32(TEMPO_GELU_ERFC_T_FACTOR), 1.0f));
+  const float u = fmaf(t, as_f32(TEMPO_GELU_ERFC_UA), as_f32(TEMPO_GELU_ERFC_UB));
+  static_assert(TEMPO_GELU_ERFC_DEG == 8, "Horner chain below");
+  float q = as_f32(TEMPO_GELU_ERFC_Q8);
+  q = fmaf(q, u, as_f32(TEMPO_GELU_ERFC_Q7));
+  q = fmaf(q, u, as_f32(TEMPO_GELU_ERFC_Q6));
+  q = fmaf(q, u, as_f32(TEMPO_GELU_ERFC_Q5));
+  q = fmaf(q, u, as_f32(TEMPO_GELU_ERFC_Q4));
+  q = fmaf(q, u, as_f32(TEMPO_GELU_ERFC_Q3));
+  q = fmaf(q, u, as_f32(TEMPO_GELU_ERFC_Q2));
+  q = fmaf(q, u, as_f32(TEMPO_GELU_ERFC_Q1));
+  q = fmaf(q, u, as_f32(TEMPO_GELU_ERFC_Q0));
+  const float half_erfc = t * q * __builtin_amdgcn_exp2f(-(w * w));  // 1/2 erfc(|x| / sqrt 2)
+  const float phi = (x < 0.0f) ? half_erfc : 1.0f - half_erfc;
+  return x * phi;  // NaN stays NaN
 }
 
 // GELU(x), tanh form written as x * sigmoid(2u): no cancellation on the left tail.
@@ -81,8 +91,8 @@ __device__ __forceinline__ float silu_value(float x) {
 }
 
 template <int KIND>
-__device__ __forceinline__ float act_value(float x, const f32x4* tab) {
-  if constexpr (KIND == TEMPO_GELU_ERF) return gelu_erf_value(x, tab);
+__device__ __forceinline__ float act_value(float x) {
+  if constexpr (KIND == TEMPO_GELU_ERF) return gelu_erf_value(x);
   else if constexpr (KIND == TEMPO_GELU_TANH) return gelu_tanh_value(x);
   else return silu_value(x);
 }
@@ -134,19 +144,17 @@ __device__ __forceinline__ void load_table(f32x4* lds, const uint32_t (*src)[4])
 // Work decomposition: workgroup b owns the contiguous tile of THREADS*K pieces (4 floats each)
 // starting at piece b*THREADS*K; piece k of lane t is tile_base + k*THREADS + t, so each
 // access of a wave is one contiguous 1 KiB run, workgroups are short-lived, and the whole grid
-// sweeps memory front to back.  All of a lane's loads are issued before the table is staged
-// into LDS, so the two latencies overlap.  8 lanes share a 32-bit mask word.
+// sweeps memory front to back.  8 lanes share a 32-bit mask word.
 // Workgroup size: the memory system moves the most for workgroups of a single wave with one
-// piece per lane (a plain copy gains 3-6 % over four waves), and the kernels without a table
-// (tanh form, SiLU) take exactly that shape (5 % faster than four waves of four pieces); a
-// kernel that stages a table pays for it once per workgroup and does best with four waves
-// (two waves measured equal within noise for the 4 KiB forward table and 5 % slower for the
-// 17 KiB backward table of SiLU).
+// piece per lane (a plain copy gains 3-6 % over four waves).  The forward kernels stage no
+// table and take exactly that shape (5 % faster than four waves of four pieces).  The
+// backward kernels stage a table of 13-17 KiB, paid once per workgroup, and do best with four
+// waves of two pieces (two waves measured 5 % slower for SiLU's table).  In the backward all
+// of a lane's loads are issued before the table is staged into LDS, so the latencies overlap.
 template <int KIND, int K, int THREADS>
 __global__ __launch_bounds__(THREADS) void gelu_fwd_kernel(const float* x, float* y,  // may alias
                                                            uint32_t* __restrict__ mask,
                                                            int64_t n) {
-  __shared__ f32x4 tab[KIND == TEMPO_GELU_ERF ? TEMPO_GELU_FWD_ROWS : 1];
   const float xstar = as_f32(GeluConst<KIND>::xstar);
   const int64_t q_base = static_cast<int64_t>(blockIdx.x) * (THREADS * K) + threadIdx.x;
   float v[K][4];
@@ -161,7 +169,6 @@ __global__ __launch_bounds__(THREADS) void gelu_fwd_kernel(const float* x, float
       for (int i = 0; i < 4; ++i) v[k][i] = -1.0e30f;  // absent: mask bit 0
     }
   }
-  if (KIND == TEMPO_GELU_ERF) load_table<TEMPO_GELU_FWD_ROWS, THREADS>(tab, tempo_gelu_fwd_table_erf);
 #pragma unroll
   for (int k = 0; k < K; ++k) {
     const int64_t q = q_base + k * THREADS;
@@ -172,7 +179,7 @@ __global__ __launch_bounds__(THREADS) void gelu_fwd_kernel(const float* x, float
     for (int i = 0; i < 4; ++i) {
       const float xv = v[k][i];
       bits |= (xv >= xstar ? 1u : 0u) << i;
-      r[i] = act_value<KIND>(xv, tab);
+      r[i] = act_value<KIND>(xv);
     }
     // every lane of the wave takes part in the merge; absent pieces contribute zero bits
     const uint32_t word = merge_mask_word<4>(bits, threadIdx.x);
@@ -448,18 +455,16 @@ int pick_k(int tuned) { return tuned >= 4 ? 4 : (tuned >= 2 ? 2 : 1); }
 }  // namespace
 
 // Shape of the float32 kernels: lanes per workgroup and pieces per lane.  Knob 15 at 1: the
-// measured optimum (see gelu_fwd_kernel: one wave of one piece without a table, else four waves
-// of four (forward) or two (backward) pieces); else that many lanes with the pieces of knobs 0 / 1.
+// measured optimum (see gelu_fwd_kernel: one wave of one piece forward, four waves of two pieces
+// backward); else that many lanes with the pieces of knobs 0 / 1.
 struct F32Shape {
   int threads;
   int k;
 };
 static F32Shape f32_shape(bool forward, int kind) {
   const int forced = tune_get(kTuneGeluF32Threads);
-  if (forced == 1) {
-    const bool table = !forward || kind == TEMPO_GELU_ERF;
-    return table ? F32Shape{256, forward ? 4 : 2} : F32Shape{64, 1};
-  }
+  (void)kind;
+  if (forced == 1) return forward ? F32Shape{64, 1} : F32Shape{256, 2};
   const int k = pick_k(tune_get(forward ? kTuneGeluFwdChunks : kTuneGeluBwdChunks));
   return {forced >= 256 ? 256 : (forced >= 128 ? 128 : 64), k};
 }

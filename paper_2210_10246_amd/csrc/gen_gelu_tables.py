@@ -23,11 +23,14 @@ No inversion is needed to fit: sample x densely, compute y = GELU(x) and d = GEL
 exactly in float64, derive the piece and local variable from y, least-squares fit in the
 Chebyshev basis per piece.  The script prints the worst absolute error of each region.
 
-Forward (erf kind) table: the factor Phi(x) of GELU(x) = x Phi(x) as cubics on uniform pieces
-of width 1/16 in x over [-8, 8); the kernel multiplies by x, so that GELU(0) = 0 exactly and
-the relative error stays that of Phi for arbitrarily small |x| (a cubic of GELU itself leaves
-an absolute error of ~1e-9 around its zero).  Outside the range GELU(x) = x (right) or -0 (left)
-to below 1e-14.
+Forward (erf kind), float32: no table.  GELU(x) = x Phi(x) with Phi(x) = 1/2 erfc(-x/sqrt 2) and
+erfc(z) = exp(-z^2) erfcx(z) for z >= 0; the scaled function erfcx is smooth and slowly varying,
+and erfcx(z) (1 + z/2) is fitted by ONE polynomial of degree 8 in t = 1/(1 + z/2) over the whole
+range (relative error 7e-8).  The kernel works in w = |x| sqrt(log2(e)/2), for which
+exp(-z^2) = exp2(-w^2), and multiplies by x last, so GELU(0) = 0 exactly and the relative error
+stays that of Phi however small |x| is.  Emitted: the scale of w, the factor of w in t, the
+affine map of t onto [-1, 1] and the nine monomial coefficients in that variable, with the
+factor 1/2 folded in.
 
 bfloat16 lookup tables.  A bfloat16 input has only 2^16 bit patterns, so for bf16 storage
 both GELU and the backward composite are tabulated per pattern instead of being evaluated:
@@ -80,9 +83,9 @@ TAIL_TOP_EXP = -4          # tail is -y < 2^-4
 TAIL_OCTAVES = 24          # 2^-5 .. 2^-28
 TAIL_SUB_BITS = 2          # quarter octaves
 NT = TAIL_OCTAVES * (1 << TAIL_SUB_BITS) + 1   # + the all-zero piece
-FWD_PER_UNIT = 16
-FWD_LO, FWD_HI = -8.0, 8.0
-NF = int((FWD_HI - FWD_LO) * FWD_PER_UNIT)
+ERFC_DEG = 8
+ERFC_P = 0.5               # t = 1 / (1 + ERFC_P z)
+ERFC_XMAX = 9.0            # fitted for |x| up to here; beyond, exp2(-w^2) < 2^-58 makes Phi 0 or 1
 
 A_TANH = 0.044715
 K_TANH = math.sqrt(2.0 / math.pi)
@@ -194,16 +197,23 @@ def bwd_table(kind):
     return xs, ys, rows, errs
 
 
-def fwd_table():
-    rows = np.zeros((NF, 4))
-    worst = 0.0
-    for i in range(NF):
-        a = FWD_LO + i / FWD_PER_UNIT
-        z = 0.5 - 0.5 * np.cos(np.linspace(0, math.pi, 400))
-        x = a + z / FWD_PER_UNIT
-        rows[i], e = fit_piece(z, factor(x, "erf"))
-        worst = max(worst, e)
-    return rows, worst
+def erfc_fit():
+    """Coefficients of h(u) ~ 1/2 erfcx(z) / t, u the affine image of t = 1/(1 + P z) on [-1, 1],
+    z in [0, XMAX/sqrt 2]; relative least squares in the Chebyshev basis, returned as monomials in
+    u.  Also the constants that take |x| to w and w to t, and the worst relative error."""
+    from scipy.special import erfcx
+    zmax = ERFC_XMAX / math.sqrt(2.0)
+    t0 = 1.0 / (1.0 + ERFC_P * zmax)
+    t = np.linspace(t0, 1.0, 200001)
+    z = (1.0 / t - 1.0) / ERFC_P
+    f = 0.5 * erfcx(z) / t
+    ua, ub = 2.0 / (1.0 - t0), -2.0 * t0 / (1.0 - t0) - 1.0
+    u = ua * t + ub
+    c = cheb.chebfit(u, f, ERFC_DEG, w=1.0 / f)
+    err = float(np.abs(cheb.chebval(u, c) / f - 1.0).max())
+    w_scale = math.sqrt(math.log2(math.e) / 2.0)           # w = |x| w_scale, w^2 = z^2 log2(e)
+    t_factor = ERFC_P / math.sqrt(math.log2(math.e))        # P z = t_factor w
+    return cheb.cheb2poly(c), ua, ub, w_scale, t_factor, err
 
 
 LUT_LO = 0x3980            # bf16 pattern of 2^-12
@@ -310,10 +320,6 @@ def main(path=None):
         f"#define TEMPO_GELU_NT {NT}",
         f"#define TEMPO_GELU_TAIL_SUB_BITS {TAIL_SUB_BITS}",
         f"#define TEMPO_GELU_TAIL_TOP_EXP ({TAIL_TOP_EXP})",
-        f"#define TEMPO_GELU_FWD_ROWS {NF}",
-        f"#define TEMPO_GELU_FWD_PER_UNIT {FWD_PER_UNIT}",
-        f"#define TEMPO_GELU_FWD_LO ({FWD_LO}f)",
-        f"#define TEMPO_GELU_FWD_HI ({FWD_HI}f)",
     ]
     report = []
     for kind in KINDS:
@@ -341,9 +347,16 @@ def main(path=None):
         fwd, bwd = lut_tables(kind)
         lines += emit_flat(f"tempo_gelu_lut_fwd_{kind}", fwd)
         lines += emit_flat(f"tempo_gelu_lut_bwd_{kind}", bwd)
-    rows, worst = fwd_table()
-    lines += emit_rows("tempo_gelu_fwd_table_erf", rows)
-    report.append(f"fwd erf table (Phi): {worst:.2e}")
+    mono, ua, ub, w_scale, t_factor, worst = erfc_fit()
+    lines += [
+        f"#define TEMPO_GELU_ERFC_DEG {ERFC_DEG}",
+        f"#define TEMPO_GELU_ERFC_W_SCALE {f32_hex(w_scale)}",
+        f"#define TEMPO_GELU_ERFC_T_FACTOR {f32_hex(t_factor)}",
+        f"#define TEMPO_GELU_ERFC_UA {f32_hex(ua)}",
+        f"#define TEMPO_GELU_ERFC_UB {f32_hex(ub)}",
+    ]
+    lines += [f"#define TEMPO_GELU_ERFC_Q{i} {f32_hex(v)}" for i, v in enumerate(mono)]
+    report.append(f"fwd erf, 1/2 erfcx(z)/t as a polynomial (relative): {worst:.2e}")
     lines.insert(1, "// worst abs fit error (float64 coefficients): " + "; ".join(report))
     if path is None:
         path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "gelu_tables.inc")
