@@ -19,8 +19,12 @@ namespace {
 constexpr int kFwdThreads = 256;
 constexpr int kBwdWaves = 8;
 constexpr int kBwdThreads = kBwdWaves * kWave;
-constexpr int kMaxFastM = 4096;  // rows longer than this take the generic kernels; the backward
-                                 // LDS tree needs 32*M bytes (128 KiB at 4096)
+// Rows of more than 1024 pieces (4096 float32 or 8192 bfloat16 columns: 4 pieces per lane of
+// 4 waves) take the generic kernels.  Dynamic LDS of the backward: the reduction tree's slots
+// (32*M bytes while a row fits one wave, 128 KiB at M = 4096; 16*M over two waves; 8*M over
+// four), or gamma, 1/gamma and beta/gamma (12*M bytes, 96 KiB at M = 8192) when a lane's share of
+// them does not fit its registers, whichever is more.
+constexpr int kMaxFastPieces = 1024;
 
 // Forward.  A batch is kGroups*R consecutive rows; lane group g takes rows base + r*kGroups + g
 // and fetches all R of them (packed) before any arithmetic, so that short rows still keep
@@ -37,7 +41,9 @@ __global__ __launch_bounds__(kFwdThreads) void ln_fwd_kernel(
   const int g = threadIdx.x / LANES;
   const int t = threadIdx.x % LANES;
   const int chunks = M / V;
-  const float inv_m = 1.0f / static_cast<float>(M);
+  // mean and variance by a true division: a row of equal values c then has the mean c exactly
+  // (its sum c*M is exact) and zero variance, whatever the rounding of 1/M would do
+  const float m_f = static_cast<float>(M);
   __shared__ float red[2][kFwdThreads / kWave];
   static_assert(LANES <= kWave || R == 1, "rows over several waves: one row per group");
 
@@ -99,7 +105,7 @@ __global__ __launch_bounds__(kFwdThreads) void ln_fwd_kernel(
 #pragma unroll
         for (int i = 0; i < V; ++i) sum += v[c][i];
       }
-      const float mu = row_reduce<LANES, false>(sum, red[0]) * inv_m;
+      const float mu = row_reduce<LANES, false>(sum, red[0]) / m_f;
       float sq = 0.0f;
 #pragma unroll
       for (int c = 0; c < CH; ++c) {
@@ -111,7 +117,7 @@ __global__ __launch_bounds__(kFwdThreads) void ln_fwd_kernel(
           sq += (ch < chunks) ? d * d : 0.0f;
         }
       }
-      const float var = row_reduce<LANES, false>(sq, red[1]) * inv_m;
+      const float var = row_reduce<LANES, false>(sq, red[1]) / m_f;
       const float rs = 1.0f / sqrtf(var + eps);
 #pragma unroll
       for (int c = 0; c < CH; ++c) {
@@ -158,19 +164,19 @@ __global__ __launch_bounds__(256) void ln_fwd_generic_kernel(
     const T* x, const float* __restrict__ gamma, const float* __restrict__ beta, T* y,
     float* __restrict__ rstd_out, float* __restrict__ mean_out, int64_t N, int64_t M, float eps) {
   __shared__ float lds[4];
-  const float inv_m = 1.0f / static_cast<float>(M);
+  const float m_f = static_cast<float>(M);
   for (int64_t row = blockIdx.x; row < N; row += gridDim.x) {
     const T* xr = x + row * M;
     T* yr = y + row * M;
     float s = 0.0f;
     for (int64_t j = threadIdx.x; j < M; j += 256) s += Store<T>::load1(xr + j);
-    const float mu = block_sum_256(s, lds) * inv_m;
+    const float mu = block_sum_256(s, lds) / m_f;
     float q = 0.0f;
     for (int64_t j = threadIdx.x; j < M; j += 256) {
       const float d = Store<T>::load1(xr + j) - mu;
       q += d * d;
     }
-    const float var = block_sum_256(q, lds) * inv_m;
+    const float var = block_sum_256(q, lds) / m_f;
     const float rs = 1.0f / sqrtf(var + eps);
     for (int64_t j = threadIdx.x; j < M; j += 256) {
       const float d = Store<T>::load1(xr + j) - mu;
@@ -194,7 +200,7 @@ __global__ __launch_bounds__(kBwdThreads) void ln_bwd_kernel(
     const T* dy, const T* __restrict__ y, const float* __restrict__ gamma,
     const float* __restrict__ beta, const float* __restrict__ rstd, T* dx,
     float* __restrict__ partial, int64_t N, int M) {
-  extern __shared__ float lds[];  // [kBwdWaves/2][2][M] floats (>= 3*M)
+  extern __shared__ float lds[];  // bwd_lds_bytes(): the tree's [slots][2][M] floats, >= 3*M
   constexpr int kGroups = kBwdThreads / LANES;
   constexpr int V = Store<T>::kVec;
   const int g = threadIdx.x / LANES;
@@ -401,7 +407,8 @@ __global__ __launch_bounds__(kBwdThreads) void ln_bwd_kernel(
   }
   // Column sums: first over the groups that share a wave (fixed butterfly), then a binary tree
   // over the waves through LDS.  When a row takes W > 1 waves, wave w holds the columns of
-  // part w % W of the row: the tree only pairs waves W apart or more and stops at W waves.
+  // part w % W of the row: the tree only pairs waves W apart or more and stops at W waves, and
+  // the W waves of one row, whose columns are disjoint, share one [2][M] slot.
 #pragma unroll
   for (int c = 0; c < CH; ++c) {
 #pragma unroll
@@ -419,7 +426,7 @@ __global__ __launch_bounds__(kBwdThreads) void ln_bwd_kernel(
   for (int half = kBwdWaves / 2; half >= kRowWaves; half >>= 1) {
     __syncthreads();
     if (wave >= half && wave < 2 * half && owner) {
-      float* slot = lds + static_cast<size_t>(wave - half) * 2 * M;
+      float* slot = lds + static_cast<size_t>((wave - half) / kRowWaves) * 2 * M;
 #pragma unroll
       for (int c = 0; c < CH; ++c) {
         const int ch = c * LANES + t;
@@ -431,7 +438,7 @@ __global__ __launch_bounds__(kBwdThreads) void ln_bwd_kernel(
     }
     __syncthreads();
     if (wave < half && owner) {
-      const float* slot = lds + static_cast<size_t>(wave) * 2 * M;
+      const float* slot = lds + static_cast<size_t>(wave / kRowWaves) * 2 * M;
 #pragma unroll
       for (int c = 0; c < CH; ++c) {
         const int ch = c * LANES + t;
@@ -646,7 +653,7 @@ static void ln_fwd_go(int rr, bool loop, int grid, hipStream_t st, const void* x
 
 static bool fast_shape(int64_t M, tempo_dtype dt, bool backward, Shape* sh) {
   const int vec = dt == TEMPO_F32 ? 4 : 8;
-  if (M % vec != 0 || M > kMaxFastM) return false;
+  if (M % vec != 0 || M / vec > kMaxFastPieces) return false;
   const int pieces = static_cast<int>(M / vec);
   *sh = widen_shape(pick_shape(pieces, backward), pieces,
                     tune_get(backward ? kTuneLnBwdMaxPieces : kTuneLnFwdMaxPieces), 256);
@@ -723,6 +730,18 @@ static BwdPlan bwd_plan(int64_t N, const Shape& sh) {
   }
   if (p.grid < 1) p.grid = 1;
   return p;
+}
+
+// Dynamic LDS of the backward kernel: the reduction tree's slots, one per kRowWaves waves of
+// the upper half of the workgroup, or the three parameter vectors when they live in LDS.
+static size_t bwd_lds_bytes(const Shape& sh, int64_t M, tempo_dtype dt) {
+  const int row_waves = sh.lanes > kWave ? sh.lanes / kWave : 1;
+  const int slots = kBwdWaves / 2 / row_waves > 0 ? kBwdWaves / 2 / row_waves : 1;
+  const int vec = dt == TEMPO_F32 ? 4 : 8;
+  const bool reg_params = sh.ch * vec <= 24;  // kRegParams of ln_bwd_kernel
+  size_t floats = static_cast<size_t>(slots) * 2 * M;
+  if (!reg_params && floats < static_cast<size_t>(3) * M) floats = static_cast<size_t>(3) * M;
+  return floats * sizeof(float);
 }
 
 // Launches the register-resident backward kernel; returns the number of workgroups used (the
@@ -817,7 +836,7 @@ tempo_status launch_layernorm_bwd(const void* dy, const void* y, const float* ga
   int grid = b.plan.grid;
   if (b.fast) {
     const Shape sh = b.sh;
-    const size_t lds_bytes = static_cast<size_t>(kBwdWaves / 2) * 2 * M * sizeof(float);
+    const size_t lds_bytes = bwd_lds_bytes(sh, M, dt);
     const BwdPlan plan = b.plan;
 #define TEMPO_LAUNCH(L, C)                                                                   \
   do {                                                                                       \

@@ -208,7 +208,9 @@ def test_gelu_round_trip_against_input_based_gradient(B, dt, kind):
 
 # ------------------------------------------------------------------ LayerNorm
 LN_SHAPES = [(256, 768), (5, 1024), (37, 768), (3, 8), (9, 64), (7, 100), (4, 4096), (3, 2048),
-             (2, 4104), (1, 1), (6, 1536), (300, 1024), (3, 3072), (1030, 256)]
+             (2, 4104), (1, 1), (6, 1536), (300, 1024), (3, 3072), (1030, 256),
+             # beyond 4096 columns: register-resident in bfloat16 up to 8192, any-shape kernels else
+             (5, 8192), (70, 6144), (300, 5120), (2, 8200)]
 
 
 @pytest.mark.parametrize("eps", [1e-12, 1e-5])
@@ -752,7 +754,7 @@ def test_attn_scores_with_minus_infinity_and_large_magnitudes(B, Sk, dt):
 
 @pytest.mark.parametrize("eps", [1e-12, 1e-5])
 @pytest.mark.parametrize("dt", ["f32", "bf16"])
-@pytest.mark.parametrize("M", [64, 1024, 4104])
+@pytest.mark.parametrize("M", [64, 768, 1024, 4104, 6152])
 def test_layernorm_constant_rows(B, M, dt, eps):
     # zero variance: rstd = 1/sqrt(eps), y = beta exactly (the constants are chosen so that the
     # float32 row sums are exact), and backward from y = beta
