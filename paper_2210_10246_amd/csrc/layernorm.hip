@@ -20,11 +20,15 @@ constexpr int kFwdThreads = 256;
 constexpr int kBwdWaves = 8;
 constexpr int kBwdThreads = kBwdWaves * kWave;
 // Rows of more than 1024 pieces (4096 float32 or 8192 bfloat16 columns: 4 pieces per lane of
-// 4 waves) take the generic kernels.  Dynamic LDS of the backward: the reduction tree's slots
-// (32*M bytes while a row fits one wave, 128 KiB at M = 4096; 16*M over two waves; 8*M over
-// four), or gamma, 1/gamma and beta/gamma (12*M bytes, 96 KiB at M = 8192) when a lane's share of
-// them does not fit its registers, whichever is more.
+// 4 waves) take the generic kernels.  Dynamic LDS of the backward: the column sums' slots (all
+// of them, 64*M bytes while a row fits one wave, when that is at most kOneStepLdsBytes; else
+// half of them for a tree: 32*M bytes while a row fits one wave, 128 KiB at M = 4096; 16*M over
+// two waves; 8*M over four), or gamma, 1/gamma and beta/gamma (12*M bytes, 96 KiB at M = 8192)
+// when a lane's share of them does not fit its registers, whichever is more.
 constexpr int kMaxFastPieces = 1024;
+// Most LDS the backward's column sums may take in one step (every wave's sums at once); two
+// workgroups of that size still fit a compute unit.
+constexpr size_t kOneStepLdsBytes = 64 * 1024;
 
 // Forward.  A batch is kGroups*R consecutive rows; lane group g takes rows base + r*kGroups + g
 // and fetches all R of them (packed) before any arithmetic, so that short rows still keep
@@ -152,9 +156,9 @@ __global__ __launch_bounds__(kFwdThreads) void ln_fwd_kernel(
 __device__ __forceinline__ float block_sum_256(float v, float* lds) {
   v = group_sum<kWave>(v);
   const int w = threadIdx.x / kWave;
-  __syncthreads();
+  lds_barrier();
   if ((threadIdx.x & (kWave - 1)) == 0) lds[w] = v;
-  __syncthreads();
+  lds_barrier();
   return (lds[0] + lds[1]) + (lds[2] + lds[3]);
 }
 
@@ -291,7 +295,7 @@ __global__ __launch_bounds__(kBwdThreads) void ln_bwd_kernel(
       p_rg[j] = rj;
       p_bg[j] = beta[j] * rj;
     }
-    __syncthreads();
+    lds_barrier();
   }
   while (base < N) {
     const int64_t next = base + static_cast<int64_t>(gridDim.x) * batch_rows;
@@ -405,10 +409,19 @@ __global__ __launch_bounds__(kBwdThreads) void ln_bwd_kernel(
       base = next;
     }
   }
-  // Column sums: first over the groups that share a wave (fixed butterfly), then a binary tree
-  // over the waves through LDS.  When a row takes W > 1 waves, wave w holds the columns of
-  // part w % W of the row: the tree only pairs waves W apart or more and stops at W waves, and
-  // the W waves of one row, whose columns are disjoint, share one [2][M] slot.
+  // Column sums of the workgroup -> its [2][M] slot of `partial`.  First over the lane groups
+  // that share a wave (fixed butterfly), then over the waves through LDS.  When a row takes
+  // W > 1 waves, wave w holds the columns of part w % W of the row; the W waves of one row, whose
+  // columns are disjoint, share one [2][M] LDS slot, so there are S = kBwdWaves / W slots to add.
+  // The association is the same on both routes, a binary tree that pairs slot s with s + S/2,
+  // then s + S/4, ...:
+  //  - all S slots fit kOneStepLdsBytes: every wave writes its sums, one barrier, and each lane
+  //    of the workgroup adds one 16-byte piece of the S slots and stores it;
+  //  - else the tree runs through S/2 slots, a barrier pair per level, and the waves of slot 0
+  //    store the result.
+  // This tail is on the critical path of the kernel (the tree and the slot's store were each
+  // measured at about a microsecond of it); running it before the last batch's dx is stored
+  // hides the store but puts a barrier between the waves' loads and stores, and was slower.
 #pragma unroll
   for (int c = 0; c < CH; ++c) {
 #pragma unroll
@@ -422,9 +435,41 @@ __global__ __launch_bounds__(kBwdThreads) void ln_bwd_kernel(
   }
   const bool owner = lane < LANES;  // one copy per wave
   constexpr int kRowWaves = LANES > kWave ? LANES / kWave : 1;
+  constexpr int S = kBwdWaves / kRowWaves;
+  float* out = partial + static_cast<size_t>(blockIdx.x) * 2 * M;
+  if (static_cast<size_t>(S) * 2 * M * sizeof(float) <= kOneStepLdsBytes) {
+    if constexpr (!kRegParams) lds_barrier();  // the parameters in LDS are no longer read
+    if (owner) {
+      float* slot = lds + static_cast<size_t>(wave / kRowWaves) * 2 * M;
+#pragma unroll
+      for (int c = 0; c < CH; ++c) {
+        const int ch = c * LANES + t;
+        if (ch < chunks) {
+          store_floats<V>(slot + ch * V, acc_g[c]);
+          store_floats<V>(slot + M + ch * V, acc_b[c]);
+        }
+      }
+    }
+    lds_barrier();
+    for (int j = threadIdx.x * 4; j < 2 * M; j += kBwdThreads * 4) {
+      float v[S][4];
+#pragma unroll
+      for (int k = 0; k < S; ++k) load_floats<4>(lds + static_cast<size_t>(k) * 2 * M + j, v[k]);
+#pragma unroll
+      for (int half = S / 2; half >= 1; half >>= 1) {
+#pragma unroll
+        for (int k = 0; k < half; ++k) {
+#pragma unroll
+          for (int i = 0; i < 4; ++i) v[k][i] += v[k + half][i];
+        }
+      }
+      store_floats<4>(out + j, v[0]);
+    }
+    return;
+  }
 #pragma unroll
   for (int half = kBwdWaves / 2; half >= kRowWaves; half >>= 1) {
-    __syncthreads();
+    lds_barrier();
     if (wave >= half && wave < 2 * half && owner) {
       float* slot = lds + static_cast<size_t>((wave - half) / kRowWaves) * 2 * M;
 #pragma unroll
@@ -436,7 +481,7 @@ __global__ __launch_bounds__(kBwdThreads) void ln_bwd_kernel(
         }
       }
     }
-    __syncthreads();
+    lds_barrier();
     if (wave < half && owner) {
       const float* slot = lds + static_cast<size_t>(wave / kRowWaves) * 2 * M;
 #pragma unroll
@@ -456,13 +501,12 @@ __global__ __launch_bounds__(kBwdThreads) void ln_bwd_kernel(
     }
   }
   if (wave < kRowWaves && owner) {
-    float* slot = partial + static_cast<size_t>(blockIdx.x) * 2 * M;
 #pragma unroll
     for (int c = 0; c < CH; ++c) {
       const int ch = c * LANES + t;
       if (ch < chunks) {
-        store_floats<V>(slot + ch * V, acc_g[c]);
-        store_floats<V>(slot + M + ch * V, acc_b[c]);
+        store_floats<V>(out + ch * V, acc_g[c]);
+        store_floats<V>(out + M + ch * V, acc_b[c]);
       }
     }
   }
@@ -536,7 +580,7 @@ __global__ __launch_bounds__(kFinCols* kFinSlices) void ln_bwd_finalize_kernel(
     for (; p < parts; p += kFinSlices) s += p0[static_cast<size_t>(p) * 2 * M];
   }
   lds[slice][col] = s;
-  __syncthreads();
+  lds_barrier();
   if (slice == 0 && j2 < 2 * M) {
     float tot = 0.0f;
 #pragma unroll
@@ -732,11 +776,14 @@ static BwdPlan bwd_plan(int64_t N, const Shape& sh) {
   return p;
 }
 
-// Dynamic LDS of the backward kernel: the reduction tree's slots, one per kRowWaves waves of
-// the upper half of the workgroup, or the three parameter vectors when they live in LDS.
+// Dynamic LDS of the backward kernel: the column sums' slots (one per kRowWaves waves: all of
+// them when they fit kOneStepLdsBytes, else those of the upper half of the workgroup for the
+// tree), or the three parameter vectors when they live in LDS.
 static size_t bwd_lds_bytes(const Shape& sh, int64_t M, tempo_dtype dt) {
   const int row_waves = sh.lanes > kWave ? sh.lanes / kWave : 1;
-  const int slots = kBwdWaves / 2 / row_waves > 0 ? kBwdWaves / 2 / row_waves : 1;
+  const int all = kBwdWaves / row_waves;
+  const size_t one_step = static_cast<size_t>(all) * 2 * M * sizeof(float);
+  const int slots = one_step <= kOneStepLdsBytes ? all : (all / 2 > 0 ? all / 2 : 1);
   const int vec = dt == TEMPO_F32 ? 4 : 8;
   const bool reg_params = sh.ch * vec <= 24;  // kRegParams of ln_bwd_kernel
   size_t floats = static_cast<size_t>(slots) * 2 * M;

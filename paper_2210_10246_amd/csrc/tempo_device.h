@@ -199,6 +199,16 @@ __device__ __forceinline__ float group_max(float v) {
   return v;
 }
 
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits until the wave's
+// outstanding global loads and stores have completed (s_waitcnt vmcnt(0)): behind a batch of
+// stores that is microseconds, and in a loop it also waits for the rows fetched ahead.  No
+// kernel here passes data between the waves of a workgroup through global memory.
+__device__ __forceinline__ void lds_barrier() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
 // Row reductions for rows owned by LANES consecutive threads of a workgroup.  A row inside
 // one wave: butterflies.  A row spread over LANES/64 waves: butterfly per wave, then one
 // exchange through `slots` (one entry per wave of the workgroup) behind a workgroup barrier, so
@@ -212,7 +222,7 @@ __device__ __forceinline__ float row_reduce(float v, float* slots) {
   } else {
     v = MAX ? group_max<kWave>(v) : group_sum<kWave>(v);
     if ((threadIdx.x & (kWave - 1)) == 0) slots[threadIdx.x / kWave] = v;
-    __syncthreads();
+    lds_barrier();
     constexpr int W = LANES / kWave;
     const int w0 = (threadIdx.x / LANES) * W;
     float r = slots[w0];
@@ -232,7 +242,7 @@ __device__ __forceinline__ void row_sum2(float& a, float& b, float2* slots) {
     a = group_sum<kWave>(a);
     b = group_sum<kWave>(b);
     if ((threadIdx.x & (kWave - 1)) == 0) slots[threadIdx.x / kWave] = make_float2(a, b);
-    __syncthreads();
+    lds_barrier();
     constexpr int W = LANES / kWave;
     const int w0 = (threadIdx.x / LANES) * W;
     float2 r = slots[w0];
