@@ -861,7 +861,9 @@ static BwdLaunch bwd_launch(int64_t N, int64_t M, tempo_dtype dt) {
     b.plan = bwd_plan(N, b.sh);
     b.slots = b.plan.grid;
   } else {
-    b.plan = {1, true, static_cast<int>(N > 4096 ? 4096 : (N < 1 ? 1 : N))};  // one row per workgroup, strided
+    // one row per workgroup, strided; four 256-lane workgroups per compute unit, and a workspace
+    // of at most 1024 slots
+    b.plan = {1, true, static_cast<int>(N > 1024 ? 1024 : (N < 1 ? 1 : N))};
     b.slots = b.plan.grid;
   }
   return b;
