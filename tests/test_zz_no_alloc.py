@@ -59,13 +59,14 @@ def _case(B, N, M, dt, seed, check_oracle):
 @pytest.mark.parametrize("dt", ["f32", "bf16"])
 def test_static_scratch_matches_workspace_entry_point_on_shrinking_calls(B, dt):
     # looping grid (every slot of a 256-workgroup grid), then smaller and smaller problems whose
-    # grids use a prefix of those slots, a row length of the any-M kernel, and one row
-    for i, (N, M) in enumerate([(9000, 1024), (700, 1024), (300, 768), (37, 4096), (65, 100), (1, 8)]):
+    # grids use a prefix of those slots, a row of 8192 columns (register-resident in bfloat16, the
+    # any-M kernel in float32), a row length of the any-M kernel, and one row
+    for i, (N, M) in enumerate([(9000, 1024), (100, 8192), (700, 1024), (300, 768), (37, 4096), (65, 100), (1, 8)]):
         _case(B, N, M, dt, 1000 + i, check_oracle=True)
 
 
 def test_static_scratch_rejects_problems_beyond_the_array(B):
-    N, M = 5000, 4104                     # any-M kernel: min(N, 4096) slots of 8*M bytes > 8 MiB
+    N, M = 5000, 4104                     # any-M kernel: min(N, 1024) slots of 8*M bytes > 8 MiB
     assert B.tempo_layernorm_bwd_workspace_bytes(N, M) > (8 << 20)
     z = torch.zeros(N, M, dtype=torch.float32, device="cuda")
     g = torch.ones(M, dtype=torch.float32, device="cuda")
