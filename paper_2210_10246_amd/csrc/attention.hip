@@ -511,6 +511,154 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_generic_kernel(
   }
 }
 
+// ---- any Sk up to 64 * KMAX: one wave per row, scalar accesses, the row held in registers ---
+// Element j of a row belongs to lane j % 64 (chunk k = j / 64), so every access of a wave is one
+// contiguous run whatever the row's alignment, and the row is read once.  Same arithmetic, in the
+// same order per lane, as the any-length kernels above.
+
+// Keep bits of the chunks of such a row.  One generator call yields the bits of 8 consecutive
+// elements, so instead of one call per element each lane draws one group of a block of 7 chunks
+// (448 elements: at most 57 groups, whatever the block's alignment) and the lanes fetch the byte
+// of their element's group from the lane that drew it.
+constexpr int kChunksPerDraw = 7;
+template <int KMAX>
+struct RowKeep {
+  static constexpr int kBlocks = (KMAX + kChunksPerDraw - 1) / kChunksPerDraw;
+  uint32_t bytes[kBlocks];
+  int64_t e_row;
+  __device__ __forceinline__ void draw(int64_t row_start, int Sk, int lane, const RngArgs& rng) {
+    e_row = row_start;
+#pragma unroll
+    for (int b = 0; b < kBlocks; ++b) {
+      bytes[b] = 0;
+      if (b * kChunksPerDraw * kWave < Sk)  // uniform over the wave
+        bytes[b] = keep_byte(
+            static_cast<uint64_t>((e_row + b * kChunksPerDraw * kWave) >> 3) + lane, rng);
+    }
+  }
+  // Every lane of the wave has to make the call (cross-lane fetch), also lanes beyond the row.
+  __device__ __forceinline__ bool kept(int k, int lane) const {
+    const int b = k / kChunksPerDraw;
+    const int64_t e = e_row + k * kWave + lane;
+    const int src = static_cast<int>((e >> 3) - ((e_row + b * kChunksPerDraw * kWave) >> 3));
+    return (__shfl(bytes[b], src, kWave) >> (e & 7)) & 1u;
+  }
+};
+
+template <typename T, int KMAX>
+__global__ __launch_bounds__(kThreads) void attn_fwd_rows_kernel(
+    const T* scores, const int32_t* __restrict__ key_len, int causal, T* probs,
+    T* __restrict__ out, int64_t rows, int64_t rows_per_batch, int Sq, int Sk, float scale,
+    RngArgs rng) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = threadIdx.x / kWave;
+  constexpr int kWaves = kThreads / kWave;
+  for (int64_t row = static_cast<int64_t>(blockIdx.x) * kWaves + wave; row < rows;
+       row += static_cast<int64_t>(gridDim.x) * kWaves) {
+    const int key_limit = key_len ? min(max(key_len[row / rows_per_batch], 0), Sk) : Sk;
+    const int limit = row_limit(static_cast<int>(row % Sq), key_limit, causal, Sq, Sk);
+    const T* sr = scores + row * Sk;
+    float v[KMAX];
+    float mx = -INFINITY;
+#pragma unroll
+    for (int k = 0; k < KMAX; ++k) {
+      const int j = k * kWave + lane;
+      v[k] = -INFINITY;
+      if (k * kWave < limit) {  // uniform over the wave
+        if (j < limit) v[k] = Store<T>::load1(sr + j);
+        mx = fmaxf(mx, v[k]);
+      }
+    }
+    mx = group_max<kWave>(mx);
+    const float shift = (mx == -INFINITY) ? 0.0f : mx * kLog2e;
+    float sum = 0.0f;
+#pragma unroll
+    for (int k = 0; k < KMAX; ++k) {
+      const int j = k * kWave + lane;
+      float e = 0.0f;
+      if (k * kWave < limit && j < limit) {
+        e = __builtin_amdgcn_exp2f(fmaf(v[k], kLog2e, -shift));
+        sum += e;
+      }
+      v[k] = e;
+    }
+    sum = group_sum<kWave>(sum);
+    const float rinv = (sum > 0.0f) ? 1.0f / sum : 0.0f;
+    RowKeep<KMAX> keep;
+    if (out) keep.draw(row * Sk, Sk, lane, rng);
+#pragma unroll
+    for (int k = 0; k < KMAX; ++k) {
+      if (k * kWave < Sk) {  // uniform over the wave
+        const int j = k * kWave + lane;
+        const float p = (j < limit) ? Store<T>::round(v[k] * rinv) : 0.0f;
+        const bool kb = out ? keep.kept(k, lane) : false;
+        if (j < Sk) {
+          const int64_t e = row * Sk + j;
+          Store<T>::store1(probs + e, p);
+          if (out) Store<T>::store1(out + e, kb ? p * scale : 0.0f);
+        }
+      }
+    }
+  }
+}
+
+template <typename T, MaskSource MASK, int KMAX>
+__global__ __launch_bounds__(kThreads) void attn_bwd_rows_kernel(
+    const T* dout, const T* __restrict__ probs, const uint32_t* __restrict__ keep_bits,
+    T* dscores, T* __restrict__ out_re, int64_t rows, int Sk, float scale, RngArgs rng) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = threadIdx.x / kWave;
+  constexpr int kWaves = kThreads / kWave;
+  for (int64_t row = static_cast<int64_t>(blockIdx.x) * kWaves + wave; row < rows;
+       row += static_cast<int64_t>(gridDim.x) * kWaves) {
+    RowKeep<KMAX> keep;
+    if constexpr (MASK == kMaskRegen) keep.draw(row * Sk, Sk, lane, rng);
+    float dp[KMAX], pr[KMAX];
+    uint32_t kept_bits = 0;  // bit k: element k * 64 + lane is kept
+    float dot = 0.0f;
+#pragma unroll
+    for (int k = 0; k < KMAX; ++k) {
+      dp[k] = pr[k] = 0.0f;
+      if (k * kWave < Sk) {  // uniform over the wave
+        const int j = k * kWave + lane;
+        const int64_t e = row * Sk + j;
+        bool kb = false;
+        if constexpr (MASK == kMaskRegen) {
+          kb = keep.kept(k, lane);
+        } else if (j < Sk) {
+          if constexpr (MASK == kMaskBools) kb = reinterpret_cast<const uint8_t*>(keep_bits)[e] != 0;
+          else kb = (keep_bits[e >> 5] >> (e & 31)) & 1u;
+        }
+        if (j < Sk) {
+          pr[k] = Store<T>::load1(probs + e);
+          dp[k] = kb ? Store<T>::load1(dout + e) * scale : 0.0f;
+          dot = fmaf(dp[k], pr[k], dot);
+          kept_bits |= (kb ? 1u : 0u) << k;
+        }
+      }
+    }
+    dot = group_sum<kWave>(dot);
+#pragma unroll
+    for (int k = 0; k < KMAX; ++k) {
+      const int j = k * kWave + lane;
+      if (k * kWave < Sk && j < Sk) {
+        const int64_t e = row * Sk + j;
+        Store<T>::store1(dscores + e, pr[k] * (dp[k] - dot));
+        if (out_re) Store<T>::store1(out_re + e, ((kept_bits >> k) & 1u) ? pr[k] * scale : 0.0f);
+      }
+    }
+  }
+}
+
+// Chunks of 64 elements a row of Sk elements needs in registers: 4, 16 or 32; 0: too long.
+int row_chunks(int64_t Sk) { return Sk <= 256 ? 4 : (Sk <= 1024 ? 16 : (Sk <= 2048 ? 32 : 0)); }
+template <typename F>
+void with_row_chunks(int kmax, F&& f) {
+  if (kmax == 4) f(std::integral_constant<int, 4>{});
+  else if (kmax == 16) f(std::integral_constant<int, 16>{});
+  else f(std::integral_constant<int, 32>{});
+}
+
 struct Shape {
   int lanes;
   int ch;
@@ -714,7 +862,21 @@ tempo_status launch_attn_fwd(const void* scores, const int32_t* key_len, int cau
     return launch_status();
   }
   const int grid = row_grid(rows, kWave, bpc);
-  if (dt == TEMPO_F32)
+  if (const int kmax = row_chunks(Sk)) {
+    with_row_chunks(kmax, [&](auto km) {
+      constexpr int KM = decltype(km)::value;
+      if (dt == TEMPO_F32)
+        hipLaunchKernelGGL((attn_fwd_rows_kernel<float, KM>), dim3(grid), dim3(kThreads), 0, st,
+                           static_cast<const float*>(scores), key_len, causal,
+                           static_cast<float*>(probs), static_cast<float*>(out), rows,
+                           rows_per_batch, static_cast<int>(Sq), static_cast<int>(Sk), scale, rng);
+      else
+        hipLaunchKernelGGL((attn_fwd_rows_kernel<bf16_t, KM>), dim3(grid), dim3(kThreads), 0, st,
+                           static_cast<const bf16_t*>(scores), key_len, causal,
+                           static_cast<bf16_t*>(probs), static_cast<bf16_t*>(out), rows,
+                           rows_per_batch, static_cast<int>(Sq), static_cast<int>(Sk), scale, rng);
+    });
+  } else if (dt == TEMPO_F32)
     hipLaunchKernelGGL((attn_fwd_generic_kernel<float>), dim3(grid), dim3(kThreads), 0, st,
                        static_cast<const float*>(scores), key_len, causal,
                        static_cast<float*>(probs), static_cast<float*>(out), rows, rows_per_batch,
@@ -766,8 +928,18 @@ static tempo_status attn_bwd_any(const void* dout, const void* probs, const uint
     return launch_status();
   }
   const int grid = row_grid(rows, kWave, bpc);
+  const int kmax = row_chunks(Sk);
   auto go = [&](auto tag, auto m) {
     using T = decltype(tag);
+    if (kmax) {
+      with_row_chunks(kmax, [&](auto km) {
+        hipLaunchKernelGGL((attn_bwd_rows_kernel<T, decltype(m)::value, decltype(km)::value>),
+                           dim3(grid), dim3(kThreads), 0, st, static_cast<const T*>(dout),
+                           static_cast<const T*>(probs), keep_bits, static_cast<T*>(dscores),
+                           static_cast<T*>(out_re), rows, static_cast<int>(Sk), scale, rng);
+      });
+      return;
+    }
     hipLaunchKernelGGL((attn_bwd_generic_kernel<T, decltype(m)::value>), dim3(grid),
                        dim3(kThreads), 0, st, static_cast<const T*>(dout),
                        static_cast<const T*>(probs), keep_bits, static_cast<T*>(dscores),

@@ -401,6 +401,12 @@ ATTN_CASES = [
     (2, 1, 5, 1544, "padding", 0.1),   # long row ending inside a mask word
     (2, 2, 64, 160, "padding", 0.0),   # p = 0: everything kept
     (1, 1, 70, 1, "none", 0.1),
+    # rows of any length held in registers by one wave (4, 16 or 32 chunks of 64 elements), the
+    # keep bits of 448 elements drawn together; and the any-length kernels beyond 2048
+    (1, 1, 70, 449, "none", 0.3),
+    (2, 1, 5, 1001, "causal", 0.1),
+    (1, 2, 3, 1543, "padding", 0.1),
+    (1, 1, 3, 2055, "none", 0.1),
 ]
 
 
