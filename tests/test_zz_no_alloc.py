@@ -76,3 +76,36 @@ def test_static_scratch_rejects_problems_beyond_the_array(B):
     assert e.value.status == 3            # TEMPO_ERR_WORKSPACE
     # zero-size calls need no pointers and no scratch
     assert B.load().tempo_layernorm_bwd_static(None, None, None, None, None, None, None, None, 0, 8, 0, None) == 0
+
+
+def test_static_scratch_under_graph_capture(B):
+    # the callers it is for: captured once (after one ordinary call on this GPU, so that the
+    # array's address is already known), replayed with new inputs, with eager work in between
+    N, M, dt = 3000, 1024, "bf16"
+    rng = np.random.default_rng(77)
+    t = lambda a, d: torch.from_numpy(np.ascontiguousarray(a)).to(TDT[d]).cuda()
+    gd = t(O.round_to_dtype(1 + 0.1 * rng.standard_normal(M), "f32"), "f32")
+    bd = t(O.round_to_dtype(0.1 * rng.standard_normal(M), "f32"), "f32")
+    dyd, yd = t(rng.standard_normal((N, M)), dt), t(rng.standard_normal((N, M)), dt)
+    rd = t(0.5 + rng.random(N), "f32")
+    ws = torch.empty(B.tempo_layernorm_bwd_workspace_bytes(N, M), dtype=torch.uint8, device="cuda")
+    out = lambda: (torch.empty_like(dyd), torch.empty(M, device="cuda"), torch.empty(M, device="cuda"))
+    warm = out()
+    B.tempo_layernorm_bwd_static(dyd, yd, gd, bd, rd, *warm)
+    torch.cuda.synchronize()
+    cap = out()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        B.tempo_layernorm_bwd_static(dyd, yd, gd, bd, rd, *cap)
+    for rep in range(3):
+        dyd.copy_(t(rng.standard_normal((N, M)), dt))
+        yd.copy_(t(rng.standard_normal((N, M)), dt))
+        for o in cap:
+            o.fill_(3.0)
+        torch.cuda.synchronize()
+        g.replay()
+        ref = out()
+        B.tempo_layernorm_bwd(dyd, yd, gd, bd, rd, *ref, ws)     # eager work between replays
+        torch.cuda.synchronize()
+        for a, b in zip(cap, ref):
+            assert torch.equal(a.view(torch.uint8), b.view(torch.uint8)), rep
