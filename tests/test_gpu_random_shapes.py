@@ -38,19 +38,20 @@ def stored(rng, shape, dt, scale=1.0):
 
 def _row_lengths(rng, count, top):
     """Row lengths spread over the whole range, with boundaries of the kernel shapes mixed in."""
-    edges = [8, 16, 24, 32, 64, 96, 128, 192, 256, 264, 384, 512, 520, 768, 1024, 1032, 1536, 2048,
-             2056, 3072, 4096]
+    edges = [8, 16, 24, 32, 64, 96, 128, 192, 256, 264, 384, 448, 512, 520, 768, 896, 1024, 1032,
+             1536, 2048, 2056, 3072, 4096, 5120, 6144, 8192]
     picks = [int(x) for x in rng.integers(1, top, count // 2)]
     picks += [int(e + d) for e, d in zip(rng.choice(edges, count - count // 2),
                                          rng.choice([-8, -1, 0, 0, 1, 8], count - count // 2))]
-    return [min(max(p, 1), top) for p in picks]
+    return [min(max(p, 1), top) for p in picks if p <= top + 8]
 
 
 @pytest.mark.parametrize("dt", ["f32", "bf16"])
 def test_layernorm_random_shapes(B, dt):
     rng = np.random.default_rng(1234)
-    for M in _row_lengths(rng, 36, 4200):
-        N = int(rng.integers(1, 70))
+    for M in _row_lengths(rng, 40, 8300):
+        # mostly a few rows; now and then enough for workgroups that loop
+        N = int(rng.integers(1, 70)) if rng.random() < 0.75 else int(rng.integers(300, 1200))
         x = stored(rng, (N, M), dt) * rng.uniform(0.5, 3.0) + rng.normal()
         x = O.round_to_dtype(x, dt)
         gamma = O.round_to_dtype(1 + 0.1 * rng.standard_normal(M), "f32")
