@@ -545,19 +545,51 @@ struct RowKeep {
   }
 };
 
+// The stored keep bits of such a row: the row's words (at most 2 per lane: 64 * KMAX elements
+// span up to 2 * KMAX + 1 words) are loaded once, one per lane, and fetched across lanes, instead
+// of one load per element.
+template <int KMAX>
+struct RowMaskWords {
+  static constexpr int kRegs = (2 * KMAX + 1 + kWave - 1) / kWave;
+  uint32_t w[kRegs];
+  int64_t e_row;
+  __device__ __forceinline__ void load(const uint32_t* keep_bits, int64_t row_start,
+                                       int64_t total_words, int lane) {
+    e_row = row_start;
+#pragma unroll
+    for (int r = 0; r < kRegs; ++r) {
+      const int64_t i = (e_row >> 5) + r * kWave + lane;
+      w[r] = (i < total_words) ? keep_bits[i] : 0u;
+    }
+  }
+  // Every lane of the wave has to make the call, also lanes beyond the row.
+  __device__ __forceinline__ bool kept(int k, int lane) const {
+    const int64_t e = e_row + k * kWave + lane;
+    const int wi = static_cast<int>((e >> 5) - (e_row >> 5));
+    uint32_t word = __shfl(w[0], wi & (kWave - 1), kWave);
+    if constexpr (kRegs > 1) {
+      const uint32_t hi = __shfl(w[1], wi & (kWave - 1), kWave);
+      word = wi < kWave ? word : hi;
+    }
+    return (word >> (e & 31)) & 1u;
+  }
+};
+
 template <typename T, int KMAX>
 __global__ __launch_bounds__(kThreads) void attn_fwd_rows_kernel(
     const T* scores, const int32_t* __restrict__ key_len, int causal, T* probs,
     T* __restrict__ out, int64_t rows, int64_t rows_per_batch, int Sq, int Sk, float scale,
     RngArgs rng) {
   const int lane = threadIdx.x & (kWave - 1);
-  const int wave = threadIdx.x / kWave;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);  // uniform: row math stays scalar
   constexpr int kWaves = kThreads / kWave;
   for (int64_t row = static_cast<int64_t>(blockIdx.x) * kWaves + wave; row < rows;
        row += static_cast<int64_t>(gridDim.x) * kWaves) {
     const int key_limit = key_len ? min(max(key_len[row / rows_per_batch], 0), Sk) : Sk;
     const int limit = row_limit(static_cast<int>(row % Sq), key_limit, causal, Sq, Sk);
     const T* sr = scores + row * Sk;
+    T* pr = probs + row * Sk;
+    T* orow = out ? out + row * Sk : nullptr;
     float v[KMAX];
     float mx = -INFINITY;
 #pragma unroll
@@ -593,9 +625,8 @@ __global__ __launch_bounds__(kThreads) void attn_fwd_rows_kernel(
         const float p = (j < limit) ? Store<T>::round(v[k] * rinv) : 0.0f;
         const bool kb = out ? keep.kept(k, lane) : false;
         if (j < Sk) {
-          const int64_t e = row * Sk + j;
-          Store<T>::store1(probs + e, p);
-          if (out) Store<T>::store1(out + e, kb ? p * scale : 0.0f);
+          Store<T>::store1(pr + j, p);
+          if (out) Store<T>::store1(orow + j, kb ? p * scale : 0.0f);
         }
       }
     }
@@ -607,12 +638,19 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_rows_kernel(
     const T* dout, const T* __restrict__ probs, const uint32_t* __restrict__ keep_bits,
     T* dscores, T* __restrict__ out_re, int64_t rows, int Sk, float scale, RngArgs rng) {
   const int lane = threadIdx.x & (kWave - 1);
-  const int wave = threadIdx.x / kWave;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);  // uniform: row math stays scalar
   constexpr int kWaves = kThreads / kWave;
   for (int64_t row = static_cast<int64_t>(blockIdx.x) * kWaves + wave; row < rows;
        row += static_cast<int64_t>(gridDim.x) * kWaves) {
+    const int64_t e_row = row * Sk;
     RowKeep<KMAX> keep;
-    if constexpr (MASK == kMaskRegen) keep.draw(row * Sk, Sk, lane, rng);
+    RowMaskWords<KMAX> stored;
+    if constexpr (MASK == kMaskRegen) keep.draw(e_row, Sk, lane, rng);
+    if constexpr (MASK == kMaskWords) stored.load(keep_bits, e_row, (rows * Sk + 31) >> 5, lane);
+    const T* do_row = dout + e_row;
+    const T* p_row = probs + e_row;
+    T* ds_row = dscores + e_row;
+    T* or_row = out_re ? out_re + e_row : nullptr;
     float dp[KMAX], pr[KMAX];
     uint32_t kept_bits = 0;  // bit k: element k * 64 + lane is kept
     float dot = 0.0f;
@@ -621,17 +659,18 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_rows_kernel(
       dp[k] = pr[k] = 0.0f;
       if (k * kWave < Sk) {  // uniform over the wave
         const int j = k * kWave + lane;
-        const int64_t e = row * Sk + j;
+        const int64_t e = e_row + j;
         bool kb = false;
         if constexpr (MASK == kMaskRegen) {
           kb = keep.kept(k, lane);
+        } else if constexpr (MASK == kMaskWords) {
+          kb = stored.kept(k, lane);
         } else if (j < Sk) {
-          if constexpr (MASK == kMaskBools) kb = reinterpret_cast<const uint8_t*>(keep_bits)[e] != 0;
-          else kb = (keep_bits[e >> 5] >> (e & 31)) & 1u;
+          kb = reinterpret_cast<const uint8_t*>(keep_bits)[e] != 0;
         }
         if (j < Sk) {
-          pr[k] = Store<T>::load1(probs + e);
-          dp[k] = kb ? Store<T>::load1(dout + e) * scale : 0.0f;
+          pr[k] = Store<T>::load1(p_row + j);
+          dp[k] = kb ? Store<T>::load1(do_row + j) * scale : 0.0f;
           dot = fmaf(dp[k], pr[k], dot);
           kept_bits |= (kb ? 1u : 0u) << k;
         }
@@ -642,9 +681,8 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_rows_kernel(
     for (int k = 0; k < KMAX; ++k) {
       const int j = k * kWave + lane;
       if (k * kWave < Sk && j < Sk) {
-        const int64_t e = row * Sk + j;
-        Store<T>::store1(dscores + e, pr[k] * (dp[k] - dot));
-        if (out_re) Store<T>::store1(out_re + e, ((kept_bits >> k) & 1u) ? pr[k] * scale : 0.0f);
+        Store<T>::store1(ds_row + j, pr[k] * (dp[k] - dot));
+        if (out_re) Store<T>::store1(or_row + j, ((kept_bits >> k) & 1u) ? pr[k] * scale : 0.0f);
       }
     }
   }
