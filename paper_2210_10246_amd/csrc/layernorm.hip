@@ -19,13 +19,15 @@ namespace {
 constexpr int kFwdThreads = 256;
 constexpr int kBwdWaves = 8;
 constexpr int kBwdThreads = kBwdWaves * kWave;
-// Rows of more than 1024 pieces (4096 float32 or 8192 bfloat16 columns: 4 pieces per lane of
-// 4 waves) take the generic kernels.  Dynamic LDS of the backward: the column sums' slots (all
+// Rows of more than 1024 pieces in bfloat16 (8192 columns: 4 pieces per lane of 4 waves) or 2048
+// pieces in float32 (8192 columns: 6 or 8 pieces per lane of 4 waves, float32 only, whose pieces
+// need half the registers per column) take the generic kernels.  Dynamic LDS of the backward: the column sums' slots (all
 // of them, 64*M bytes while a row fits one wave, when that is at most kOneStepLdsBytes; else
 // half of them for a tree: 32*M bytes while a row fits one wave, 128 KiB at M = 4096; 16*M over
 // two waves; 8*M over four), or gamma, 1/gamma and beta/gamma (12*M bytes, 96 KiB at M = 8192)
 // when a lane's share of them does not fit its registers, whichever is more.
 constexpr int kMaxFastPieces = 1024;
+constexpr int kMaxFastPiecesF32 = 2048;
 // Most LDS the backward's column sums may take in one step (every wave's sums at once); two
 // workgroups of that size still fit a compute unit.
 constexpr size_t kOneStepLdsBytes = 64 * 1024;
@@ -673,11 +675,12 @@ Shape pick_shape(int pieces, bool full_wave) {
 // A row whose pieces per lane on one wave would exceed max_ch is spread over 2 or 4 waves (at
 // most 4 pieces per lane there).
 Shape widen_shape(Shape one, int pieces, int max_ch, int max_lanes) {
-  if (one.lanes == kWave && (one.ch == 0 || one.ch > max_ch)) {
+  if (one.ch == 0 || (one.lanes == kWave && one.ch > max_ch)) {  // no one-wave shape, or too many pieces
     for (int lanes = 2 * kWave; lanes <= max_lanes; lanes *= 2) {
       const int need = (pieces + lanes - 1) / lanes;
       if (need <= max_ch || lanes == max_lanes) {
         if (need <= 4) return {lanes, need};
+        if (lanes == max_lanes && need <= 8) return {lanes, need <= 6 ? 6 : 8};
         break;
       }
     }
@@ -711,6 +714,8 @@ Shape widen_shape(Shape one, int pieces, int max_ch, int max_lanes) {
     case 25602: LAUNCH(256, 2); break;                                                     \
     case 25603: LAUNCH(256, 3); break;                                                     \
     case 25604: LAUNCH(256, 4); break;                                                     \
+    case 25606: LAUNCH(256, 6); break;                                                     \
+    case 25608: LAUNCH(256, 8); break;                                                     \
     default: return TEMPO_ERR_UNSUPPORTED;                                                 \
   }
 
@@ -725,25 +730,29 @@ template <typename T, int L, int C>
 static void ln_fwd_go(int rr, bool loop, int grid, hipStream_t st, const void* x, const float* gamma,
                       const float* beta, void* y, float* rstd, float* mean, int64_t N, int64_t M,
                       float eps) {
-  auto go = [&](auto rows, auto lp) {
-    hipLaunchKernelGGL((ln_fwd_kernel<T, L, C, decltype(rows)::value, decltype(lp)::value>),
-                       dim3(grid), dim3(kFwdThreads), 0, st, static_cast<const T*>(x), gamma, beta,
-                       static_cast<T*>(y), rstd, mean, N, static_cast<int>(M), eps);
-  };
-  using std::integral_constant;
-  if constexpr (C <= 2 && L <= 64) {
-    if (rr == 2) {
-      if (loop) return go(integral_constant<int, 2>{}, std::true_type{});
-      return go(integral_constant<int, 2>{}, std::false_type{});
+  if constexpr (std::is_same<T, bf16_t>::value && C > 4 && L > kWave) {
+    // shapes that exist for float32 only (fast_shape never picks them for bfloat16)
+  } else {
+    auto go = [&](auto rows, auto lp) {
+      hipLaunchKernelGGL((ln_fwd_kernel<T, L, C, decltype(rows)::value, decltype(lp)::value>),
+                         dim3(grid), dim3(kFwdThreads), 0, st, static_cast<const T*>(x), gamma, beta,
+                         static_cast<T*>(y), rstd, mean, N, static_cast<int>(M), eps);
+    };
+    using std::integral_constant;
+    if constexpr (C <= 2 && L <= 64) {
+      if (rr == 2) {
+        if (loop) return go(integral_constant<int, 2>{}, std::true_type{});
+        return go(integral_constant<int, 2>{}, std::false_type{});
+      }
     }
+    if (loop) return go(integral_constant<int, 1>{}, std::true_type{});
+    go(integral_constant<int, 1>{}, std::false_type{});
   }
-  if (loop) return go(integral_constant<int, 1>{}, std::true_type{});
-  go(integral_constant<int, 1>{}, std::false_type{});
 }
 
 static bool fast_shape(int64_t M, tempo_dtype dt, bool backward, Shape* sh) {
   const int vec = dt == TEMPO_F32 ? 4 : 8;
-  if (M % vec != 0 || M / vec > kMaxFastPieces) return false;
+  if (M % vec != 0 || M / vec > (dt == TEMPO_F32 ? kMaxFastPiecesF32 : kMaxFastPieces)) return false;
   const int pieces = static_cast<int>(M / vec);
   *sh = widen_shape(pick_shape(pieces, backward), pieces,
                     tune_get(backward ? kTuneLnBwdMaxPieces : kTuneLnFwdMaxPieces), 256);
@@ -845,51 +854,55 @@ static int ln_bwd_go(const BwdPlan& plan, size_t lds_bytes, hipStream_t st, cons
                      const void* y, const float* gamma, const float* beta, const float* rstd,
                      void* dx, float* workspace, int64_t N, int64_t M) {
   int grid = plan.grid;
-  auto go = [&](auto rows, auto loop) {
-    auto kernel = ln_bwd_kernel<T, L, C, decltype(rows)::value, decltype(loop)::value>;
-    if (decltype(loop)::value) {
-      static std::atomic<int> resident{0};  // workgroups per compute unit, per instantiation
-      int per_cu = resident.load(std::memory_order_relaxed);
-      if (per_cu == 0) {
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, kBwdThreads,
-                                                         lds_bytes) != hipSuccess || per_cu < 1) {
-          (void)hipGetLastError();
-          per_cu = 1;
+  if constexpr (std::is_same<T, bf16_t>::value && C > 4 && L > kWave) {
+    return grid;  // shapes that exist for float32 only
+  } else {
+    auto go = [&](auto rows, auto loop) {
+      auto kernel = ln_bwd_kernel<T, L, C, decltype(rows)::value, decltype(loop)::value>;
+      if (decltype(loop)::value) {
+        static std::atomic<int> resident{0};  // workgroups per compute unit, per instantiation
+        int per_cu = resident.load(std::memory_order_relaxed);
+        if (per_cu == 0) {
+          if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, kBwdThreads,
+                                                           lds_bytes) != hipSuccess || per_cu < 1) {
+            (void)hipGetLastError();
+            per_cu = 1;
+          }
+          resident.store(per_cu, std::memory_order_relaxed);
         }
-        resident.store(per_cu, std::memory_order_relaxed);
+        const int fit = per_cu * compute_units();
+        if (grid > fit) grid = fit;
       }
-      const int fit = per_cu * compute_units();
-      if (grid > fit) grid = fit;
+      hipLaunchKernelGGL(kernel, dim3(grid), dim3(kBwdThreads), lds_bytes, st,
+                         static_cast<const T*>(dy), static_cast<const T*>(y), gamma, beta, rstd,
+                         static_cast<T*>(dx), workspace, N, static_cast<int>(M));
+    };
+    using std::integral_constant;
+    if (plan.loop) {
+      if constexpr (max_rows<L, C>() >= 4) {  // looping holds two batches: half the rows
+        if (plan.r == 2) {
+          go(integral_constant<int, 2>{}, std::true_type{});
+          return grid;
+        }
+      }
+      go(integral_constant<int, 1>{}, std::true_type{});
+      return grid;
     }
-    hipLaunchKernelGGL(kernel, dim3(grid), dim3(kBwdThreads), lds_bytes, st,
-                       static_cast<const T*>(dy), static_cast<const T*>(y), gamma, beta, rstd,
-                       static_cast<T*>(dx), workspace, N, static_cast<int>(M));
-  };
-  using std::integral_constant;
-  if (plan.loop) {
-    if constexpr (max_rows<L, C>() >= 4) {  // looping holds two batches: half the rows
-      if (plan.r == 2) {
-        go(integral_constant<int, 2>{}, std::true_type{});
+    if constexpr (max_rows<L, C>() >= 4) {
+      if (plan.r == 4) {
+        go(integral_constant<int, 4>{}, std::false_type{});
         return grid;
       }
     }
-    go(integral_constant<int, 1>{}, std::true_type{});
+    if constexpr (max_rows<L, C>() >= 2) {
+      if (plan.r >= 2) {
+        go(integral_constant<int, 2>{}, std::false_type{});
+        return grid;
+      }
+    }
+    go(integral_constant<int, 1>{}, std::false_type{});
     return grid;
   }
-  if constexpr (max_rows<L, C>() >= 4) {
-    if (plan.r == 4) {
-      go(integral_constant<int, 4>{}, std::false_type{});
-      return grid;
-    }
-  }
-  if constexpr (max_rows<L, C>() >= 2) {
-    if (plan.r >= 2) {
-      go(integral_constant<int, 2>{}, std::false_type{});
-      return grid;
-    }
-  }
-  go(integral_constant<int, 1>{}, std::false_type{});
-  return grid;
 }
 
 // Everything a backward launch depends on, taken from the knobs once: the workspace check and
