@@ -137,7 +137,7 @@ TEMPO_API tempo_status tempo_layernorm_bwd(const void* dy, const void* y, const 
  *   TEMPO_ERR_WORKSPACE: the problem needs more scratch than the array holds.  With the default
  *   launch shapes every M <= 4096 that is a multiple of 8 (bfloat16) or 4 (float32) fits for any
  *   N; longer rows up to 8192 columns (multiples of 8 in bfloat16, of 4 in float32) fit while
- *   ceil(N / 2) * 8 * M bytes do; other M fit while min(N, 1024) * 8 * M bytes do.
+ *   N * 8 * M bytes do; other M fit while min(N, 1024) * 8 * M bytes do.
  *   TEMPO_ERR_LAUNCH: the array's device address could not be obtained.  It is looked up on the
  *   first call on each GPU: make that call before a stream capture begins.
  * All calls on one GPU share that GPU's array: calls that may run at the same time on one GPU

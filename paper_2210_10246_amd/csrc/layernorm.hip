@@ -716,6 +716,8 @@ Shape widen_shape(Shape one, int pieces, int max_ch, int max_lanes) {
     case 25604: LAUNCH(256, 4); break;                                                     \
     case 25606: LAUNCH(256, 6); break;                                                     \
     case 25608: LAUNCH(256, 8); break;                                                     \
+    case 51202: LAUNCH(512, 2); break;                                                     \
+    case 51204: LAUNCH(512, 4); break;                                                     \
     default: return TEMPO_ERR_UNSUPPORTED;                                                 \
   }
 
@@ -730,8 +732,8 @@ template <typename T, int L, int C>
 static void ln_fwd_go(int rr, bool loop, int grid, hipStream_t st, const void* x, const float* gamma,
                       const float* beta, void* y, float* rstd, float* mean, int64_t N, int64_t M,
                       float eps) {
-  if constexpr (std::is_same<T, bf16_t>::value && C > 4 && L > kWave) {
-    // shapes that exist for float32 only (fast_shape never picks them for bfloat16)
+  if constexpr ((std::is_same<T, bf16_t>::value && C > 4 && L > kWave) || L > kFwdThreads) {
+    // shapes that exist for float32 only, or for the backward only (fast_shape never picks them here)
   } else {
     auto go = [&](auto rows, auto lp) {
       hipLaunchKernelGGL((ln_fwd_kernel<T, L, C, decltype(rows)::value, decltype(lp)::value>),
@@ -756,6 +758,10 @@ static bool fast_shape(int64_t M, tempo_dtype dt, bool backward, Shape* sh) {
   const int pieces = static_cast<int>(M / vec);
   *sh = widen_shape(pick_shape(pieces, backward), pieces,
                     tune_get(backward ? kTuneLnBwdMaxPieces : kTuneLnFwdMaxPieces), 256);
+  // Backward: four waves whose lanes would own more than 24 columns each (parameters in LDS,
+  // read twice per element) give the row to all eight waves, which halves the columns per lane
+  // and keeps the parameters in registers.
+  if (backward && sh->lanes == 256 && sh->ch * vec > 24) *sh = {kBwdThreads, sh->ch / 2};
   return sh->ch != 0;
 }
 
@@ -854,8 +860,9 @@ static int ln_bwd_go(const BwdPlan& plan, size_t lds_bytes, hipStream_t st, cons
                      const void* y, const float* gamma, const float* beta, const float* rstd,
                      void* dx, float* workspace, int64_t N, int64_t M) {
   int grid = plan.grid;
-  if constexpr (std::is_same<T, bf16_t>::value && C > 4 && L > kWave) {
-    return grid;  // shapes that exist for float32 only
+  if constexpr ((std::is_same<T, bf16_t>::value && C > 4 && L > kWave) ||
+                (L == kBwdThreads && C != (std::is_same<T, bf16_t>::value ? 2 : 4))) {
+    return grid;  // shapes that exist for the other dtype only
   } else {
     auto go = [&](auto rows, auto loop) {
       auto kernel = ln_bwd_kernel<T, L, C, decltype(rows)::value, decltype(loop)::value>;
