@@ -23,7 +23,8 @@ extern "C" {
  *   of 512 lanes with half the pieces per lane (65536: never);
  *   key 2, 4, 5: cap on workgroups per compute unit of layernorm_fwd, attn fwd, attn bwd
  *   (rows beyond the cap are walked in a loop);
- *   key 6, 7: rows a lane group of attn fwd / layernorm_fwd fetches at once (1 or 2);
+ *   key 6, 7: rows a lane group of attn fwd / layernorm_fwd fetches at once (1, or 2 and more:
+ *   layernorm_fwd then takes 4 rows of one piece per lane, 2 of two pieces);
  *   key 8, 9, 10, 11: attn fwd / attn bwd / layernorm_fwd / layernorm_bwd: 16-byte pieces per
  *   lane above which a row is spread over 2 or 4 waves instead of one (16 or more: never);
  *   key 15: lanes per workgroup of the float32 gelu / silu kernels (64, 128 or 256, with the

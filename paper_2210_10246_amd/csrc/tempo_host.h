@@ -18,7 +18,7 @@ enum TuneKey {
   kTuneAttnFwdBlocksPerCu = 4,  // cap on workgroups per compute unit
   kTuneAttnBwdBlocksPerCu = 5,
   kTuneAttnFwdRows = 6,         // rows a lane group of attn fwd fetches at once (1 or 2)
-  kTuneLnFwdRows = 7,           // rows a lane group of layernorm_fwd fetches at once (1 or 2)
+  kTuneLnFwdRows = 7,           // layernorm_fwd: 1 = one row per lane group at a time, else 2 or 4 by shape
   kTuneAttnFwdMaxPieces = 8,    // attn fwd: pieces per lane above which a row takes 2-4 waves
   kTuneAttnBwdMaxPieces = 9,    // the same for attn bwd
   kTuneLnFwdMaxPieces = 10,     // the same for layernorm_fwd
