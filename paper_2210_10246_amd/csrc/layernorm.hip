@@ -782,10 +782,19 @@ tempo_status launch_layernorm_fwd(const void* x, const float* gamma, const float
     // workgroups loop); rows of one piece also take one more workgroup per compute unit.
     // Measured on 16384 x 512 and 65536 x 256 bf16: 9-10 % faster than 2 rows.
     const int tuned = tune_get(kTuneLnFwdRows);
-    const int rr = (sh.ch <= 2 && sh.lanes <= kWave && tuned >= 2) ? (sh.ch == 1 ? 4 : 2) : 1;
+    int rr = (sh.ch <= 2 && sh.lanes <= kWave && tuned >= 2) ? (sh.ch == 1 ? 4 : 2) : 1;
     if (rr == 4) cap += compute_units();
-    const int groups = (kFwdThreads / sh.lanes) * rr;
-    const int64_t want = (N + groups - 1) / groups;
+    int groups = (kFwdThreads / sh.lanes) * rr;
+    int64_t want = (N + groups - 1) / groups;
+    // Rows of two pieces whose workgroups would walk five batches of two rows or more: one row
+    // at a time and one more workgroup per compute unit instead (32768 and 65536 rows of 1024
+    // bf16 columns: 5-6 % faster; up to 16384 rows the two-row form is as fast or faster).
+    if (rr == 2 && want >= 5 * cap) {
+      rr = 1;
+      cap += compute_units();
+      groups = kFwdThreads / sh.lanes;
+      want = (N + groups - 1) / groups;
+    }
     const bool loop = want > cap;
     const int grid = static_cast<int>(loop ? cap : want);
 #define TEMPO_LAUNCH(L, C)                                                                   \
