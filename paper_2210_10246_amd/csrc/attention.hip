@@ -425,9 +425,22 @@ __global__ __launch_bounds__(THREADS) void attn_bwd_kernel(
 
 // ---- any Sk: one wave per row, scalar accesses, the row re-read from cache per pass --------
 
-__device__ __forceinline__ bool keep_bit_of(int64_t e, const RngArgs& a) {
-  return (keep_byte(static_cast<uint64_t>(e) >> 3, a) >> (e & 7)) & 1u;
-}
+// Keep bits of a block of up to 448 consecutive elements (7 chunks of 64: at most 57 groups of 8
+// whatever the block's alignment): each lane draws one group, and the lanes fetch the byte of
+// their element's group from the lane that drew it, one generator call per 8 elements instead
+// of one per element.  Every lane of the wave has to make both calls.
+constexpr int kDrawBlock = 7 * kWave;
+struct KeepBlock {
+  uint32_t byte;
+  int64_t group0;
+  __device__ __forceinline__ void draw(int64_t e_block, int lane, const RngArgs& rng) {
+    group0 = e_block >> 3;
+    byte = keep_byte(static_cast<uint64_t>(group0) + lane, rng);
+  }
+  __device__ __forceinline__ bool kept(int64_t e) const {
+    return (__shfl(byte, static_cast<int>((e >> 3) - group0), kWave) >> (e & 7)) & 1u;
+  }
+};
 
 template <typename T>
 __global__ __launch_bounds__(kThreads) void attn_fwd_generic_kernel(
@@ -451,14 +464,22 @@ __global__ __launch_bounds__(kThreads) void attn_fwd_generic_kernel(
       sum += __builtin_amdgcn_exp2f(fmaf(Store<T>::load1(sr + j), kLog2e, -shift));
     sum = group_sum<kWave>(sum);
     const float rinv = (sum > 0.0f) ? 1.0f / sum : 0.0f;
-    for (int j = lane; j < Sk; j += kWave) {
-      float p = 0.0f;
-      if (j < limit)
-        p = Store<T>::round(__builtin_amdgcn_exp2f(fmaf(Store<T>::load1(sr + j), kLog2e, -shift)) *
-                            rinv);
-      const int64_t e = row * Sk + j;
-      Store<T>::store1(probs + e, p);
-      if (out) Store<T>::store1(out + e, keep_bit_of(e, rng) ? p * scale : 0.0f);
+    for (int b0 = 0; b0 < Sk; b0 += kDrawBlock) {  // uniform over the wave
+      KeepBlock keep;
+      if (out) keep.draw(row * Sk + b0, lane, rng);
+      for (int c0 = b0; c0 < min(b0 + kDrawBlock, Sk); c0 += kWave) {
+        const int j = c0 + lane;
+        const int64_t e = row * Sk + j;
+        const bool kb = out ? keep.kept(e) : false;
+        if (j < Sk) {
+          float p = 0.0f;
+          if (j < limit)
+            p = Store<T>::round(
+                __builtin_amdgcn_exp2f(fmaf(Store<T>::load1(sr + j), kLog2e, -shift)) * rinv);
+          Store<T>::store1(probs + e, p);
+          if (out) Store<T>::store1(out + e, kb ? p * scale : 0.0f);
+        }
+      }
     }
   }
 }
@@ -482,9 +503,8 @@ template <typename T, MaskSource MASK>
 __global__ __launch_bounds__(kThreads) void attn_bwd_generic_kernel(
     const T* dout, const T* __restrict__ probs, const uint32_t* __restrict__ keep_bits,
     T* dscores, T* __restrict__ out_re, int64_t rows, int Sk, float scale, RngArgs rng) {
-  auto kept = [&](int64_t e) -> bool {
-    if constexpr (MASK == kMaskRegen) return keep_bit_of(e, rng);
-    else if constexpr (MASK == kMaskBools) return reinterpret_cast<const uint8_t*>(keep_bits)[e] != 0;
+  auto stored = [&](int64_t e) -> bool {
+    if constexpr (MASK == kMaskBools) return reinterpret_cast<const uint8_t*>(keep_bits)[e] != 0;
     else return (keep_bits[e >> 5] >> (e & 31)) & 1u;
   };
   const int lane = threadIdx.x & (kWave - 1);
@@ -493,20 +513,38 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_generic_kernel(
   for (int64_t row = static_cast<int64_t>(blockIdx.x) * kWaves + wave; row < rows;
        row += static_cast<int64_t>(gridDim.x) * kWaves) {
     float dot = 0.0f;
-    for (int j = lane; j < Sk; j += kWave) {
-      const int64_t e = row * Sk + j;
-      const bool k = kept(e);
-      const float dp = k ? Store<T>::load1(dout + e) * scale : 0.0f;
-      dot = fmaf(dp, Store<T>::load1(probs + e), dot);
+    for (int b0 = 0; b0 < Sk; b0 += kDrawBlock) {  // uniform over the wave
+      KeepBlock keep;
+      if constexpr (MASK == kMaskRegen) keep.draw(row * Sk + b0, lane, rng);
+      for (int c0 = b0; c0 < min(b0 + kDrawBlock, Sk); c0 += kWave) {
+        const int j = c0 + lane;
+        const int64_t e = row * Sk + j;
+        bool k = false;
+        if constexpr (MASK == kMaskRegen) k = keep.kept(e);
+        else if (j < Sk) k = stored(e);
+        if (j < Sk) {
+          const float dp = k ? Store<T>::load1(dout + e) * scale : 0.0f;
+          dot = fmaf(dp, Store<T>::load1(probs + e), dot);
+        }
+      }
     }
     dot = group_sum<kWave>(dot);
-    for (int j = lane; j < Sk; j += kWave) {
-      const int64_t e = row * Sk + j;
-      const bool k = kept(e);
-      const float p = Store<T>::load1(probs + e);
-      const float dp = k ? Store<T>::load1(dout + e) * scale : 0.0f;
-      Store<T>::store1(dscores + e, p * (dp - dot));
-      if (out_re) Store<T>::store1(out_re + e, k ? p * scale : 0.0f);
+    for (int b0 = 0; b0 < Sk; b0 += kDrawBlock) {
+      KeepBlock keep;
+      if constexpr (MASK == kMaskRegen) keep.draw(row * Sk + b0, lane, rng);
+      for (int c0 = b0; c0 < min(b0 + kDrawBlock, Sk); c0 += kWave) {
+        const int j = c0 + lane;
+        const int64_t e = row * Sk + j;
+        bool k = false;
+        if constexpr (MASK == kMaskRegen) k = keep.kept(e);
+        else if (j < Sk) k = stored(e);
+        if (j < Sk) {
+          const float p = Store<T>::load1(probs + e);
+          const float dp = k ? Store<T>::load1(dout + e) * scale : 0.0f;
+          Store<T>::store1(dscores + e, p * (dp - dot));
+          if (out_re) Store<T>::store1(out_re + e, k ? p * scale : 0.0f);
+        }
+      }
     }
   }
 }
