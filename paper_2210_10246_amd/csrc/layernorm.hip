@@ -516,8 +516,10 @@ __global__ __launch_bounds__(kBwdThreads) void ln_bwd_kernel(
 
 // Any M: one workgroup per row for dx; per-workgroup column partials are accumulated by
 // walking rows blockIdx.x, blockIdx.x + gridDim.x, ... with thread j owning columns j, j+256...
-// directly in the partial slot (private to the workgroup).
-template <typename T>
+// KC > 0: rows of at most 256 * KC columns; the thread's column sums and the gamma and beta of
+// its columns live in registers and the partial slot is written once at the end.  KC == 0: any
+// length; the sums are kept in the partial slot itself (private to the workgroup).
+template <typename T, int KC>
 __global__ __launch_bounds__(256) void ln_bwd_generic_kernel(
     const T* dy, const T* __restrict__ y, const float* __restrict__ gamma,
     const float* __restrict__ beta, const float* __restrict__ rstd, T* dx,
@@ -526,31 +528,81 @@ __global__ __launch_bounds__(256) void ln_bwd_generic_kernel(
   const float inv_m = 1.0f / static_cast<float>(M);
   float* pg = partial + static_cast<size_t>(blockIdx.x) * 2 * M;
   float* pb = pg + M;
-  for (int64_t j = threadIdx.x; j < M; j += 256) {
-    pg[j] = 0.0f;
-    pb[j] = 0.0f;
-  }
-  for (int64_t row = blockIdx.x; row < N; row += gridDim.x) {
-    const T* dyr = dy + row * M;
-    const T* yr = y + row * M;
-    T* dxr = dx + row * M;
-    float c1 = 0.0f, c2 = 0.0f;
-    for (int64_t j = threadIdx.x; j < M; j += 256) {
-      const float d = Store<T>::load1(dyr + j);
-      const float h = (Store<T>::load1(yr + j) - beta[j]) / gamma[j];
-      const float q = d * gamma[j];
-      c1 = fmaf(q, h, c1);
-      c2 += q;
-      pg[j] = fmaf(d, h, pg[j]);
-      pb[j] += d;
+  if constexpr (KC > 0) {
+    float ag[KC], ab[KC], ga[KC], be[KC];
+#pragma unroll
+    for (int k = 0; k < KC; ++k) {
+      const int64_t j = k * 256 + threadIdx.x;
+      ag[k] = ab[k] = 0.0f;
+      ga[k] = j < M ? gamma[j] : 1.0f;
+      be[k] = j < M ? beta[j] : 0.0f;
     }
-    c1 = block_sum_256(c1, lds) * inv_m;
-    c2 = block_sum_256(c2, lds) * inv_m;
-    const float rs = rstd[row];
+    for (int64_t row = blockIdx.x; row < N; row += gridDim.x) {
+      const T* dyr = dy + row * M;
+      const T* yr = y + row * M;
+      T* dxr = dx + row * M;
+      float c1 = 0.0f, c2 = 0.0f;
+#pragma unroll
+      for (int k = 0; k < KC; ++k) {
+        const int64_t j = k * 256 + threadIdx.x;
+        if (j < M) {
+          const float d = Store<T>::load1(dyr + j);
+          const float h = (Store<T>::load1(yr + j) - be[k]) / ga[k];
+          const float q = d * ga[k];
+          c1 = fmaf(q, h, c1);
+          c2 += q;
+          ag[k] = fmaf(d, h, ag[k]);
+          ab[k] += d;
+        }
+      }
+      c1 = block_sum_256(c1, lds) * inv_m;
+      c2 = block_sum_256(c2, lds) * inv_m;
+      const float rs = rstd[row];
+#pragma unroll
+      for (int k = 0; k < KC; ++k) {
+        const int64_t j = k * 256 + threadIdx.x;
+        if (j < M) {
+          const float d = Store<T>::load1(dyr + j);
+          const float h = (Store<T>::load1(yr + j) - be[k]) / ga[k];
+          Store<T>::store1(dxr + j, rs * (d * ga[k] - fmaf(h, c1, c2)));
+        }
+      }
+    }
+#pragma unroll
+    for (int k = 0; k < KC; ++k) {
+      const int64_t j = k * 256 + threadIdx.x;
+      if (j < M) {
+        pg[j] = ag[k];
+        pb[j] = ab[k];
+      }
+    }
+  } else {
     for (int64_t j = threadIdx.x; j < M; j += 256) {
-      const float d = Store<T>::load1(dyr + j);
-      const float h = (Store<T>::load1(yr + j) - beta[j]) / gamma[j];
-      Store<T>::store1(dxr + j, rs * (d * gamma[j] - fmaf(h, c1, c2)));
+      pg[j] = 0.0f;
+      pb[j] = 0.0f;
+    }
+    for (int64_t row = blockIdx.x; row < N; row += gridDim.x) {
+      const T* dyr = dy + row * M;
+      const T* yr = y + row * M;
+      T* dxr = dx + row * M;
+      float c1 = 0.0f, c2 = 0.0f;
+      for (int64_t j = threadIdx.x; j < M; j += 256) {
+        const float d = Store<T>::load1(dyr + j);
+        const float h = (Store<T>::load1(yr + j) - beta[j]) / gamma[j];
+        const float q = d * gamma[j];
+        c1 = fmaf(q, h, c1);
+        c2 += q;
+        pg[j] = fmaf(d, h, pg[j]);
+        pb[j] += d;
+      }
+      c1 = block_sum_256(c1, lds) * inv_m;
+      c2 = block_sum_256(c2, lds) * inv_m;
+      const float rs = rstd[row];
+      for (int64_t j = threadIdx.x; j < M; j += 256) {
+        const float d = Store<T>::load1(dyr + j);
+        const float h = (Store<T>::load1(yr + j) - beta[j]) / gamma[j];
+        Store<T>::store1(dxr + j, rs * (d * gamma[j] - fmaf(h, c1, c2)));
+      }
     }
   }
 }
@@ -980,14 +1032,19 @@ tempo_status launch_layernorm_bwd(const void* dy, const void* y, const float* ga
     TEMPO_LN_DISPATCH(TEMPO_LAUNCH)
 #undef TEMPO_LAUNCH
   } else {
-    if (dt == TEMPO_F32)
-      hipLaunchKernelGGL((ln_bwd_generic_kernel<float>), dim3(grid), dim3(256), 0, st,
-                         static_cast<const float*>(dy), static_cast<const float*>(y), gamma, beta,
-                         rstd, static_cast<float*>(dx), workspace, N, M);
-    else
-      hipLaunchKernelGGL((ln_bwd_generic_kernel<bf16_t>), dim3(grid), dim3(256), 0, st,
-                         static_cast<const bf16_t*>(dy), static_cast<const bf16_t*>(y), gamma,
-                         beta, rstd, static_cast<bf16_t*>(dx), workspace, N, M);
+    auto go = [&](auto tag, auto kc) {
+      using T = decltype(tag);
+      hipLaunchKernelGGL((ln_bwd_generic_kernel<T, decltype(kc)::value>), dim3(grid), dim3(256), 0,
+                         st, static_cast<const T*>(dy), static_cast<const T*>(y), gamma, beta, rstd,
+                         static_cast<T*>(dx), workspace, N, M);
+    };
+    auto by_length = [&](auto tag) {  // columns per thread held in registers: 8, 20, or none
+      if (M <= 256 * 8) go(tag, std::integral_constant<int, 8>{});
+      else if (M <= 256 * 20) go(tag, std::integral_constant<int, 20>{});
+      else go(tag, std::integral_constant<int, 0>{});
+    };
+    if (dt == TEMPO_F32) by_length(float{});
+    else by_length(bf16_t{});
   }
   if (hipGetLastError() != hipSuccess) return TEMPO_ERR_LAUNCH;
   const int fgrid = static_cast<int>((2 * M + kFinCols - 1) / kFinCols);

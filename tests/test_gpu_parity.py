@@ -211,7 +211,9 @@ LN_SHAPES = [(256, 768), (5, 1024), (37, 768), (3, 8), (9, 64), (7, 100), (4, 40
              (2, 4104), (1, 1), (6, 1536), (300, 1024), (3, 3072), (1030, 256),
              # beyond 4096 columns: register-resident up to 8192 (float32 with 6 or 8 pieces per
              # lane), the any-shape kernels beyond and for rows that are not whole pieces
-             (5, 8192), (70, 6144), (300, 5120), (2, 8200), (3, 8190), (600, 7168)]
+             (5, 8192), (70, 6144), (300, 5120), (2, 8200), (3, 8190), (600, 7168),
+             # any-shape backward: column sums in registers (up to 2048 and up to 5120 columns) / in memory
+             (1500, 1001), (2000, 4100), (3, 9300)]
 
 
 @pytest.mark.parametrize("eps", [1e-12, 1e-5])
