@@ -164,8 +164,9 @@ __device__ __forceinline__ float block_sum_256(float v, float* lds) {
   return (lds[0] + lds[1]) + (lds[2] + lds[3]);
 }
 
-// Any M: one workgroup per row, scalar accesses, x re-read from cache for each pass.
-template <typename T>
+// Any M: one workgroup per row, scalar accesses.  KC > 0: rows of at most 256 * KC columns, held in
+// registers and read once.  KC == 0: any length, x re-read from cache for each pass.
+template <typename T, int KC>
 __global__ __launch_bounds__(256) void ln_fwd_generic_kernel(
     const T* x, const float* __restrict__ gamma, const float* __restrict__ beta, T* y,
     float* __restrict__ rstd_out, float* __restrict__ mean_out, int64_t N, int64_t M, float eps) {
@@ -174,19 +175,48 @@ __global__ __launch_bounds__(256) void ln_fwd_generic_kernel(
   for (int64_t row = blockIdx.x; row < N; row += gridDim.x) {
     const T* xr = x + row * M;
     T* yr = y + row * M;
-    float s = 0.0f;
-    for (int64_t j = threadIdx.x; j < M; j += 256) s += Store<T>::load1(xr + j);
-    const float mu = block_sum_256(s, lds) / m_f;
-    float q = 0.0f;
-    for (int64_t j = threadIdx.x; j < M; j += 256) {
-      const float d = Store<T>::load1(xr + j) - mu;
-      q += d * d;
-    }
-    const float var = block_sum_256(q, lds) / m_f;
-    const float rs = 1.0f / sqrtf(var + eps);
-    for (int64_t j = threadIdx.x; j < M; j += 256) {
-      const float d = Store<T>::load1(xr + j) - mu;
-      Store<T>::store1(yr + j, fmaf(d * rs, gamma[j], beta[j]));
+    float mu, rs;
+    if constexpr (KC > 0) {
+      // rows of at most 256 * KC columns: read once, thread t holds columns t, t + 256, ...
+      float v[KC];
+      float s = 0.0f;
+#pragma unroll
+      for (int k = 0; k < KC; ++k) {
+        const int64_t j = k * 256 + threadIdx.x;
+        v[k] = j < M ? Store<T>::load1(xr + j) : 0.0f;
+        s += v[k];
+      }
+      mu = block_sum_256(s, lds) / m_f;
+      float q = 0.0f;
+#pragma unroll
+      for (int k = 0; k < KC; ++k) {
+        const int64_t j = k * 256 + threadIdx.x;
+        const float d = v[k] - mu;
+        v[k] = d;
+        q += j < M ? d * d : 0.0f;
+      }
+      const float var = block_sum_256(q, lds) / m_f;
+      rs = 1.0f / sqrtf(var + eps);
+#pragma unroll
+      for (int k = 0; k < KC; ++k) {
+        const int64_t j = k * 256 + threadIdx.x;
+        if (j < M) Store<T>::store1(yr + j, fmaf(v[k] * rs, gamma[j], beta[j]));
+      }
+    } else {
+      float s = 0.0f;
+      for (int64_t j = threadIdx.x; j < M; j += 256) s += Store<T>::load1(xr + j);
+      mu = block_sum_256(s, lds) / m_f;
+      float q = 0.0f;
+      for (int64_t j = threadIdx.x; j < M; j += 256) {
+        const float d = Store<T>::load1(xr + j) - mu;
+        q += d * d;
+      }
+      const float var = block_sum_256(q, lds) / m_f;
+      rs = 1.0f / sqrtf(var + eps);
+      for (int64_t j = threadIdx.x; j < M; j += 256) {
+        const float d = Store<T>::load1(xr + j) - mu;
+        Store<T>::store1(yr + j, fmaf(d * rs, gamma[j], beta[j]));
+      }
     }
     if (threadIdx.x == 0) {
       rstd_out[row] = rs;
@@ -857,15 +887,22 @@ tempo_status launch_layernorm_fwd(const void* x, const float* gamma, const float
     TEMPO_LN_DISPATCH(TEMPO_LAUNCH)
 #undef TEMPO_LAUNCH
   } else {
-    const int grid = static_cast<int>(N < cap ? N : cap);
-    if (dt == TEMPO_F32)
-      hipLaunchKernelGGL((ln_fwd_generic_kernel<float>), dim3(grid), dim3(256), 0, st,
-                         static_cast<const float*>(x), gamma, beta, static_cast<float*>(y), rstd,
-                         mean, N, M, eps);
-    else
-      hipLaunchKernelGGL((ln_fwd_generic_kernel<bf16_t>), dim3(grid), dim3(256), 0, st,
-                         static_cast<const bf16_t*>(x), gamma, beta, static_cast<bf16_t*>(y),
-                         rstd, mean, N, M, eps);
+    // one row per workgroup at a time: as many workgroups as a compute unit holds (8 of 256 lanes)
+    const int64_t most = static_cast<int64_t>(compute_units()) * 8;
+    const int grid = static_cast<int>(N < most ? N : most);
+    auto go = [&](auto tag, auto kc) {
+      using T = decltype(tag);
+      hipLaunchKernelGGL((ln_fwd_generic_kernel<T, decltype(kc)::value>), dim3(grid), dim3(256), 0,
+                         st, static_cast<const T*>(x), gamma, beta, static_cast<T*>(y), rstd, mean, N,
+                         M, eps);
+    };
+    auto by_length = [&](auto tag) {  // columns per thread held in registers: 8, 20, or none
+      if (M <= 256 * 8) go(tag, std::integral_constant<int, 8>{});
+      else if (M <= 256 * 20) go(tag, std::integral_constant<int, 20>{});
+      else go(tag, std::integral_constant<int, 0>{});
+    };
+    if (dt == TEMPO_F32) by_length(float{});
+    else by_length(bf16_t{});
   }
   return launch_status();
 }
